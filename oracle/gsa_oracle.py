@@ -1,0 +1,238 @@
+"""ctypes front end of the fp64 CPU oracle (``gsa_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()``
+and by ``bench.py``'s ``cpu_baseline`` leg.  The product package never imports
+this module, and this module never imports the product package.
+
+Every function takes numpy arrays; q, k, v and gate logits are float32 arrays of
+shape [n_tok, heads, d] holding the exact values the device path receives (bf16
+inputs widened exactly).  All arithmetic happens in double inside the C file.
+The steps follow Sec. 3.2 of the paper (eqs. 2-8) in its own order; see the
+header of ``gsa_oracle.c`` for the conventions and for what pins each step.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gsa_oracle.c")
+_LIB = os.path.join(_HERE, "libgsa_oracle.so")
+
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_i64 = ctypes.c_int64
+_int = ctypes.c_int
+_dbl = ctypes.c_double
+
+
+def build(force: bool = False) -> str:
+    """Compile gsa_oracle.c with gcc into libgsa_oracle.so next to it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-fno-fast-math",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.gsa_oracle_threads.restype = _int
+        lib.gsa_oracle_pool.argtypes = [_f32p, _i64, _int, _int, _int, _f64p]
+        lib.gsa_oracle_scores.argtypes = [_f64p, _f64p, _i64, _int, _int, _i64p, _i64, _f64p]
+        lib.gsa_oracle_compressed_attn.argtypes = [_f64p, _f64p, _i64, _int, _int, _i64, _dbl, _f64p]
+        lib.gsa_oracle_topk.argtypes = [_f64p, _i64, _int, _i64, _int, _i32p]
+        lib.gsa_oracle_select_attn.argtypes = [_f32p, _f32p, _f32p, _i64, _int, _int, _int, _i64p,
+                                               _i64, _i32p, _int, _dbl, _f64p, _f64p]
+        lib.gsa_oracle_merge.argtypes = [_f64p, _f64p, _f32p, _i64, _int, _int, _int, _i64p, _i64,
+                                         _f64p]
+        lib.gsa_oracle_dense_attn.argtypes = [_f32p, _f32p, _f32p, _i64, _int, _int, _i64p, _i64,
+                                              _dbl, _f64p, _f64p]
+        for name in ("gsa_oracle_pool", "gsa_oracle_scores", "gsa_oracle_compressed_attn",
+                     "gsa_oracle_topk", "gsa_oracle_select_attn", "gsa_oracle_merge",
+                     "gsa_oracle_dense_attn"):
+            getattr(lib, name).restype = None
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    """Number of OpenMP threads the oracle will use."""
+    return int(_load().gsa_oracle_threads())
+
+
+def _f32(a, shape=None):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if shape is not None:
+        assert a.shape == tuple(shape), (a.shape, shape)
+    return a
+
+
+def _ptr(a, typ):
+    return a.ctypes.data_as(typ)
+
+
+def n_blocks(n_tok: int, block: int) -> int:
+    return (n_tok + block - 1) // block
+
+
+def _rows(rows, n_blk):
+    if rows is None:
+        rows = np.arange(n_blk, dtype=np.int64)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    assert rows.ndim == 1 and (rows.size == 0 or (rows.min() >= 0 and rows.max() < n_blk))
+    return rows
+
+
+def pool(x, block: int) -> np.ndarray:
+    """Block means of x [n_tok, heads, d] -> float64 [heads, n_blk, d]."""
+    x = _f32(x)
+    n_tok, heads, d = x.shape
+    out = np.empty((heads, n_blocks(n_tok, block), d), dtype=np.float64)
+    _load().gsa_oracle_pool(_ptr(x, _f32p), n_tok, heads, d, block, _ptr(out, _f64p))
+    return out
+
+
+def scores(qc, kc, rows=None) -> np.ndarray:
+    """Eq. 4, S_guide rows for the query blocks `rows` -> [heads, n_rows, n_blk]."""
+    qc = np.ascontiguousarray(qc, dtype=np.float64)
+    kc = np.ascontiguousarray(kc, dtype=np.float64)
+    heads, n_blk, d = qc.shape
+    assert kc.shape == qc.shape
+    rows = _rows(rows, n_blk)
+    out = np.empty((heads, rows.size, n_blk), dtype=np.float64)
+    _load().gsa_oracle_scores(_ptr(qc, _f64p), _ptr(kc, _f64p), n_blk, heads, d,
+                              _ptr(rows, _i64p), rows.size, _ptr(out, _f64p))
+    return out
+
+
+def compressed_attn(s, vc, scale: float) -> np.ndarray:
+    """Eq. 3 on precomputed score rows s [heads, n_rows, n_blk] -> [heads, n_rows, d]."""
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    vc = np.ascontiguousarray(vc, dtype=np.float64)
+    heads, n_rows, n_blk = s.shape
+    assert vc.shape[:2] == (heads, n_blk)
+    d = vc.shape[2]
+    out = np.empty((heads, n_rows, d), dtype=np.float64)
+    _load().gsa_oracle_compressed_attn(_ptr(s, _f64p), _ptr(vc, _f64p), n_blk, heads, d, n_rows,
+                                       float(scale), _ptr(out, _f64p))
+    return out
+
+
+def topk(s, k: int) -> np.ndarray:
+    """TopKSelect per row of s [heads, n_rows, n_blk] -> int32 [heads, n_rows, k], ascending."""
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    heads, n_rows, n_blk = s.shape
+    assert 1 <= k <= n_blk
+    out = np.empty((heads, n_rows, k), dtype=np.int32)
+    _load().gsa_oracle_topk(_ptr(s, _f64p), n_blk, heads, n_rows, k, _ptr(out, _i32p))
+    return out
+
+
+def select_attn(q, k, v, block: int, idx, scale: float, rows=None):
+    """Eq. 6 with a given index set idx [heads, n_rows, kk].
+
+    Returns (o_sel [n_rows, block, heads, d], lse [heads, n_rows, block])."""
+    q = _f32(q)
+    k = _f32(k, q.shape)
+    v = _f32(v, q.shape)
+    n_tok, heads, d = q.shape
+    n_blk = n_blocks(n_tok, block)
+    rows = _rows(rows, n_blk)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    assert idx.shape[:2] == (heads, rows.size)
+    kk = idx.shape[2]
+    assert idx.size == 0 or (idx.min() >= 0 and idx.max() < n_blk)
+    o = np.empty((rows.size, block, heads, d), dtype=np.float64)
+    lse = np.empty((heads, rows.size, block), dtype=np.float64)
+    _load().gsa_oracle_select_attn(_ptr(q, _f32p), _ptr(k, _f32p), _ptr(v, _f32p), n_tok, heads, d,
+                                   block, _ptr(rows, _i64p), rows.size, _ptr(idx, _i32p), kk,
+                                   float(scale), _ptr(o, _f64p), _ptr(lse, _f64p))
+    return o, lse
+
+
+def merge(oc, o_sel, gate, n_tok: int, block: int, rows=None) -> np.ndarray:
+    """Eqs. 5, 7, 8 -> out [n_rows, block, heads, d]; gate None means g = 1/2."""
+    oc = np.ascontiguousarray(oc, dtype=np.float64)
+    o_sel = np.ascontiguousarray(o_sel, dtype=np.float64)
+    heads, n_rows, d = oc.shape
+    assert o_sel.shape == (n_rows, block, heads, d)
+    rows = _rows(rows, n_blocks(n_tok, block))
+    assert rows.size == n_rows
+    gp = None
+    if gate is not None:
+        gate = _f32(gate, (n_tok, heads, d))
+        gp = _ptr(gate, _f32p)
+    out = np.empty_like(o_sel)
+    _load().gsa_oracle_merge(_ptr(oc, _f64p), _ptr(o_sel, _f64p), gp, n_tok, heads, d, block,
+                             _ptr(rows, _i64p), n_rows, _ptr(out, _f64p))
+    return out
+
+
+def dense_attn(q, k, v, scale: float, q_tok=None, want_lse: bool = False):
+    """Plain softmax attention (eq. 2 form) of the query tokens q_tok over all keys.
+
+    Returns out [n_q, heads, d] (and lse [heads, n_q] if want_lse)."""
+    q = _f32(q)
+    k = _f32(k, q.shape)
+    v = _f32(v, q.shape)
+    n_tok, heads, d = q.shape
+    if q_tok is None:
+        q_tok = np.arange(n_tok, dtype=np.int64)
+    q_tok = np.ascontiguousarray(q_tok, dtype=np.int64)
+    out = np.empty((q_tok.size, heads, d), dtype=np.float64)
+    lse = np.empty((heads, q_tok.size), dtype=np.float64) if want_lse else None
+    _load().gsa_oracle_dense_attn(_ptr(q, _f32p), _ptr(k, _f32p), _ptr(v, _f32p), n_tok, heads, d,
+                                  _ptr(q_tok, _i64p), q_tok.size, float(scale), _ptr(out, _f64p),
+                                  _ptr(lse, _f64p) if want_lse else None)
+    return (out, lse) if want_lse else out
+
+
+def gsa_forward(q, k, v, block: int, topk_blocks: int, gate=None, scale=None, rows=None,
+                idx_override=None) -> dict:
+    """The whole GSA path of Sec. 3.2 for the query blocks `rows` (all if None).
+
+    Steps, in the paper's order: pool (compression branch), S_guide (eq. 4),
+    compressed attention (eq. 3), TopKSelect, selection attention (eq. 6),
+    upsample + gated merge (eqs. 5, 7, 8).  `idx_override` replaces the TopK
+    result for the selection step (used to score a valid alternative resolution
+    of a near-tie).  Returns every intermediate."""
+    q = _f32(q)
+    n_tok, heads, d = q.shape
+    n_blk = n_blocks(n_tok, block)
+    kk = min(int(topk_blocks), n_blk)
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(d)
+    rows = _rows(rows, n_blk)
+    qc, kc, vc = pool(q, block), pool(k, block), pool(v, block)
+    s = scores(qc, kc, rows)
+    oc = compressed_attn(s, vc, scale)
+    idx = topk(s, kk)
+    use_idx = idx if idx_override is None else np.ascontiguousarray(idx_override, dtype=np.int32)
+    o_sel, lse = select_attn(q, k, v, block, use_idx, scale, rows)
+    out = merge(oc, o_sel, gate, n_tok, block, rows)
+    return {"qc": qc, "kc": kc, "vc": vc, "s": s, "o_comp": oc, "idx": idx, "o_sel": o_sel,
+            "lse": lse, "out": out, "rows": rows, "k": kk, "scale": scale}
+
+
+def rows_to_tokens(x_rows, rows, n_tok: int, block: int):
+    """Flatten a [n_rows, block, ...] result to its valid tokens.
+
+    Returns (token_ids int64 [m], values [m, ...]) in the order of `rows`."""
+    rows = np.asarray(rows, dtype=np.int64)
+    tok = (rows[:, None] * block + np.arange(block)[None, :]).reshape(-1)
+    vals = np.asarray(x_rows).reshape((tok.size,) + tuple(np.asarray(x_rows).shape[2:]))
+    keep = tok < n_tok
+    return tok[keep], vals[keep]
