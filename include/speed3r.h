@@ -1,0 +1,166 @@
+/*
+ * speed3r.h -- C ABI of the MI355X (gfx950) implementation of Speed3R's Global
+ * Sparse Attention (GSA), Sec. 3.2 of the paper, forward pass, one scene
+ * (batch omitted as in the paper), one GPU.
+ *
+ * The path (Sec. 3.2, eqs. 3-8; supplementary Alg. 1 and Alg. 2):
+ *   1. pool      Q, K, V are mean-pooled over blocks of `block` consecutive
+ *                tokens (the paper's s x s window read as a 1-D token run; the
+ *                last block may be short and is averaged over its valid tokens).
+ *   2. scores    S_guide[h,i,j] = Qc[h,i] . Kc[h,j]                  (eq. 4)
+ *   3. compress  Oc'[h,i] = softmax_j(scale * S_guide[h,i,:]) Vc[h]  (eq. 3)
+ *   4. topk      per (h,i): the k = min(topk, n_blk) key blocks with the
+ *                largest S_guide[h,i,:] ("Selection Branch"); all queries of a
+ *                block share the set; stored ascending.
+ *   5. select    O_sel[t,h] = softmax over the valid tokens of the selected
+ *                blocks of (scale * q[t,h] . k[u,h]), times v      (eq. 6, Alg. 2)
+ *   6. merge     out = g * Oc'[h, t / block] + (1 - g) * O_sel,
+ *                g = sigmoid(gate_logits) or 1/2                   (eqs. 5, 7, 8)
+ * and, as the comparison point, plain dense softmax attention (eq. 2 form).
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer unless stated otherwise; the
+ *     caller owns all of them; the library never frees caller memory.
+ *   - q, k, v, out, gate_logits, o_sel: layout [n_tok][heads][head_dim],
+ *     contiguous, element type given by `dtype`, 16-byte aligned.  Inputs are
+ *     read-only and must not alias outputs.
+ *   - n_blk = ceil(n_tok / block).  head_dim must be 64, block one of
+ *     16, 32, 64, 128 (else S3R_ERR_UNSUPPORTED).  topk > n_blk is clamped.
+ *     n_tok need not be a multiple of block.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream); no call synchronises the host except where noted.
+ *   - Every function returns a status code; speed3r_last_error() gives a
+ *     message for the last failure on the calling thread.  Nothing is thrown.
+ *   - Entry points that say "library-held scratch" keep one grow-only device
+ *     buffer per process (allocated with hipMalloc on first use or growth;
+ *     growth synchronises the device); calls using it must not overlap.
+ */
+#ifndef SPEED3R_H
+#define SPEED3R_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    S3R_OK = 0,
+    S3R_ERR_INVALID_ARG = 1, /* null / misaligned pointer, non-positive size ...   */
+    S3R_ERR_UNSUPPORTED = 2, /* head_dim != 64, block not in {16,32,64,128}, dtype */
+    S3R_ERR_WORKSPACE = 3,   /* caller workspace too small / allocation failed     */
+    S3R_ERR_HIP = 4          /* a HIP runtime call or kernel launch failed         */
+} s3r_status;
+
+typedef enum { S3R_F32 = 0, S3R_BF16 = 1 } s3r_dtype;
+
+/* Stages of the path, for speed3r_get_stage_ms(). */
+enum {
+    S3R_STAGE_POOL = 0,     /* block pooling (+ K/V tile re-layout for the MFMA path) */
+    S3R_STAGE_SPLIT = 1,    /* pooled fp32 -> bf16 hi/lo operand tiles                */
+    S3R_STAGE_COMPRESS = 2, /* S_guide + compressed attention                         */
+    S3R_STAGE_TOPK = 3,     /* per-query-block TopK                                   */
+    S3R_STAGE_SELECT = 4,   /* block-sparse attention + merge                         */
+    S3R_STAGE_DENSE = 5,    /* dense attention                                        */
+    S3R_N_STAGES = 6
+};
+
+typedef struct s3r_params {
+    const void *q, *k, *v;   /* in   [n_tok][heads][head_dim]                                   */
+    void *out;               /* out  [n_tok][heads][head_dim], merged result (eq. 8)            */
+    const void *gate_logits; /* in, optional (NULL: g = 1/2), same layout and dtype as q        */
+    int64_t n_tok;
+    int heads, head_dim, block, topk;
+    s3r_dtype dtype;
+    float softmax_scale;     /* <= 0: 1/sqrt(head_dim).  Used by both branches.                 */
+    int32_t *topk_idx;       /* out, optional: [heads][n_blk][k] ascending block indices        */
+    float *lse_sel;          /* out, optional: [heads][n_tok], Alg. 2's L (natural log)         */
+    float *o_comp;           /* out, optional: [heads][n_blk][head_dim] fp32, Oc' of eq. 3      */
+    void *o_sel;             /* out, optional: [n_tok][heads][head_dim], O_sel of eq. 6         */
+    void *workspace;         /* caller-owned device scratch, 256-byte aligned                   */
+    size_t workspace_bytes;  /* >= speed3r_workspace_bytes(...) for the same problem            */
+    void *stream;            /* hipStream_t                                                     */
+} s3r_params;
+
+/* Bytes of device scratch speed3r_sparse_global_attn_ex needs (0 on invalid arguments). */
+size_t speed3r_workspace_bytes(int64_t n_tok, int heads, int head_dim, int block, int topk,
+                               s3r_dtype dtype);
+
+/* The whole GSA path (steps 1-6 above; Sec. 3.2, eqs. 3-8).  Re-entrant across streams when each
+ * call has its own workspace.  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
+s3r_status speed3r_sparse_global_attn_ex(const s3r_params *params);
+
+/* Short form of the above: bf16, scale 1/sqrt(head_dim), no gate (g = 1/2), library-held scratch.
+ * Returns an s3r_status as int. */
+int speed3r_sparse_global_attn(const void *q, const void *k, const void *v, void *out,
+                               int64_t n_tok, int heads, int head_dim, int block, int topk,
+                               void *stream);
+
+/* Dense softmax attention over all n_tok keys (eq. 2 form): out[t,h] = softmax_u(scale q.k) v.
+ * The speed-up denominator.  lse (optional) is [heads][n_tok].  Library-held scratch. */
+s3r_status speed3r_dense_attn(const void *q, const void *k, const void *v, void *out, float *lse,
+                              int64_t n_tok, int heads, int head_dim, s3r_dtype dtype,
+                              float softmax_scale, void *stream);
+
+/* ---- stage entry points (per-kernel parity tests and profiling) ---------------------------- */
+
+/* Step 1 (Sec. 3.2 "Compression Branch"): block means of q, k, v.
+ * qc, kc, vc: out, fp32 [heads][n_blk][head_dim]. */
+s3r_status speed3r_pool_blocks(const void *q, const void *k, const void *v, float *qc, float *kc,
+                               float *vc, int64_t n_tok, int heads, int head_dim, int block,
+                               s3r_dtype dtype, void *stream);
+
+/* Steps 2-3 (eqs. 3-4; Alg. 1 without its TopK part) on pooled fp32 tensors.
+ *   qc, kc, vc : in  fp32 [heads][n_blk][head_dim]
+ *   s_guide    : out fp32 [heads][n_blk][ld_s], unscaled scores; ld_s >= n_blk, ld_s % 4 == 0;
+ *                columns n_blk..ld_s-1 of a row are scratch (unspecified values)
+ *   o_comp     : out fp32 [heads][n_blk][head_dim]
+ *   accurate_pv: nonzero computes P.Vc with bf16 hi+lo operand pairs (fp32-level accuracy,
+ *                used for S3R_F32 problems); zero uses single bf16 operands.
+ * Library-held scratch. */
+s3r_status speed3r_compress_attn_scores(const float *qc, const float *kc, const float *vc,
+                                        float *s_guide, int64_t ld_s, float *o_comp, int64_t n_blk,
+                                        int heads, int head_dim, float softmax_scale,
+                                        int accurate_pv, void *stream);
+
+/* Step 4 (TopKSelect): idx[h][i][0..k) = ascending indices of the k = min(topk, n_blk) largest
+ * entries of s_guide[h][i][0..n_blk); equal scores go to the smaller index.  Deterministic.
+ * s_guide must hold no NaN. */
+s3r_status speed3r_topk_blocks(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t n_blk,
+                               int heads, int topk, void *stream);
+
+/* Steps 5-6 (eq. 6 / Alg. 2, then eqs. 5, 7, 8) with a given index tensor.
+ *   idx     : in  [heads][n_blk][kk] block indices in [0, n_blk), distinct per row; 1 <= kk <= n_blk
+ *   o_comp  : in, optional fp32 [heads][n_blk][head_dim]; NULL: `out` receives O_sel unmerged
+ *   gate_logits, o_sel, lse: as in s3r_params (all optional)
+ * Library-held scratch. */
+s3r_status speed3r_select_attn(const void *q, const void *k, const void *v, const int32_t *idx,
+                               const float *o_comp, const void *gate_logits, void *out, void *o_sel,
+                               float *lse, int64_t n_tok, int heads, int head_dim, int block, int kk,
+                               s3r_dtype dtype, float softmax_scale, void *stream);
+
+/* ---- utilities ------------------------------------------------------------------------------ */
+
+/* When enabled, every entry point brackets each kernel launch with HIP events on the call's own
+ * stream and keeps them for speed3r_get_stage_ms (process-wide switch; default off). */
+s3r_status speed3r_set_profiling(int enable);
+
+/* Host arrays of S3R_N_STAGES entries: summed kernel milliseconds and number of launches per
+ * stage of the most recent profiled entry-point call.  Waits for that call's events. */
+s3r_status speed3r_get_stage_ms(float *ms, int *launches);
+
+/* Selects the selection/dense kernel family: 0 = automatic (MFMA kernels for bf16 with block 64
+ * or 128, the generic kernel otherwise), 1 = always the generic kernel.  Process-wide. */
+s3r_status speed3r_set_kernel_choice(int choice);
+
+/* Frees the library-held scratch (synchronises the device). */
+s3r_status speed3r_release_scratch(void);
+
+/* Message for the last non-OK status on this thread (static storage, never NULL). */
+const char *speed3r_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPEED3R_H */

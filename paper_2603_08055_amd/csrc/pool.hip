@@ -1,0 +1,161 @@
+// Block mean-pooling of Q, K, V (Sec. 3.2 "Compression Branch": non-overlapping average
+// pooling, here over runs of B consecutive tokens) fused with the re-layout of K and V into
+// per-(head, block) MFMA operand tiles for the selection kernel.  One pass over Q, K, V: the
+// kernel is HBM-bandwidth bound (reads 3 * n_tok * heads * 64 elements once).
+#include "s3r_device.h"
+#include "s3r_kernels.h"
+
+namespace s3r {
+
+template <typename T> struct Load8;
+template <> struct Load8<bf16_t> {
+    static __device__ __forceinline__ void run(const bf16_t *p, float (&f)[8], bf16x8 &raw)
+    {
+        raw = *reinterpret_cast<const bf16x8 *>(p);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = static_cast<float>(raw[i]);
+    }
+};
+template <> struct Load8<float> {
+    static __device__ __forceinline__ void run(const float *p, float (&f)[8], bf16x8 &raw)
+    {
+        const floatx4 a = *reinterpret_cast<const floatx4 *>(p);
+        const floatx4 b = *reinterpret_cast<const floatx4 *>(p + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { f[i] = a[i]; f[4 + i] = b[i]; }
+        (void)raw;
+    }
+};
+
+// grid: one workgroup per (block j, head h), head fastest; 256 threads.
+// Thread (r0 = tid / 8, c = tid % 8) handles channels 8c..8c+7 of rows r0, r0 + 32, ...
+template <typename T, int B, bool REPACK>
+__global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ q, const T *__restrict__ k,
+                                                   const T *__restrict__ v, float *__restrict__ qc,
+                                                   float *__restrict__ kc, float *__restrict__ vc,
+                                                   bf16_t *__restrict__ kb, bf16_t *__restrict__ vb,
+                                                   int64_t n_tok, int heads, int64_t n_blk)
+{
+    constexpr int VS_STRIDE = 72;  // bf16 elements per staged V row (64 + pad: conflict-free columns)
+    __shared__ float red[3][32][65];
+    __shared__ bf16_t vs[REPACK ? B : 1][VS_STRIDE];
+
+    const int64_t bid = blockIdx.x;
+    const int h = static_cast<int>(bid % heads);
+    const int64_t j = bid / heads;
+    const int tid = threadIdx.x;
+    const int c = tid & 7, r0 = tid >> 3;
+    const int64_t t0 = j * B;
+    const int len = static_cast<int>((n_tok - t0 < B) ? (n_tok - t0) : B);
+    const int64_t tile_base = (static_cast<int64_t>(h) * n_blk + j) * (B * 64);
+
+    float acc[3][8];
+#pragma unroll
+    for (int x = 0; x < 3; ++x)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[x][i] = 0.f;
+
+#pragma unroll
+    for (int r = r0; r < B; r += 32) {
+        float f[8];
+        bf16x8 raw;
+        const bool valid = r < len;
+        const int64_t off = ((t0 + r) * heads + h) * 64 + c * 8;
+        if (valid) {
+            Load8<T>::run(q + off, f, raw);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[0][i] += f[i];
+            Load8<T>::run(k + off, f, raw);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[1][i] += f[i];
+        }
+        if constexpr (REPACK) {
+            if (!valid)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) raw[i] = static_cast<bf16_t>(0.f);
+            bf16_t *dst = kb + tile_base + (r >> 5) * kRowTileElems + row_tile_chunk_offset(r & 31, c);
+            *reinterpret_cast<bf16x8 *>(dst) = raw;
+        }
+        if (valid) {
+            Load8<T>::run(v + off, f, raw);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[2][i] += f[i];
+        }
+        if constexpr (REPACK) {
+            if (!valid)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) raw[i] = static_cast<bf16_t>(0.f);
+            *reinterpret_cast<bf16x8 *>(&vs[r][c * 8]) = raw;
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < 3; ++x)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) red[x][r0][c * 8 + i] = acc[x][i];
+    __syncthreads();
+
+    if (qc != nullptr && tid < 192) {
+        const int x = tid >> 6, d = tid & 63;
+        float s = 0.f;
+#pragma unroll
+        for (int g = 0; g < 32; ++g) s += red[x][g][d];
+        float *dst = (x == 0) ? qc : (x == 1) ? kc : vc;
+        dst[(static_cast<int64_t>(h) * n_blk + j) * 64 + d] = s / static_cast<float>(len);
+    }
+
+    if constexpr (REPACK) {
+        // V tile, contraction (key) index made contiguous per lane: see tr_tile_key().
+        for (int ci = tid; ci < B * 8; ci += 256) {
+            const int l = ci & 63, dt = (ci >> 6) & 1, u = ci >> 7;
+            const int d = 32 * dt + (l & 31);
+            bf16x8 o;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = vs[tr_tile_key(u, l, i)][d];
+            *reinterpret_cast<bf16x8 *>(vb + tile_base + static_cast<int64_t>(ci) * 8) = o;
+        }
+    }
+}
+
+template <typename T, int B, bool REPACK>
+static hipError_t run_pool(const void *q, const void *k, const void *v, float *qc, float *kc,
+                           float *vc, void *kb, void *vb, int64_t n_tok, int heads, int64_t n_blk,
+                           hipStream_t stream)
+{
+    const int64_t grid = n_blk * heads;
+    hipLaunchKernelGGL((pool_kernel<T, B, REPACK>), dim3(static_cast<unsigned>(grid)), dim3(256), 0,
+                       stream, static_cast<const T *>(q), static_cast<const T *>(k),
+                       static_cast<const T *>(v), qc, kc, vc, static_cast<bf16_t *>(kb),
+                       static_cast<bf16_t *>(vb), n_tok, heads, n_blk);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, float *kc, float *vc,
+                       void *kb, void *vb, int64_t n_tok, int heads, int block, bool is_bf16,
+                       hipStream_t stream)
+{
+    const int64_t n_blk = (n_tok + block - 1) / block;
+    if (n_blk * heads > 0x7fffffffLL) return hipErrorInvalidValue;
+    const bool repack = kb != nullptr;
+    if (repack && !(is_bf16 && (block == 64 || block == 128))) return hipErrorInvalidValue;
+#define S3R_POOL_CASE(TT, BB, RR) \
+    return run_pool<TT, BB, RR>(q, k, v, qc, kc, vc, kb, vb, n_tok, heads, n_blk, stream)
+    if (is_bf16) {
+        switch (block) {
+        case 16: S3R_POOL_CASE(bf16_t, 16, false);
+        case 32: S3R_POOL_CASE(bf16_t, 32, false);
+        case 64: if (repack) S3R_POOL_CASE(bf16_t, 64, true); else S3R_POOL_CASE(bf16_t, 64, false);
+        case 128: if (repack) S3R_POOL_CASE(bf16_t, 128, true); else S3R_POOL_CASE(bf16_t, 128, false);
+        }
+    } else {
+        switch (block) {
+        case 16: S3R_POOL_CASE(float, 16, false);
+        case 32: S3R_POOL_CASE(float, 32, false);
+        case 64: S3R_POOL_CASE(float, 64, false);
+        case 128: S3R_POOL_CASE(float, 128, false);
+        }
+    }
+#undef S3R_POOL_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace s3r

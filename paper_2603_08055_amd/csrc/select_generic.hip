@@ -1,0 +1,142 @@
+// Selection attention + merge (Sec. 3.2 eq. 6, Alg. 2; eqs. 5, 7, 8) and dense attention (eq. 2
+// form), generic version: one thread per query row, fp32 FMA arithmetic, key/value chunks of 32
+// tokens staged through LDS.  Serves fp32 problems and block sizes the MFMA kernels do not cover.
+// Not tuned for throughput; the bf16 MFMA kernels are the fast path.
+#include "s3r_device.h"
+#include "s3r_kernels.h"
+
+namespace s3r {
+
+constexpr int kChunk = 32;  // keys staged per step
+
+// grid: one workgroup per (query block i, head h), head fastest; blockDim = max(64, block).
+// idx == nullptr: attend to every block (dense attention).
+template <typename T>
+__global__ void select_generic_kernel(const T *__restrict__ q, const T *__restrict__ k,
+                                      const T *__restrict__ v, const int32_t *__restrict__ idx,
+                                      const float *__restrict__ o_comp, const T *__restrict__ gate,
+                                      T *__restrict__ out, T *__restrict__ o_sel, float *__restrict__ lse,
+                                      int64_t n_tok, int64_t n_blk, int heads, int block, int kk,
+                                      float scale_log2)
+{
+    __shared__ __attribute__((aligned(16))) float ks[kChunk][64];
+    __shared__ __attribute__((aligned(16))) float vs[kChunk][64];
+
+    const int64_t bid = blockIdx.x;
+    const int h = static_cast<int>(bid % heads);
+    const int64_t i = bid / heads;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int64_t t = i * block + tid;
+    const bool active = tid < block && t < n_tok;
+
+    float qr[64], acc[64];
+#pragma unroll
+    for (int c = 0; c < 64; ++c) {
+        qr[c] = active ? to_float(q[(t * heads + h) * 64 + c]) : 0.f;
+        acc[c] = 0.f;
+    }
+    float m_run = -1e30f, l_run = 0.f;
+
+    const int64_t n_sel = (idx != nullptr) ? kk : n_blk;
+    const int32_t *sel = (idx != nullptr) ? idx + (static_cast<int64_t>(h) * n_blk + i) * kk : nullptr;
+
+    for (int64_t a = 0; a < n_sel; ++a) {
+        const int64_t j = (sel != nullptr) ? sel[a] : a;
+        const int64_t u0 = j * block;
+        const int len = static_cast<int>((n_tok - u0 < block) ? (n_tok - u0) : block);
+        for (int c0 = 0; c0 < len; c0 += kChunk) {
+            const int nk = (len - c0 < kChunk) ? (len - c0) : kChunk;
+            __syncthreads();
+            for (int e = tid; e < nk * 64; e += nthr) {
+                const int r = e >> 6, c = e & 63;
+                const int64_t src = ((u0 + c0 + r) * heads + h) * 64 + c;
+                ks[r][c] = to_float(k[src]);
+                vs[r][c] = to_float(v[src]);
+            }
+            __syncthreads();
+            float s[kChunk];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < kChunk; ++r) {
+                float d = 0.f;
+                if (r < nk) {
+#pragma unroll
+                    for (int c = 0; c < 64; c += 4) {
+                        const floatx4 kv = *reinterpret_cast<const floatx4 *>(&ks[r][c]);
+                        d += qr[c] * kv[0] + qr[c + 1] * kv[1] + qr[c + 2] * kv[2] + qr[c + 3] * kv[3];
+                    }
+                    d *= scale_log2;
+                    mx = fmaxf(mx, d);
+                } else {
+                    d = -INFINITY;
+                }
+                s[r] = d;
+            }
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = fast_exp2(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int c = 0; c < 64; ++c) acc[c] *= alpha;
+#pragma unroll
+            for (int r = 0; r < kChunk; ++r) {
+                if (r < nk) {
+                    const float p = fast_exp2(s[r] - m_new);
+                    l_run += p;
+#pragma unroll
+                    for (int c = 0; c < 64; c += 4) {
+                        const floatx4 vv = *reinterpret_cast<const floatx4 *>(&vs[r][c]);
+                        acc[c] += p * vv[0];
+                        acc[c + 1] += p * vv[1];
+                        acc[c + 2] += p * vv[2];
+                        acc[c + 3] += p * vv[3];
+                    }
+                }
+            }
+        }
+    }
+
+    if (!active) return;
+    const float inv = 1.f / l_run;
+    const int64_t o = (t * heads + h) * 64;
+    if (lse != nullptr) lse[static_cast<int64_t>(h) * n_tok + t] = (m_run + __builtin_log2f(l_run)) * kLn2;
+    const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_blk + i) * 64 : nullptr;
+#pragma unroll
+    for (int c = 0; c < 64; ++c) {
+        const float os = acc[c] * inv;
+        if (o_sel != nullptr) o_sel[o + c] = from_float<T>(os);
+        float r = os;
+        if (oc != nullptr) {
+            float gt = 0.5f;
+            if (gate != nullptr) gt = 1.f / (1.f + __expf(-to_float(gate[o + c])));
+            r = gt * oc[c] + (1.f - gt) * os;
+        }
+        out[o + c] = from_float<T>(r);
+    }
+}
+
+hipError_t launch_select_generic(const SelectArgs &a, hipStream_t stream)
+{
+    const int64_t grid = a.n_blk * a.heads;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int threads = a.block < 64 ? 64 : a.block;
+    const float scale_log2 = a.scale * kLog2e;
+    if (a.is_bf16) {
+        hipLaunchKernelGGL(select_generic_kernel<bf16_t>, dim3(static_cast<unsigned>(grid)), dim3(threads),
+                           0, stream, static_cast<const bf16_t *>(a.q), static_cast<const bf16_t *>(a.k),
+                           static_cast<const bf16_t *>(a.v), a.idx, a.o_comp,
+                           static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
+                           static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.block,
+                           a.kk, scale_log2);
+    } else {
+        hipLaunchKernelGGL(select_generic_kernel<float>, dim3(static_cast<unsigned>(grid)), dim3(threads),
+                           0, stream, static_cast<const float *>(a.q), static_cast<const float *>(a.k),
+                           static_cast<const float *>(a.v), a.idx, a.o_comp,
+                           static_cast<const float *>(a.gate), static_cast<float *>(a.out),
+                           static_cast<float *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.block, a.kk,
+                           scale_log2);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace s3r

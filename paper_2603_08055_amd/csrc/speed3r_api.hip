@@ -1,0 +1,460 @@
+// C ABI of the library (see include/speed3r.h): argument checks, workspace carving, launch
+// sequencing, optional per-stage event timing.  No kernel code here.
+#include "../../include/speed3r.h"
+#include "s3r_kernels.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <mutex>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "no error";
+
+s3r_status fail(s3r_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+s3r_status hip_fail(hipError_t e, const char *what)
+{
+    return fail(S3R_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define S3R_HIP(call, what)                                  \
+    do {                                                     \
+        hipError_t e_ = (call);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, what);     \
+    } while (0)
+
+constexpr size_t kAlign = 256;
+constexpr size_t kScoreBytesCap = size_t(8) << 30;  // S_guide is processed in head chunks of at most this size
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int g_kernel_choice = 0;  // 0 auto, 1 generic only
+
+bool mfma_ok(s3r_dtype dtype, int block) { return g_kernel_choice == 0 && dtype == S3R_BF16 && (block == 64 || block == 128); }
+
+s3r_status check_shape(int64_t n_tok, int heads, int head_dim, int block, int topk, int dtype)
+{
+    if (n_tok <= 0 || heads <= 0 || topk <= 0)
+        return fail(S3R_ERR_INVALID_ARG, "n_tok (%lld), heads (%d) and topk (%d) must be positive",
+                    static_cast<long long>(n_tok), heads, topk);
+    if (dtype != S3R_F32 && dtype != S3R_BF16) return fail(S3R_ERR_UNSUPPORTED, "unknown dtype %d", dtype);
+    if (head_dim != 64) return fail(S3R_ERR_UNSUPPORTED, "head_dim %d unsupported (must be 64)", head_dim);
+    if (block != 16 && block != 32 && block != 64 && block != 128)
+        return fail(S3R_ERR_UNSUPPORTED, "block %d unsupported (must be 16, 32, 64 or 128)", block);
+    if (heads > 65535) return fail(S3R_ERR_UNSUPPORTED, "heads %d unsupported (max 65535)", heads);
+    const int64_t n_blk = (n_tok + block - 1) / block;
+    if (n_blk * heads > 0x7fffffffLL) return fail(S3R_ERR_UNSUPPORTED, "n_blk * heads exceeds 2^31 - 1");
+    return S3R_OK;
+}
+
+// ---- workspace layout of the full path -------------------------------------------------------
+struct Layout {
+    int64_t n_blk, tiles, ld_s;
+    int kk, head_chunk;
+    size_t qc, kc, vc, oc, tile[6], idx, s, kb, vb, total;
+};
+
+Layout make_layout(int64_t n_tok, int heads, int block, int topk, s3r_dtype dtype)
+{
+    Layout L{};
+    L.n_blk = (n_tok + block - 1) / block;
+    L.kk = static_cast<int>(topk < L.n_blk ? topk : L.n_blk);
+    L.tiles = s3r::pooled_tiles_padded(L.n_blk);
+    L.ld_s = (L.n_blk + 63) / 64 * 64;
+    const size_t per_head_s = static_cast<size_t>(L.n_blk) * L.ld_s * sizeof(float);
+    int64_t hc = static_cast<int64_t>(kScoreBytesCap / per_head_s);
+    if (hc < 1) hc = 1;
+    if (hc > heads) hc = heads;
+    L.head_chunk = static_cast<int>(hc);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
+    const size_t pooled = static_cast<size_t>(heads) * L.n_blk * 64 * sizeof(float);
+    L.qc = take(pooled);
+    L.kc = take(pooled);
+    L.vc = take(pooled);
+    L.oc = take(pooled);
+    for (int a = 0; a < 6; ++a) L.tile[a] = take(static_cast<size_t>(heads) * L.tiles * 32 * 64 * 2);
+    L.idx = take(static_cast<size_t>(heads) * L.n_blk * L.kk * sizeof(int32_t));
+    L.s = take(per_head_s * L.head_chunk);
+    const size_t blocked = mfma_ok(dtype, block) ? static_cast<size_t>(heads) * L.n_blk * block * 64 * 2 : 0;
+    L.kb = take(blocked);
+    L.vb = take(blocked);
+    L.total = off;
+    return L;
+}
+
+// ---- library-held scratch --------------------------------------------------------------------
+std::mutex g_mu;
+constexpr int kMaxDevices = 64;
+void *g_scratch[kMaxDevices] = {};
+size_t g_scratch_bytes[kMaxDevices] = {};
+
+s3r_status scratch_get(size_t bytes, void **out)
+{
+    int dev = 0;
+    S3R_HIP(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(S3R_ERR_UNSUPPORTED, "device ordinal %d unsupported", dev);
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (bytes > g_scratch_bytes[dev]) {
+        S3R_HIP(hipDeviceSynchronize(), "hipDeviceSynchronize before growing scratch");
+        if (g_scratch[dev]) {
+            S3R_HIP(hipFree(g_scratch[dev]), "hipFree(scratch)");
+            g_scratch[dev] = nullptr;
+            g_scratch_bytes[dev] = 0;
+        }
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, bytes);
+        if (e != hipSuccess) return fail(S3R_ERR_WORKSPACE, "hipMalloc of %zu scratch bytes failed: %s", bytes, hipGetErrorString(e));
+        g_scratch[dev] = p;
+        g_scratch_bytes[dev] = bytes;
+    }
+    *out = g_scratch[dev];
+    return S3R_OK;
+}
+
+// ---- per-stage event timing ------------------------------------------------------------------
+bool g_profiling = false;
+struct Span { int stage; hipEvent_t start, stop; };
+std::vector<Span> g_spans;        // spans of the most recent profiled call
+std::vector<hipEvent_t> g_pool;   // recycled events
+
+hipEvent_t event_take()
+{
+    if (!g_pool.empty()) { hipEvent_t e = g_pool.back(); g_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void spans_reset()
+{
+    if (!g_profiling) return;
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (auto &s : g_spans) { g_pool.push_back(s.start); g_pool.push_back(s.stop); }
+    g_spans.clear();
+}
+
+struct StageTimer {
+    hipStream_t stream;
+    Span span{};
+    bool on = false;
+    StageTimer(int stage, hipStream_t st) : stream(st)
+    {
+        if (!g_profiling) return;
+        std::lock_guard<std::mutex> lock(g_mu);
+        span.stage = stage;
+        span.start = event_take();
+        span.stop = event_take();
+        on = span.start && span.stop;
+        if (on) on = hipEventRecord(span.start, stream) == hipSuccess;
+    }
+    ~StageTimer()
+    {
+        if (!on) return;
+        if (hipEventRecord(span.stop, stream) != hipSuccess) return;
+        std::lock_guard<std::mutex> lock(g_mu);
+        g_spans.push_back(span);
+    }
+};
+
+char *at(void *base, size_t off) { return static_cast<char *>(base) + off; }
+
+// pooled fp32 -> operand tiles -> S_guide / Oc' -> TopK, in head chunks bounded by the S buffer
+s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, void *const tile[6],
+                             float *s_buf, int64_t ld_s, int head_chunk, float *o_comp, int32_t *idx,
+                             int64_t n_blk, int64_t tiles, int heads, int kk, float scale,
+                             bool accurate_pv, bool want_topk, hipStream_t stream)
+{
+    {
+        StageTimer tm(S3R_STAGE_SPLIT, stream);
+        S3R_HIP(s3r::launch_split(qc, kc, vc, tile[0], tile[1], tile[2], tile[3], tile[4],
+                                  accurate_pv ? tile[5] : nullptr, n_blk, heads, stream),
+                "split kernel launch");
+    }
+    const size_t tile_head = static_cast<size_t>(tiles) * 32 * 64 * 2;  // bytes per head per array
+    for (int h0 = 0; h0 < heads; h0 += head_chunk) {
+        const int hc = (heads - h0 < head_chunk) ? heads - h0 : head_chunk;
+        {
+            StageTimer tm(S3R_STAGE_COMPRESS, stream);
+            S3R_HIP(s3r::launch_compress(at(tile[0], h0 * tile_head), at(tile[1], h0 * tile_head),
+                                         at(tile[2], h0 * tile_head), at(tile[3], h0 * tile_head),
+                                         at(tile[4], h0 * tile_head),
+                                         accurate_pv ? at(tile[5], h0 * tile_head) : nullptr, s_buf, ld_s,
+                                         o_comp + static_cast<size_t>(h0) * n_blk * 64, n_blk, hc, scale,
+                                         stream),
+                    "compress kernel launch");
+        }
+        if (want_topk) {
+            StageTimer tm(S3R_STAGE_TOPK, stream);
+            S3R_HIP(s3r::launch_topk(s_buf, ld_s, idx + static_cast<size_t>(h0) * n_blk * kk, n_blk,
+                                     static_cast<int64_t>(hc) * n_blk, kk, stream),
+                    "topk kernel launch");
+        }
+    }
+    return S3R_OK;
+}
+
+float resolve_scale(float s, int head_dim) { return s > 0.f ? s : 1.f / std::sqrt(static_cast<float>(head_dim)); }
+
+}  // namespace
+
+extern "C" {
+
+const char *speed3r_last_error(void) { return g_err; }
+
+s3r_status speed3r_set_profiling(int enable)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_profiling = enable != 0;
+    return S3R_OK;
+}
+
+s3r_status speed3r_set_kernel_choice(int choice)
+{
+    if (choice != 0 && choice != 1) return fail(S3R_ERR_INVALID_ARG, "kernel choice %d unknown", choice);
+    g_kernel_choice = choice;
+    return S3R_OK;
+}
+
+s3r_status speed3r_get_stage_ms(float *ms, int *launches)
+{
+    if (!ms || !launches) return fail(S3R_ERR_INVALID_ARG, "ms and launches must be non-null host arrays");
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (int i = 0; i < S3R_N_STAGES; ++i) { ms[i] = 0.f; launches[i] = 0; }
+    for (auto &s : g_spans) {
+        S3R_HIP(hipEventSynchronize(s.stop), "hipEventSynchronize");
+        float t = 0.f;
+        S3R_HIP(hipEventElapsedTime(&t, s.start, s.stop), "hipEventElapsedTime");
+        ms[s.stage] += t;
+        launches[s.stage] += 1;
+    }
+    return S3R_OK;
+}
+
+s3r_status speed3r_release_scratch(void)
+{
+    int dev = 0;
+    S3R_HIP(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return S3R_OK;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (g_scratch[dev]) {
+        S3R_HIP(hipDeviceSynchronize(), "hipDeviceSynchronize");
+        S3R_HIP(hipFree(g_scratch[dev]), "hipFree(scratch)");
+        g_scratch[dev] = nullptr;
+        g_scratch_bytes[dev] = 0;
+    }
+    return S3R_OK;
+}
+
+size_t speed3r_workspace_bytes(int64_t n_tok, int heads, int head_dim, int block, int topk, s3r_dtype dtype)
+{
+    if (check_shape(n_tok, heads, head_dim, block, topk, dtype) != S3R_OK) return 0;
+    return make_layout(n_tok, heads, block, topk, dtype).total;
+}
+
+s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
+{
+    if (!p) return fail(S3R_ERR_INVALID_ARG, "params is null");
+    s3r_status st = check_shape(p->n_tok, p->heads, p->head_dim, p->block, p->topk, p->dtype);
+    if (st != S3R_OK) return st;
+    if (!p->q || !p->k || !p->v || !p->out) return fail(S3R_ERR_INVALID_ARG, "q, k, v and out must be non-null");
+    if (!aligned16(p->q) || !aligned16(p->k) || !aligned16(p->v) || !aligned16(p->out) ||
+        !aligned16(p->gate_logits) || !aligned16(p->o_sel) || !aligned16(p->o_comp) ||
+        !aligned16(p->topk_idx) || !aligned16(p->lse_sel))
+        return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    if (p->out == p->q || p->out == p->k || p->out == p->v) return fail(S3R_ERR_INVALID_ARG, "out must not alias an input");
+    const Layout L = make_layout(p->n_tok, p->heads, p->block, p->topk, p->dtype);
+    if (!p->workspace) return fail(S3R_ERR_WORKSPACE, "workspace is null (%zu bytes needed)", L.total);
+    if ((reinterpret_cast<uintptr_t>(p->workspace) & (kAlign - 1)) != 0)
+        return fail(S3R_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    if (p->workspace_bytes < L.total)
+        return fail(S3R_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", p->workspace_bytes, L.total);
+
+    hipStream_t stream = static_cast<hipStream_t>(p->stream);
+    const bool is_bf16 = p->dtype == S3R_BF16;
+    const bool mfma = mfma_ok(p->dtype, p->block);
+    const float scale = resolve_scale(p->softmax_scale, p->head_dim);
+    void *ws = p->workspace;
+    float *qc = reinterpret_cast<float *>(at(ws, L.qc));
+    float *kc = reinterpret_cast<float *>(at(ws, L.kc));
+    float *vc = reinterpret_cast<float *>(at(ws, L.vc));
+    float *oc = p->o_comp ? p->o_comp : reinterpret_cast<float *>(at(ws, L.oc));
+    int32_t *idx = p->topk_idx ? p->topk_idx : reinterpret_cast<int32_t *>(at(ws, L.idx));
+    void *tile[6];
+    for (int a = 0; a < 6; ++a) tile[a] = at(ws, L.tile[a]);
+    void *kb = mfma ? at(ws, L.kb) : nullptr;
+    void *vb = mfma ? at(ws, L.vb) : nullptr;
+
+    spans_reset();
+    {
+        StageTimer tm(S3R_STAGE_POOL, stream);
+        S3R_HIP(s3r::launch_pool(p->q, p->k, p->v, qc, kc, vc, kb, vb, p->n_tok, p->heads, p->block, is_bf16, stream),
+                "pool kernel launch");
+    }
+    st = run_compress_topk(qc, kc, vc, tile, reinterpret_cast<float *>(at(ws, L.s)), L.ld_s, L.head_chunk, oc,
+                           idx, L.n_blk, L.tiles, p->heads, L.kk, scale, !is_bf16, true, stream);
+    if (st != S3R_OK) return st;
+
+    s3r::SelectArgs a{};
+    a.q = p->q; a.k = p->k; a.v = p->v; a.kb = kb; a.vb = vb; a.idx = idx; a.o_comp = oc;
+    a.gate = p->gate_logits; a.out = p->out; a.o_sel = p->o_sel; a.lse = p->lse_sel;
+    a.n_tok = p->n_tok; a.n_blk = L.n_blk; a.heads = p->heads; a.block = p->block; a.kk = L.kk;
+    a.scale = scale; a.is_bf16 = is_bf16;
+    {
+        StageTimer tm(S3R_STAGE_SELECT, stream);
+        S3R_HIP(mfma ? s3r::launch_select_mfma(a, stream) : s3r::launch_select_generic(a, stream),
+                "select kernel launch");
+    }
+    return S3R_OK;
+}
+
+int speed3r_sparse_global_attn(const void *q, const void *k, const void *v, void *out, int64_t n_tok,
+                               int heads, int head_dim, int block, int topk, void *stream)
+{
+    s3r_status st = check_shape(n_tok, heads, head_dim, block, topk, S3R_BF16);
+    if (st != S3R_OK) return st;
+    s3r_params p{};
+    p.q = q; p.k = k; p.v = v; p.out = out;
+    p.n_tok = n_tok; p.heads = heads; p.head_dim = head_dim; p.block = block; p.topk = topk;
+    p.dtype = S3R_BF16; p.softmax_scale = 0.f; p.stream = stream;
+    p.workspace_bytes = speed3r_workspace_bytes(n_tok, heads, head_dim, block, topk, S3R_BF16);
+    st = scratch_get(p.workspace_bytes, &p.workspace);
+    if (st != S3R_OK) return st;
+    return speed3r_sparse_global_attn_ex(&p);
+}
+
+s3r_status speed3r_pool_blocks(const void *q, const void *k, const void *v, float *qc, float *kc, float *vc,
+                               int64_t n_tok, int heads, int head_dim, int block, s3r_dtype dtype, void *stream)
+{
+    s3r_status st = check_shape(n_tok, heads, head_dim, block, 1, dtype);
+    if (st != S3R_OK) return st;
+    if (!q || !k || !v || !qc || !kc || !vc) return fail(S3R_ERR_INVALID_ARG, "all six tensors must be non-null");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    spans_reset();
+    StageTimer tm(S3R_STAGE_POOL, static_cast<hipStream_t>(stream));
+    S3R_HIP(s3r::launch_pool(q, k, v, qc, kc, vc, nullptr, nullptr, n_tok, heads, block, dtype == S3R_BF16,
+                             static_cast<hipStream_t>(stream)),
+            "pool kernel launch");
+    return S3R_OK;
+}
+
+s3r_status speed3r_compress_attn_scores(const float *qc, const float *kc, const float *vc, float *s_guide,
+                                        int64_t ld_s, float *o_comp, int64_t n_blk, int heads, int head_dim,
+                                        float softmax_scale, int accurate_pv, void *stream)
+{
+    if (n_blk <= 0 || heads <= 0 || heads > 65535) return fail(S3R_ERR_INVALID_ARG, "n_blk and heads must be positive");
+    if (head_dim != 64) return fail(S3R_ERR_UNSUPPORTED, "head_dim %d unsupported (must be 64)", head_dim);
+    if (!qc || !kc || !vc || !s_guide || !o_comp) return fail(S3R_ERR_INVALID_ARG, "all five tensors must be non-null");
+    if (ld_s < n_blk || ld_s % 4 != 0) return fail(S3R_ERR_INVALID_ARG, "ld_s must be >= n_blk and a multiple of 4");
+    if (!aligned16(s_guide) || !aligned16(o_comp)) return fail(S3R_ERR_INVALID_ARG, "s_guide and o_comp must be 16-byte aligned");
+    const int64_t tiles = s3r::pooled_tiles_padded(n_blk);
+    const size_t arr = align_up(static_cast<size_t>(heads) * tiles * 32 * 64 * 2);
+    void *ws = nullptr;
+    s3r_status st = scratch_get(6 * arr, &ws);
+    if (st != S3R_OK) return st;
+    void *tile[6];
+    for (int a = 0; a < 6; ++a) tile[a] = at(ws, a * arr);
+    spans_reset();
+    return run_compress_topk(qc, kc, vc, tile, s_guide, ld_s, heads, o_comp, nullptr, n_blk, tiles, heads, 0,
+                             resolve_scale(softmax_scale, head_dim), accurate_pv != 0, false,
+                             static_cast<hipStream_t>(stream));
+}
+
+s3r_status speed3r_topk_blocks(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t n_blk, int heads,
+                               int topk, void *stream)
+{
+    if (n_blk <= 0 || heads <= 0 || topk <= 0) return fail(S3R_ERR_INVALID_ARG, "n_blk, heads and topk must be positive");
+    if (!s_guide || !idx) return fail(S3R_ERR_INVALID_ARG, "s_guide and idx must be non-null");
+    if (ld_s < n_blk) return fail(S3R_ERR_INVALID_ARG, "ld_s must be >= n_blk");
+    if (n_blk * heads > 0x7fffffffLL) return fail(S3R_ERR_UNSUPPORTED, "n_blk * heads exceeds 2^31 - 1");
+    const int kk = static_cast<int>(topk < n_blk ? topk : n_blk);
+    spans_reset();
+    StageTimer tm(S3R_STAGE_TOPK, static_cast<hipStream_t>(stream));
+    S3R_HIP(s3r::launch_topk(s_guide, ld_s, idx, n_blk, n_blk * heads, kk, static_cast<hipStream_t>(stream)),
+            "topk kernel launch");
+    return S3R_OK;
+}
+
+s3r_status speed3r_select_attn(const void *q, const void *k, const void *v, const int32_t *idx,
+                               const float *o_comp, const void *gate_logits, void *out, void *o_sel,
+                               float *lse, int64_t n_tok, int heads, int head_dim, int block, int kk,
+                               s3r_dtype dtype, float softmax_scale, void *stream)
+{
+    s3r_status st = check_shape(n_tok, heads, head_dim, block, kk, dtype);
+    if (st != S3R_OK) return st;
+    if (!q || !k || !v || !idx || !out) return fail(S3R_ERR_INVALID_ARG, "q, k, v, idx and out must be non-null");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(gate_logits) ||
+        !aligned16(o_sel) || !aligned16(o_comp))
+        return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    const int64_t n_blk = (n_tok + block - 1) / block;
+    if (kk > n_blk) return fail(S3R_ERR_INVALID_ARG, "k (%d) exceeds the number of blocks (%lld)", kk, static_cast<long long>(n_blk));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool mfma = mfma_ok(dtype, block);
+    s3r::SelectArgs a{};
+    spans_reset();
+    if (mfma) {
+        const size_t blocked = align_up(static_cast<size_t>(heads) * n_blk * block * 64 * 2);
+        void *ws = nullptr;
+        st = scratch_get(2 * blocked, &ws);
+        if (st != S3R_OK) return st;
+        a.kb = ws;
+        a.vb = at(ws, blocked);
+        StageTimer tm(S3R_STAGE_POOL, s);
+        S3R_HIP(s3r::launch_pool(q, k, v, nullptr, nullptr, nullptr, const_cast<void *>(a.kb),
+                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s),
+                "pool kernel launch");
+    }
+    a.q = q; a.k = k; a.v = v; a.idx = idx; a.o_comp = o_comp; a.gate = gate_logits; a.out = out;
+    a.o_sel = o_sel; a.lse = lse; a.n_tok = n_tok; a.n_blk = n_blk; a.heads = heads; a.block = block;
+    a.kk = kk; a.scale = resolve_scale(softmax_scale, head_dim); a.is_bf16 = dtype == S3R_BF16;
+    StageTimer tm(S3R_STAGE_SELECT, s);
+    S3R_HIP(mfma ? s3r::launch_select_mfma(a, s) : s3r::launch_select_generic(a, s), "select kernel launch");
+    return S3R_OK;
+}
+
+s3r_status speed3r_dense_attn(const void *q, const void *k, const void *v, void *out, float *lse, int64_t n_tok,
+                              int heads, int head_dim, s3r_dtype dtype, float softmax_scale, void *stream)
+{
+    const int block = 64;
+    s3r_status st = check_shape(n_tok, heads, head_dim, block, 1, dtype);
+    if (st != S3R_OK) return st;
+    if (!q || !k || !v || !out) return fail(S3R_ERR_INVALID_ARG, "q, k, v and out must be non-null");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+        return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    const int64_t n_blk = (n_tok + block - 1) / block;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool mfma = mfma_ok(dtype, block);
+    s3r::SelectArgs a{};
+    spans_reset();
+    if (mfma) {
+        const size_t blocked = align_up(static_cast<size_t>(heads) * n_blk * block * 64 * 2);
+        void *ws = nullptr;
+        st = scratch_get(2 * blocked, &ws);
+        if (st != S3R_OK) return st;
+        a.kb = ws;
+        a.vb = at(ws, blocked);
+        StageTimer tm(S3R_STAGE_POOL, s);
+        S3R_HIP(s3r::launch_pool(q, k, v, nullptr, nullptr, nullptr, const_cast<void *>(a.kb),
+                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s),
+                "pool kernel launch");
+    }
+    a.q = q; a.k = k; a.v = v; a.idx = nullptr; a.o_comp = nullptr; a.gate = nullptr; a.out = out;
+    a.o_sel = nullptr; a.lse = lse; a.n_tok = n_tok; a.n_blk = n_blk; a.heads = heads; a.block = block;
+    a.kk = 0; a.scale = resolve_scale(softmax_scale, head_dim); a.is_bf16 = dtype == S3R_BF16;
+    StageTimer tm(S3R_STAGE_DENSE, s);
+    S3R_HIP(mfma ? s3r::launch_select_mfma(a, s) : s3r::launch_select_generic(a, s), "dense kernel launch");
+    return S3R_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,161 @@
+"""Helpers of the GPU parity tests: tolerances, the TopK acceptance rule, and a driver that runs
+the device path through the C ABI binding and the fp64 oracle on the same inputs."""
+from __future__ import annotations
+
+import math
+import sys
+import time
+
+import numpy as np
+import torch
+
+# Output tolerance: max relative error, bf16 I/O 2e-2, fp32 I/O 1e-4.  The error of an element is
+# |gpu - ref| / max(|ref|, rms(ref)).  Every output here is a softmax-weighted average
+# o_c = sum_u p_u v_uc; rounding p (and v) perturbs it by at most eps * sum_u p_u |v_uc|, a quantity
+# of the order of the tensor's RMS whatever the size of o_c itself, so an element that happens to
+# lie near zero is judged against the RMS, a large one against itself.  (Plain element-wise
+# relative error is unbounded at the zero crossings of the reference.)  The global form
+# max|gpu - ref| / max|ref| is reported too and must pass as well.
+TOL = {"bf16": 2e-2, "f32": 1e-4}
+# Near-tie rule for TopK: with tau the oracle's k-th largest score and s_next the (k+1)-th,
+# delta = 1e-3 * max(|tau|, |s_next|, 1e-30).  A device index set is valid iff it has k distinct
+# in-range indices, holds every j with S > tau + delta and none with S < tau - delta.  When
+# tau - s_next > delta this forces the oracle's exact set.
+TIE_REL = 1e-3
+
+
+def log(msg):
+    print(f"[parity {time.strftime('%H:%M:%S')}] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def rel_errors(gpu, ref):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert gpu.shape == ref.shape, (gpu.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0, 0.0
+    assert np.isfinite(gpu).all(), "non-finite values in the device result"
+    diff = np.abs(gpu - ref)
+    rms = math.sqrt(float(np.mean(ref * ref)))
+    floor = max(rms, 1e-30)
+    elem = float(np.max(diff / np.maximum(np.abs(ref), floor)))
+    glob = float(np.max(diff) / max(float(np.max(np.abs(ref))), 1e-30))
+    return elem, glob
+
+
+def assert_close(gpu, ref, tol, what):
+    elem, glob = rel_errors(gpu, ref)
+    assert elem <= tol and glob <= tol, f"{what}: rel err elem {elem:.3e} glob {glob:.3e} > {tol:.1e}"
+    return elem
+
+
+def check_topk_sets(s_rows, gpu_idx, k):
+    """s_rows [H, R, n_blk] oracle scores, gpu_idx [H, R, k].  Asserts validity of every set under
+    the near-tie rule; returns (n_exact, n_tie_resolved) against the oracle's own choice."""
+    H, R, n_blk = s_rows.shape
+    assert gpu_idx.shape == (H, R, k), (gpu_idx.shape, (H, R, k))
+    n_exact = n_tie = 0
+    for h in range(H):
+        for r in range(R):
+            s = s_rows[h, r]
+            got = gpu_idx[h, r]
+            assert np.all(np.diff(got) > 0), f"indices not strictly ascending at h={h} r={r}: {got}"
+            assert got[0] >= 0 and got[-1] < n_blk, f"index out of range at h={h} r={r}"
+            order = np.lexsort((np.arange(n_blk), -s))          # score desc, then index asc
+            want = np.sort(order[:k])
+            if np.array_equal(want, got):
+                n_exact += 1
+                continue
+            tau = s[order[k - 1]]
+            s_next = s[order[k]] if k < n_blk else tau
+            delta = TIE_REL * max(abs(tau), abs(s_next), 1e-30)
+            chosen = np.zeros(n_blk, dtype=bool)
+            chosen[got] = True
+            must = s > tau + delta
+            never = s < tau - delta
+            assert not np.any(must & ~chosen), (
+                f"h={h} r={r}: device set misses a block above the tie band "
+                f"(tau={tau:.6g}, delta={delta:.3g}, missing={np.where(must & ~chosen)[0][:5]})")
+            assert not np.any(never & chosen), (
+                f"h={h} r={r}: device set holds a block below the tie band "
+                f"(tau={tau:.6g}, delta={delta:.3g}, bad={np.where(never & chosen)[0][:5]})")
+            n_tie += 1
+    return n_exact, n_tie
+
+
+def to_host_f32(t: torch.Tensor) -> np.ndarray:
+    """Exact widening of a (bf16 / fp32) tensor to a float32 numpy array on the host."""
+    return t.detach().to("cpu").to(torch.float32).numpy()
+
+
+def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "lse", "o_comp", "o_sel")):
+    """One call of the whole path through the C ABI; returns numpy results."""
+    n_tok, heads, d = q.shape
+    n_blk = (n_tok + block - 1) // block
+    kk = min(topk, n_blk)
+    dev = q.device
+    out = torch.full_like(q, float("nan"))
+    bufs = {}
+    if "idx" in want:
+        bufs["topk_idx"] = torch.full((heads, n_blk, kk), -1, dtype=torch.int32, device=dev)
+    if "lse" in want:
+        bufs["lse_sel"] = torch.full((heads, n_tok), float("nan"), dtype=torch.float32, device=dev)
+    if "o_comp" in want:
+        bufs["o_comp"] = torch.full((heads, n_blk, d), float("nan"), dtype=torch.float32, device=dev)
+    if "o_sel" in want:
+        bufs["o_sel"] = torch.full_like(q, float("nan"))
+    s3r.speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, gate_logits=gate,
+                                      softmax_scale=scale, **bufs)
+    torch.cuda.synchronize()
+    res = {"out": out}
+    res.update({"idx": bufs.get("topk_idx"), "lse": bufs.get("lse_sel"),
+                "o_comp": bufs.get("o_comp"), "o_sel": bufs.get("o_sel")})
+    return res
+
+
+def compare_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, dtype, rows=None, scale=None,
+                        label=""):
+    """Element-by-element comparison of a device result (tensors from run_device) with the oracle
+    on the query blocks `rows` (all when None).  qf, kf, vf, gate_f: host float32 arrays holding
+    exactly the device inputs.  TopK sets are checked with the near-tie rule; selection outputs are
+    compared against the oracle evaluated on the device's (validated) index sets."""
+    n_tok, heads, d = qf.shape
+    n_blk = (n_tok + block - 1) // block
+    kk = min(topk, n_blk)
+    tol = TOL[dtype]
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(d)
+    rows = np.arange(n_blk, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
+    qc, kc, vc = oracle.pool(qf, block), oracle.pool(kf, block), oracle.pool(vf, block)
+    s = oracle.scores(qc, kc, rows)
+    o_comp = oracle.compressed_attn(s, vc, scale)
+    stats = {}
+
+    def tok_sel(x):          # device tensor [n_tok, ...] -> valid tokens of `rows` (rows order), host f32
+        tok = (rows[:, None] * block + np.arange(block)[None, :]).reshape(-1)
+        tok_t = torch.from_numpy(tok[tok < n_tok]).to(x.device)
+        return to_host_f32(x.index_select(0, tok_t))
+
+    if dev_res.get("o_comp") is not None:
+        g = dev_res["o_comp"][:, torch.from_numpy(rows).to(dev_res["o_comp"].device)].cpu().numpy()
+        stats["o_comp"] = assert_close(g, o_comp, tol, f"{label} o_comp")
+    assert dev_res.get("idx") is not None
+    gidx = dev_res["idx"][:, torch.from_numpy(rows).to(dev_res["idx"].device)].cpu().numpy()
+    n_exact, n_tie = check_topk_sets(s, gidx, kk)
+    stats["topk_exact"], stats["topk_tie_resolved"] = n_exact, n_tie
+    o_sel, lse = oracle.select_attn(qf, kf, vf, block, gidx, scale, rows)
+    out = oracle.merge(o_comp, o_sel, gate_f, n_tok, block, rows)
+    _, o_sel_v = oracle.rows_to_tokens(o_sel, rows, n_tok, block)
+    _, out_v = oracle.rows_to_tokens(out, rows, n_tok, block)
+    _, lse_v = oracle.rows_to_tokens(lse.transpose(1, 2, 0), rows, n_tok, block)      # [m, H]
+    if dev_res.get("o_sel") is not None:
+        stats["o_sel"] = assert_close(tok_sel(dev_res["o_sel"]), o_sel_v, tol, f"{label} o_sel")
+    if dev_res.get("lse") is not None:
+        g = tok_sel(dev_res["lse"].T)
+        # L is a logarithm: compare absolutely (an absolute error in L is a relative error in exp L)
+        err = float(np.max(np.abs(g - lse_v)))
+        assert err <= tol, f"{label} lse abs err {err:.3e} > {tol:.1e}"
+        stats["lse_abs"] = err
+    stats["out"] = assert_close(tok_sel(dev_res["out"]), out_v, tol, f"{label} out")
+    return stats

@@ -1,0 +1,124 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every function that
+include/speed3r.h declares, the Python binding covers the same names, and argument validation
+that needs no device returns the documented status codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "speed3r.h")
+
+
+@pytest.fixture(scope="module")
+def s3r():
+    from paper_2603_08055_amd import speed3r
+    if not os.path.exists(speed3r.LIB_PATH):
+        from paper_2603_08055_amd import build
+        build.build_library()
+    speed3r.load()
+    return speed3r
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(speed3r_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported_and_bound(s3r):
+    names = declared_functions()
+    assert len(names) >= 12
+    lib = ctypes.CDLL(s3r.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in speed3r.h but not exported"
+        assert n in s3r.EXPORTS, f"{n} has no ctypes prototype in the binding"
+        assert hasattr(s3r, n), f"{n} has no Python wrapper of the same name"
+    assert sorted(s3r.EXPORTS) == names
+
+
+def test_params_struct_matches_header(s3r):
+    text = open(HEADER).read()
+    body = re.search(r"typedef struct s3r_params \{(.*?)\} s3r_params;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        for name in decl.split(","):
+            fields.append(re.findall(r"[A-Za-z_][A-Za-z0-9_]*", name)[-1])
+    assert fields == [f[0] for f in s3r.s3r_params._fields_]
+
+
+def test_workspace_bytes_and_shape_validation(s3r):
+    lib = s3r.load()
+    assert s3r.speed3r_workspace_bytes(1024, 2, 64, 64, 4, s3r.S3R_F32) > 0
+    big = s3r.speed3r_workspace_bytes(1374000, 16, 64, 64, 64, s3r.S3R_BF16)
+    assert 8 * 2 ** 30 < big < 40 * 2 ** 30          # fits one MI355X (288 GB) many times over
+    assert s3r.speed3r_workspace_bytes(0, 2, 64, 64, 4, s3r.S3R_F32) == 0
+    assert s3r.speed3r_workspace_bytes(1024, 2, 128, 64, 4, s3r.S3R_F32) == 0
+    assert s3r.speed3r_workspace_bytes(1024, 2, 64, 48, 4, s3r.S3R_F32) == 0
+    # grows with the problem
+    a = s3r.speed3r_workspace_bytes(10992, 16, 64, 64, 16, s3r.S3R_BF16)
+    b = s3r.speed3r_workspace_bytes(137400, 16, 64, 64, 32, s3r.S3R_BF16)
+    assert a < b < big
+    # null / bad arguments are rejected before any device work
+    assert lib.speed3r_sparse_global_attn_ex(None) == s3r.S3R_ERR_INVALID_ARG
+    assert "null" in s3r.speed3r_last_error()
+    p = s3r.s3r_params()
+    p.n_tok, p.heads, p.head_dim, p.block, p.topk, p.dtype = 128, 2, 64, 64, 2, s3r.S3R_BF16
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_INVALID_ARG     # null q
+    p.head_dim = 32
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_UNSUPPORTED
+    p.head_dim, p.block = 64, 20
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_UNSUPPORTED
+    p.block, p.topk = 64, 0
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_INVALID_ARG
+    p.topk, p.dtype = 2, 7
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_UNSUPPORTED
+    # misaligned pointer (never dereferenced: validation comes first)
+    p.dtype = s3r.S3R_BF16
+    p.q = p.k = p.v = 0x1000
+    p.out = 0x2004
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_INVALID_ARG
+    assert "aligned" in s3r.speed3r_last_error()
+    p.out = 0x2000
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_WORKSPACE       # no workspace
+    assert lib.speed3r_topk_blocks(None, 8, None, 8, 1, 2, None) == s3r.S3R_ERR_INVALID_ARG
+    assert lib.speed3r_compress_attn_scores(0x1000, 0x1000, 0x1000, 0x1000, 6, 0x1000, 8, 1, 64, 0.0, 0,
+                                            None) == s3r.S3R_ERR_INVALID_ARG                  # ld_s < n_blk
+    assert lib.speed3r_set_kernel_choice(5) == s3r.S3R_ERR_INVALID_ARG
+    assert lib.speed3r_set_kernel_choice(0) == s3r.S3R_OK
+
+
+def test_binding_rejects_cpu_tensors(s3r):
+    import torch
+    q = torch.zeros((64, 1, 64), dtype=torch.bfloat16)
+    with pytest.raises(TypeError):
+        s3r.speed3r_sparse_global_attn(q, q, q, torch.empty_like(q), 64, 1, stream=0)
+
+
+def test_workloads_are_seeded_and_shaped():
+    import torch
+    from paper_2603_08055_amd import workloads
+    wl = workloads.config(1)
+    a = workloads.make_inputs(wl)
+    b = workloads.make_inputs(wl)
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+    assert a[0].shape == (1024, 2, 64) and a[0].dtype == torch.float32
+    assert abs(float(a[0].std()) - 0.125) < 0.01 and abs(float(a[1].std()) - 1.0) < 0.02
+    for i, (n_tok, n_blk) in enumerate([(1024, 16), (10992, 172), (137400, 2147), (1374000, 21469),
+                                        (410700, 3209)], start=1):
+        w = workloads.config(i)
+        assert (w.n_tok, w.n_blk) == (n_tok, n_blk)
+    small = workloads.config(3, views=2)
+    q, k, v = workloads.make_inputs(small)
+    assert q.dtype == torch.bfloat16 and q.shape == (2748, 16, 64)
+    # clustered keys: a block's mean stays close to unit norm (peaked block scores)
+    km = k.float()[:64, 0].mean(0)
+    assert 0.8 < float(km.norm()) < 1.2
+    o = workloads.make_inputs(workloads.config(5, views=1))[1].float()
+    hot = (o[:, 0].norm(dim=-1) > 20).float().mean()
+    assert 0.02 < float(hot) < 0.09

@@ -1,0 +1,296 @@
+"""GPU parity: the HIP path, called through the C ABI binding, against the fp64 CPU oracle on the
+same seeded inputs -- stage by stage and end to end.  Run with `-m gpu` on an MI355X."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_08055_amd import workloads
+from tests.parity_util import (TOL, assert_close, check_topk_sets, compare_with_oracle, log,
+                               rel_errors, run_device, to_host_f32)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def s3r():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2603_08055_amd import speed3r
+    speed3r.load()          # raises if libspeed3r.so is missing: there is no fallback
+    return speed3r
+
+
+def draw(n_tok, heads, dtype, seed, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    x = torch.randn((n_tok, heads, 64), generator=g) * scale
+    return x.to(torch.bfloat16 if dtype == "bf16" else torch.float32)
+
+
+# ------------------------------------------------------------------------------- stage: pool --
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_tok,block", [(1024, 64), (1000, 64), (333, 16), (333, 32), (700, 128),
+                                         (1, 64), (129, 128)])
+def test_pool_blocks(s3r, oracle, dtype, n_tok, block):
+    heads = 3
+    q, k, v = (draw(n_tok, heads, dtype, 100 + i) for i in range(3))
+    n_blk = (n_tok + block - 1) // block
+    outs = [torch.full((heads, n_blk, 64), float("nan"), device="cuda") for _ in range(3)]
+    s3r.speed3r_pool_blocks(q.cuda(), k.cuda(), v.cuda(), *outs, block)
+    torch.cuda.synchronize()
+    for x, got in zip((q, k, v), outs):
+        ref = oracle.pool(to_host_f32(x), block)
+        # fp32 accumulation of <= 128 terms: ~1e-7 of mean|x| absolute, far inside the fp32 output bound
+        assert_close(got.cpu().numpy(), ref, TOL["f32"], f"pool {dtype} n={n_tok} B={block}")
+        assert rel_errors(got.cpu().numpy(), ref)[1] <= 2e-6
+
+
+# --------------------------------------------------------------------- stage: compress/score --
+
+@pytest.mark.parametrize("n_blk,heads,accurate", [(16, 2, True), (172, 4, False), (172, 4, True),
+                                                  (300, 2, True), (1, 1, True), (33, 3, False),
+                                                  (2147, 2, False)])
+def test_compress_attn_scores(s3r, oracle, n_blk, heads, accurate):
+    rng = np.random.default_rng(7 + n_blk)
+    qc = (rng.standard_normal((heads, n_blk, 64)) * 0.5).astype(np.float32)
+    kc = (rng.standard_normal((heads, n_blk, 64)) * 0.5).astype(np.float32)
+    vc = rng.standard_normal((heads, n_blk, 64)).astype(np.float32)
+    ld_s = (n_blk + 3) // 4 * 4
+    s_dev = torch.full((heads, n_blk, ld_s), float("nan"), device="cuda")
+    oc_dev = torch.full((heads, n_blk, 64), float("nan"), device="cuda")
+    scale = 0.125
+    s3r.speed3r_compress_attn_scores(torch.from_numpy(qc).cuda(), torch.from_numpy(kc).cuda(),
+                                     torch.from_numpy(vc).cuda(), s_dev, oc_dev, scale, accurate)
+    torch.cuda.synchronize()
+    s_ref = oracle.scores(qc, kc)
+    oc_ref = oracle.compressed_attn(s_ref, vc, scale)
+    s_got = s_dev.cpu().numpy()[:, :, :n_blk]
+    # scores: hi/lo bf16 operand pairs -> error ~2^-16 of |q||k| per row/column pair
+    bound = 4e-5 * np.linalg.norm(qc, axis=2)[:, :, None] * np.linalg.norm(kc, axis=2)[:, None, :]
+    assert np.all(np.abs(s_got - s_ref) <= bound + 1e-7), float(np.max(np.abs(s_got - s_ref) / (bound + 1e-7)))
+    assert_close(oc_dev.cpu().numpy(), oc_ref, 1e-4 if accurate else 2e-2, f"o_comp n_blk={n_blk}")
+
+
+# ------------------------------------------------------------------------------- stage: topk --
+
+def topk_case(s3r, oracle, s_np, k):
+    heads, n_blk, _ = s_np.shape
+    ld_s = (n_blk + 3) // 4 * 4
+    s_dev = torch.zeros((heads, n_blk, ld_s), device="cuda")
+    s_dev[:, :, :n_blk] = torch.from_numpy(s_np).cuda()
+    s_dev[:, :, n_blk:] = 1e30          # the padding columns must never be selected
+    kk = min(k, n_blk)
+    idx = torch.full((heads, n_blk, kk), -1, dtype=torch.int32, device="cuda")
+    s3r.speed3r_topk_blocks(s_dev, idx, n_blk, k)
+    torch.cuda.synchronize()
+    ref = oracle.topk(s_np.astype(np.float64), kk)
+    assert np.array_equal(idx.cpu().numpy(), ref)       # integer work: bit-exact, ties included
+
+
+@pytest.mark.parametrize("n_blk,k", [(16, 4), (172, 16), (300, 1), (300, 300), (300, 1000), (257, 256),
+                                     (700, 300), (5, 3), (1, 1), (2147, 32), (4100, 64)])
+def test_topk_random_rows(s3r, oracle, n_blk, k):
+    rng = np.random.default_rng(n_blk * 31 + k)
+    heads = 2
+    rows = min(n_blk, 64)
+    s = rng.standard_normal((heads, n_blk, n_blk)).astype(np.float32)
+    s[:, rows:] = s[:, :1]              # keep the oracle's sort work small: repeat one row
+    topk_case(s3r, oracle, s, k)
+
+
+@pytest.mark.parametrize("n_blk,k", [(300, 16), (2000, 64), (2000, 300), (64, 64)])
+def test_topk_ties_and_degenerate_rows(s3r, oracle, n_blk, k):
+    rng = np.random.default_rng(n_blk + k)
+    s = np.zeros((1, n_blk, n_blk), dtype=np.float32)
+    s[0, 0] = 0.0                                               # all equal -> first k indices
+    s[0, 1] = rng.integers(0, 3, n_blk)                          # three distinct values, many ties
+    s[0, 2] = -np.arange(n_blk)                                  # descending: first k
+    s[0, 3] = np.arange(n_blk)                                   # ascending: last k
+    s[0, 4] = np.where(np.arange(n_blk) % 2 == 0, -0.0, 0.0)     # signed zeros compare equal
+    s[0, 5] = rng.integers(0, 2, n_blk) * 1e-30                  # tiny values
+    s[0, 6] = np.where(np.arange(n_blk) % 256 < 3, 5.0, rng.standard_normal(n_blk))  # stride-256 pattern
+    s[0, 7] = -np.abs(rng.standard_normal(n_blk)) * 1e20         # all negative, large
+    for r in range(8, n_blk):
+        s[0, r] = s[0, r % 8]
+    topk_case(s3r, oracle, s, k)
+
+
+# ----------------------------------------------------------------------------- stage: select --
+
+def select_case(s3r, oracle, dtype, n_tok, heads, block, kk, choice, with_gate, seed):
+    s3r.speed3r_set_kernel_choice(choice)
+    try:
+        q, k, v = (draw(n_tok, heads, dtype, seed + i, 1.0 if i else 0.7) for i in range(3))
+        n_blk = (n_tok + block - 1) // block
+        rng = np.random.default_rng(seed)
+        idx = np.stack([[np.sort(rng.choice(n_blk, kk, replace=False)) for _ in range(n_blk)]
+                        for _ in range(heads)]).astype(np.int32)
+        idx[:, 0, -1] = n_blk - 1                                    # make sure the tail block is used
+        idx[:, 0] = np.sort(idx[:, 0], axis=-1)
+        for h in range(heads):                                       # keep rows duplicate-free
+            if len(set(idx[h, 0])) < kk:
+                idx[h, 0] = np.arange(n_blk - kk, n_blk)
+        gate = draw(n_tok, heads, dtype, seed + 9) if with_gate else None
+        oc = torch.randn((heads, n_blk, 64), generator=torch.Generator().manual_seed(seed + 5))
+        out = torch.full_like(q, float("nan")).cuda()
+        o_sel = torch.full_like(q, float("nan")).cuda()
+        lse = torch.full((heads, n_tok), float("nan"), device="cuda")
+        s3r.speed3r_select_attn(q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(idx).cuda(), out, block,
+                                o_comp=oc.cuda(), gate_logits=None if gate is None else gate.cuda(),
+                                o_sel=o_sel, lse=lse)
+        torch.cuda.synchronize()
+        qf, kf, vf = (to_host_f32(x) for x in (q, k, v))
+        scale = 1 / math.sqrt(64)
+        ref_sel, ref_lse = oracle.select_attn(qf, kf, vf, block, idx, scale)
+        ref_out = oracle.merge(oc.numpy().astype(np.float64), ref_sel,
+                               None if gate is None else to_host_f32(gate), n_tok, block)
+        rows = np.arange(n_blk)
+        _, sel_v = oracle.rows_to_tokens(ref_sel, rows, n_tok, block)
+        _, out_v = oracle.rows_to_tokens(ref_out, rows, n_tok, block)
+        _, lse_v = oracle.rows_to_tokens(ref_lse.transpose(1, 2, 0), rows, n_tok, block)
+        tol = TOL[dtype]
+        label = f"select {dtype} n={n_tok} B={block} k={kk} choice={choice}"
+        assert_close(to_host_f32(o_sel), sel_v, tol, label + " o_sel")
+        assert_close(to_host_f32(out), out_v, tol, label + " out")
+        assert float(np.max(np.abs(lse.cpu().numpy().T - lse_v))) <= tol, label + " lse"
+    finally:
+        s3r.speed3r_set_kernel_choice(0)
+
+
+@pytest.mark.parametrize("block,n_tok,kk", [(64, 1024, 4), (64, 1000, 5), (128, 1100, 3), (64, 64, 1),
+                                            (128, 2000, 16), (64, 2500, 40)])
+@pytest.mark.parametrize("with_gate", [False, True])
+def test_select_attn_mfma_bf16(s3r, oracle, block, n_tok, kk, with_gate):
+    select_case(s3r, oracle, "bf16", n_tok, 3, block, kk, 0, with_gate, 1000 + n_tok)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("block,n_tok,kk", [(16, 200, 5), (32, 333, 4), (64, 1000, 5), (128, 700, 3)])
+def test_select_attn_generic(s3r, oracle, dtype, block, n_tok, kk):
+    select_case(s3r, oracle, dtype, n_tok, 2, block, kk, 1, True, 2000 + n_tok)
+
+
+# ------------------------------------------------------------------------------ stage: dense --
+
+@pytest.mark.parametrize("dtype,n_tok,choice", [("bf16", 1024, 0), ("bf16", 1000, 0), ("bf16", 300, 0),
+                                                ("bf16", 777, 1), ("f32", 1024, 0), ("f32", 500, 0)])
+def test_dense_attn(s3r, oracle, dtype, n_tok, choice):
+    s3r.speed3r_set_kernel_choice(choice)
+    try:
+        heads = 2
+        q, k, v = (draw(n_tok, heads, dtype, 3000 + i) for i in range(3))
+        out = torch.full_like(q, float("nan")).cuda()
+        lse = torch.full((heads, n_tok), float("nan"), device="cuda")
+        s3r.speed3r_dense_attn(q.cuda(), k.cuda(), v.cuda(), out, lse)
+        torch.cuda.synchronize()
+        ref, ref_lse = oracle.dense_attn(*(to_host_f32(x) for x in (q, k, v)), 0.125, want_lse=True)
+        assert_close(to_host_f32(out), ref, TOL[dtype], f"dense {dtype} n={n_tok}")
+        assert float(np.max(np.abs(lse.cpu().numpy() - ref_lse))) <= TOL[dtype]
+    finally:
+        s3r.speed3r_set_kernel_choice(0)
+
+
+# ------------------------------------------------------------------------------- end to end --
+
+def end_to_end(s3r, oracle, wl, rows=None, with_gate=False, device_gen="cpu", label=None):
+    label = label or wl.name
+    log(f"{label}: drawing inputs n_tok={wl.n_tok} heads={wl.heads} block={wl.block} topk={wl.topk}")
+    q, k, v = workloads.make_inputs(wl, device=device_gen)
+    gate = workloads.make_gate_logits(wl, device=device_gen) if with_gate else None
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    gd = None if gate is None else gate.cuda()
+    log(f"{label}: device path")
+    res = run_device(s3r, qd, kd, vd, wl.block, wl.topk, gate=gd)
+    log(f"{label}: oracle")
+    stats = compare_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v),
+                                None if gate is None else to_host_f32(gate), wl.block, wl.topk,
+                                wl.dtype, rows=rows, label=label)
+    log(f"{label}: {stats}")
+    return stats
+
+
+def test_config1_tiny_f32(s3r, oracle):
+    end_to_end(s3r, oracle, workloads.config(1))
+    end_to_end(s3r, oracle, workloads.config(1), with_gate=True, label="config1+gate")
+
+
+def test_config2_vggt_8_views(s3r, oracle):
+    end_to_end(s3r, oracle, workloads.config(2), with_gate=True)
+
+
+def test_config2_generic_kernels(s3r, oracle):
+    s3r.speed3r_set_kernel_choice(1)
+    try:
+        end_to_end(s3r, oracle, workloads.config(2, views=3), label="config2/3views/generic")
+    finally:
+        s3r.speed3r_set_kernel_choice(0)
+
+
+def test_config3_100_views_sampled_rows(s3r, oracle):
+    wl = workloads.config(3)
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 1, wl.n_blk - 2, wl.n_blk - 1], rng.choice(wl.n_blk, 44, replace=False)]))
+    end_to_end(s3r, oracle, wl, rows=rows, device_gen="cuda")
+
+
+@pytest.mark.parametrize("topk", [16, 128])
+def test_config5_pi3_block128_small(s3r, oracle, topk):
+    wl = workloads.config(5, views=12, topk=topk)
+    rng = np.random.default_rng(6)
+    rows = np.unique(np.concatenate([[0, wl.n_blk - 1], rng.choice(wl.n_blk, 22, replace=False)]))
+    end_to_end(s3r, oracle, wl, rows=rows, with_gate=(topk == 16))
+
+
+@pytest.mark.parametrize("n_tok,block,topk,dtype", [(1, 64, 4, "bf16"), (63, 64, 1, "bf16"), (65, 64, 2, "bf16"),
+                                                    (130, 128, 7, "bf16"), (100, 16, 3, "bf16"),
+                                                    (100, 32, 2, "f32"), (64, 64, 1, "f32"),
+                                                    (4097, 64, 1000, "bf16")])
+def test_edge_shapes(s3r, oracle, n_tok, block, topk, dtype):
+    wl = workloads.Workload(f"edge_{n_tok}_{block}_{topk}", 1, n_tok, 2, 64, dtype, block, topk, 77, "normal")
+    end_to_end(s3r, oracle, wl, with_gate=True)
+
+
+def test_full_topk_equals_dense_kernel(s3r, oracle):
+    """topk >= n_blk makes the selection branch dense attention: the sparse path's O_sel must agree
+    with the in-house dense kernel (and both with the oracle's dense attention)."""
+    wl = workloads.config(2, views=2, topk=10 ** 6)
+    q, k, v = (x.cuda() for x in workloads.make_inputs(wl))
+    res = run_device(s3r, q, k, v, wl.block, wl.topk)
+    dense = torch.empty_like(q)
+    s3r.speed3r_dense_attn(q, k, v, dense)
+    torch.cuda.synchronize()
+    ref = oracle.dense_attn(to_host_f32(q), to_host_f32(k), to_host_f32(v), 0.125)
+    assert_close(to_host_f32(res["o_sel"]), ref, TOL["bf16"], "o_sel with all blocks vs dense oracle")
+    assert_close(to_host_f32(dense), ref, TOL["bf16"], "dense kernel vs dense oracle")
+
+
+def test_deterministic_and_stream(s3r):
+    wl = workloads.config(2, views=2)
+    q, k, v = (x.cuda() for x in workloads.make_inputs(wl))
+    a = run_device(s3r, q, k, v, wl.block, wl.topk)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        b = run_device(s3r, q, k, v, wl.block, wl.topk)
+    st.synchronize()
+    for key in ("out", "idx", "lse", "o_comp", "o_sel"):
+        assert torch.equal(a[key], b[key]), key
+    out = torch.empty_like(q)
+    s3r.speed3r_sparse_global_attn(q, k, v, out, wl.block, wl.topk)      # short form, library scratch
+    torch.cuda.synchronize()
+    assert torch.equal(out, a["out"])
+
+
+def test_errors_on_device_arguments(s3r):
+    q = torch.zeros((128, 2, 64), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty_like(q)
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(s3r.Speed3rError) as e:
+        s3r.speed3r_sparse_global_attn_ex(q, q, q, out, 64, 2, workspace=ws)
+    assert e.value.status == s3r.S3R_ERR_WORKSPACE
+    with pytest.raises(s3r.Speed3rError) as e:
+        s3r.speed3r_sparse_global_attn_ex(q, q, q, out, 48, 2)
+    assert e.value.status == s3r.S3R_ERR_UNSUPPORTED
+    with pytest.raises(s3r.Speed3rError) as e:
+        s3r.speed3r_sparse_global_attn_ex(q, q, q, q, 64, 2)
+    assert e.value.status == s3r.S3R_ERR_INVALID_ARG
