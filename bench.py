@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse global attention path on one MI355X.
+
+A "step" is one pass of the whole path (pool -> S_guide + compressed attention -> TopK ->
+selection attention + merge) over one batch of synthetic Q/K/V that is already resident in HBM.
+Default workload: config 4, 1000 views x 1374 tokens, 16 heads, head_dim 64, bf16, block 64,
+top-64.  Prints ONE JSON line (see the design doc for the fields).  The in-house dense attention on the
+same inputs is timed once for the speed-up ratio, and the fp64 CPU oracle is timed on a bounded
+sample of the same workload as a reported baseline (cpu_baseline)."""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+PAPER_CONTEXT = {"speedup_end_to_end_model": 12.4, "views": 1024, "hardware": "1x NVIDIA H100",
+                 "note": "whole-model inference latency, pi3 backbone (Fig. 4); context, not a target"}
+
+
+def say(msg):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def valid_pairs(idx: torch.Tensor, n_tok: int, block: int) -> int:
+    """Number of (query token, key token) pairs the selection stage evaluates: executed work only."""
+    heads, n_blk, kk = idx.shape
+    lens = torch.full((n_blk,), block, dtype=torch.int64, device=idx.device)
+    lens[-1] = n_tok - (n_blk - 1) * block
+    keys = lens[idx.long()].sum(dim=-1)                      # [heads, n_blk] valid keys per query block
+    return int((keys * lens[None, :]).sum().item())
+
+
+def cpu_baseline(wl, q, k, v, idx_dev, budget_s: float):
+    """Times the fp64 oracle on the host: pooling in full, then scores / compressed attention /
+    TopK / selection / merge on as many sampled query blocks as fit the time budget; the per-block
+    time is extrapolated linearly to all blocks."""
+    from oracle import gsa_oracle
+    gsa_oracle.build()
+    say("cpu_baseline: copying inputs to the host")
+    qf, kf, vf = (t.cpu().to(torch.float32).numpy() for t in (q, k, v))
+    scale = 1.0 / math.sqrt(wl.head_dim)
+    t0 = time.perf_counter()
+    qc, kc, vc = gsa_oracle.pool(qf, wl.block), gsa_oracle.pool(kf, wl.block), gsa_oracle.pool(vf, wl.block)
+    t_pool = time.perf_counter() - t0
+    say(f"cpu_baseline: pooling (full) {t_pool:.2f} s")
+    rng = np.random.default_rng(0)
+    n_rows, t_rows, batch = 0, 0.0, 4
+    kk = min(wl.topk, wl.n_blk)
+    while t_rows + t_pool < budget_s and n_rows < wl.n_blk:
+        rows = np.sort(rng.choice(wl.n_blk, size=min(batch, wl.n_blk - n_rows), replace=False)).astype(np.int64)
+        t0 = time.perf_counter()
+        s = gsa_oracle.scores(qc, kc, rows)
+        oc = gsa_oracle.compressed_attn(s, vc, scale)
+        idx = gsa_oracle.topk(s, kk)
+        o_sel, _ = gsa_oracle.select_attn(qf, kf, vf, wl.block, idx, scale, rows)
+        gsa_oracle.merge(oc, o_sel, None, wl.n_tok, wl.block, rows)
+        dt = time.perf_counter() - t0
+        t_rows += dt
+        n_rows += rows.size
+        if dt < 2.0:
+            batch *= 2
+    est_total = t_pool + t_rows / max(n_rows, 1) * wl.n_blk
+    say(f"cpu_baseline: {n_rows} query blocks in {t_rows:.2f} s -> estimated full job {est_total:.1f} s")
+    return {"value": wl.n_tok / est_total, "unit": "tokens/s", "cores": gsa_oracle.threads(),
+            "kind": "oracle",
+            "sample": (f"pooling of all {wl.n_blk} blocks ({t_pool:.2f} s) + scores, compressed attention, "
+                       f"TopK, selection and merge on {n_rows} random query blocks x {wl.heads} heads "
+                       f"({t_rows:.2f} s), extrapolated linearly to all {wl.n_blk} query blocks"),
+            "estimated_full_job_s": est_total}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload (1..5); the metric is quoted on 4")
+    ap.add_argument("--views", type=int, default=None, help="override the number of views")
+    ap.add_argument("--topk", type=int, default=None)
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense denominator run")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget-s", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+
+    from paper_2603_08055_amd import speed3r as s3r
+    from paper_2603_08055_amd import workloads
+    s3r.load()
+    over = {}
+    if args.views is not None:
+        over["views"] = args.views
+    if args.topk is not None:
+        over["topk"] = args.topk
+    wl = workloads.config(args.config, **over)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    say(f"workload {wl.name}: n_tok={wl.n_tok} heads={wl.heads} block={wl.block} topk={wl.topk} {wl.dtype}")
+    q, k, v = workloads.make_inputs(wl, device=dev)
+    out = torch.empty_like(q)
+    kk = min(wl.topk, wl.n_blk)
+    idx = torch.empty((wl.heads, wl.n_blk, kk), dtype=torch.int32, device=dev)
+    dt_code = s3r.S3R_BF16 if wl.dtype == "bf16" else s3r.S3R_F32
+    ws_bytes = s3r.speed3r_workspace_bytes(wl.n_tok, wl.heads, wl.head_dim, wl.block, wl.topk, dt_code)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    say(f"workspace {ws_bytes / 2**30:.2f} GiB")
+
+    def step():
+        s3r.speed3r_sparse_global_attn_ex(q, k, v, out, wl.block, wl.topk, topk_idx=idx, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    s3r.speed3r_set_profiling(True)
+    s3r.speed3r_get_stage_ms()                       # clear anything recorded so far
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stage_ms, stage_n = s3r.speed3r_get_stage_ms()
+    s3r.speed3r_set_profiling(False)
+    ms_per_step = elapsed * 1e3 / args.steps
+    say(f"{ms_per_step:.3f} ms/step; per-stage ms/step: "
+        + ", ".join(f"{s}={stage_ms[s] / args.steps:.3f}" for s in ("pool", "split", "compress", "topk", "select")))
+
+    # roofline of the dominant kernel (selection attention, bf16 MFMA): executed FLOPs only
+    pairs = valid_pairs(idx, wl.n_tok, wl.block)
+    sel_flops = 4.0 * wl.head_dim * pairs
+    sel_ms = stage_ms["select"] / max(stage_n["select"], 1)
+    achieved = sel_flops / (sel_ms * 1e-3) / 1e12
+    roofline = {"kernel": "select_mfma_kernel" if wl.dtype == "bf16" and wl.block in (64, 128) else "select_generic_kernel",
+                "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "kernel_ms": sel_ms, "flops_per_launch": sel_flops}
+    # HBM-side figures of the two bandwidth-bound stages (algorithmic bytes / measured time)
+    e = 2 if wl.dtype == "bf16" else 4
+    pool_bytes = 3.0 * wl.n_tok * wl.heads * wl.head_dim * e + 3.0 * wl.n_blk * wl.heads * wl.head_dim * 4
+    topk_bytes = 4.0 * wl.n_blk * wl.n_blk * wl.heads + 4.0 * wl.n_blk * kk * wl.heads
+    hbm = {"pool_GBps": pool_bytes / (stage_ms["pool"] / args.steps * 1e-3) / 1e9,
+           "topk_GBps": topk_bytes / (stage_ms["topk"] / args.steps * 1e-3) / 1e9, "peak_GBps": 8000.0}
+
+    result = {
+        "metric": "sparse_global_attn_tokens_per_s", "value": wl.n_tok / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "views": wl.views, "tokens_per_view": wl.tokens_per_view,
+                   "n_tok": wl.n_tok, "heads": wl.heads, "head_dim": wl.head_dim, "block": wl.block,
+                   "topk": wl.topk, "kind": wl.kind, "seed": wl.seed},
+        "roofline": roofline,
+        "stage_ms_per_step": {s: stage_ms[s] / args.steps for s in ("pool", "split", "compress", "topk", "select")},
+        "stage_launches_per_step": {s: stage_n[s] / args.steps for s in ("pool", "split", "compress", "topk", "select")},
+        "hbm_stages": hbm,
+        "paper_context": PAPER_CONTEXT,
+    }
+
+    if not args.no_dense:
+        dense_out = torch.empty_like(q)
+        say("dense attention (same inputs), one timed run")
+        s3r.speed3r_set_profiling(True)
+        s3r.speed3r_get_stage_ms()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        s3r.speed3r_dense_attn(q, k, v, dense_out)
+        torch.cuda.synchronize()
+        dense_s = time.perf_counter() - t0
+        d_ms, _ = s3r.speed3r_get_stage_ms()
+        s3r.speed3r_set_profiling(False)
+        dense_flops = 4.0 * wl.head_dim * float(wl.n_tok) * float(wl.n_tok) * wl.heads
+        result["dense"] = {"ms": dense_s * 1e3, "kernel_ms": d_ms["dense"], "relayout_ms": d_ms["pool"],
+                           "tflops": dense_flops / (d_ms["dense"] * 1e-3) / 1e12,
+                           "mfma_frac": dense_flops / (d_ms["dense"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        result["speedup_vs_dense"] = dense_s * 1e3 / ms_per_step
+        say(f"dense {dense_s * 1e3:.1f} ms -> speed-up {result['speedup_vs_dense']:.1f}x")
+        del dense_out
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, q, k, v, idx, args.cpu_budget_s)
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

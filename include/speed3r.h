@@ -143,11 +143,12 @@ s3r_status speed3r_select_attn(const void *q, const void *k, const void *v, cons
 /* ---- utilities ------------------------------------------------------------------------------ */
 
 /* When enabled, every entry point brackets each kernel launch with HIP events on the call's own
- * stream and keeps them for speed3r_get_stage_ms (process-wide switch; default off). */
+ * stream and keeps them until speed3r_get_stage_ms reads them (process-wide switch; default off). */
 s3r_status speed3r_set_profiling(int enable);
 
 /* Host arrays of S3R_N_STAGES entries: summed kernel milliseconds and number of launches per
- * stage of the most recent profiled entry-point call.  Waits for that call's events. */
+ * stage over all profiled calls since the previous speed3r_get_stage_ms (or since profiling was
+ * switched on); the record is cleared.  Waits for the recorded events, so call it after the work. */
 s3r_status speed3r_get_stage_ms(float *ms, int *launches);
 
 /* Selects the selection/dense kernel family: 0 = automatic (MFMA kernels for bf16 with block 64

@@ -24,7 +24,7 @@ __global__ __launch_bounds__(NWAVES * 64) void select_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ kb, const bf16_t *__restrict__ vb,
     const int32_t *__restrict__ idx, const float *__restrict__ o_comp, const bf16_t *__restrict__ gate,
     bf16_t *__restrict__ out, bf16_t *__restrict__ o_sel, float *__restrict__ lse, int64_t n_tok,
-    int64_t n_blk, int heads, int kk, float scale_log2)
+    int64_t n_blk, int heads, int kk, float scale_log2, int64_t group_offset)
 {
     constexpr int NT = B / 32;             // 32-key MFMA tiles per key block
     constexpr int TILE = B * 64;           // elements of one K (or V) tile
@@ -36,7 +36,7 @@ __global__ __launch_bounds__(NWAVES * 64) void select_mfma_kernel(
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5;
     const int64_t bid = blockIdx.x;
     const int h = static_cast<int>(bid % heads);
-    const int64_t qgroup = bid / heads;                       // query block (selection) / row group
+    const int64_t qgroup = bid / heads + group_offset;        // query block (selection) / row group
     const int64_t t = qgroup * (32 * NWAVES) + wave * 32 + (lane & 31);
     const bool row_valid = t < n_tok;
 
@@ -193,15 +193,27 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
 {
     const int64_t rows_per_wg = 32 * NWAVES;
     const int64_t groups = DENSE ? (a.n_tok + rows_per_wg - 1) / rows_per_wg : a.n_blk;
-    const int64_t grid = groups * a.heads;
-    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((select_mfma_kernel<B, NWAVES, DENSE>), dim3(static_cast<unsigned>(grid)),
-                       dim3(NWAVES * 64), 0, stream, static_cast<const bf16_t *>(a.q),
-                       static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
-                       a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
-                       static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.kk,
-                       a.scale * kLog2e);
-    return hipGetLastError();
+    // Dense attention is quadratic: keep each launch to roughly 2e14 FLOP (a fraction of a second)
+    // so that no single kernel occupies the GPU for seconds.
+    int64_t per_launch = groups;
+    if (DENSE) {
+        const double flops_per_group = 4.0 * 64.0 * rows_per_wg * static_cast<double>(a.n_tok) * a.heads;
+        per_launch = static_cast<int64_t>(2e14 / flops_per_group);
+        if (per_launch < 1) per_launch = 1;
+    }
+    if (per_launch * a.heads > 0x7fffffffLL) return hipErrorInvalidValue;
+    for (int64_t g0 = 0; g0 < groups; g0 += per_launch) {
+        const int64_t ng = (groups - g0 < per_launch) ? groups - g0 : per_launch;
+        hipLaunchKernelGGL((select_mfma_kernel<B, NWAVES, DENSE>), dim3(static_cast<unsigned>(ng * a.heads)),
+                           dim3(NWAVES * 64), 0, stream, static_cast<const bf16_t *>(a.q),
+                           static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
+                           a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
+                           static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.kk,
+                           a.scale * kLog2e, g0);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)

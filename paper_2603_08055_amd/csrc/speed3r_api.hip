@@ -126,7 +126,7 @@ s3r_status scratch_get(size_t bytes, void **out)
 // ---- per-stage event timing ------------------------------------------------------------------
 bool g_profiling = false;
 struct Span { int stage; hipEvent_t start, stop; };
-std::vector<Span> g_spans;        // spans of the most recent profiled call
+std::vector<Span> g_spans;        // spans recorded since the last speed3r_get_stage_ms
 std::vector<hipEvent_t> g_pool;   // recycled events
 
 hipEvent_t event_take()
@@ -135,14 +135,6 @@ hipEvent_t event_take()
     hipEvent_t e = nullptr;
     if (hipEventCreate(&e) != hipSuccess) return nullptr;
     return e;
-}
-
-void spans_reset()
-{
-    if (!g_profiling) return;
-    std::lock_guard<std::mutex> lock(g_mu);
-    for (auto &s : g_spans) { g_pool.push_back(s.start); g_pool.push_back(s.stop); }
-    g_spans.clear();
 }
 
 struct StageTimer {
@@ -239,6 +231,8 @@ s3r_status speed3r_get_stage_ms(float *ms, int *launches)
         ms[s.stage] += t;
         launches[s.stage] += 1;
     }
+    for (auto &s : g_spans) { g_pool.push_back(s.start); g_pool.push_back(s.stop); }
+    g_spans.clear();
     return S3R_OK;
 }
 
@@ -296,7 +290,6 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     void *kb = mfma ? at(ws, L.kb) : nullptr;
     void *vb = mfma ? at(ws, L.vb) : nullptr;
 
-    spans_reset();
     {
         StageTimer tm(S3R_STAGE_POOL, stream);
         S3R_HIP(s3r::launch_pool(p->q, p->k, p->v, qc, kc, vc, kb, vb, p->n_tok, p->heads, p->block, is_bf16, stream),
@@ -341,7 +334,6 @@ s3r_status speed3r_pool_blocks(const void *q, const void *k, const void *v, floa
     if (st != S3R_OK) return st;
     if (!q || !k || !v || !qc || !kc || !vc) return fail(S3R_ERR_INVALID_ARG, "all six tensors must be non-null");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
-    spans_reset();
     StageTimer tm(S3R_STAGE_POOL, static_cast<hipStream_t>(stream));
     S3R_HIP(s3r::launch_pool(q, k, v, qc, kc, vc, nullptr, nullptr, n_tok, heads, block, dtype == S3R_BF16,
                              static_cast<hipStream_t>(stream)),
@@ -365,7 +357,6 @@ s3r_status speed3r_compress_attn_scores(const float *qc, const float *kc, const 
     if (st != S3R_OK) return st;
     void *tile[6];
     for (int a = 0; a < 6; ++a) tile[a] = at(ws, a * arr);
-    spans_reset();
     return run_compress_topk(qc, kc, vc, tile, s_guide, ld_s, heads, o_comp, nullptr, n_blk, tiles, heads, 0,
                              resolve_scale(softmax_scale, head_dim), accurate_pv != 0, false,
                              static_cast<hipStream_t>(stream));
@@ -379,7 +370,6 @@ s3r_status speed3r_topk_blocks(const float *s_guide, int64_t ld_s, int32_t *idx,
     if (ld_s < n_blk) return fail(S3R_ERR_INVALID_ARG, "ld_s must be >= n_blk");
     if (n_blk * heads > 0x7fffffffLL) return fail(S3R_ERR_UNSUPPORTED, "n_blk * heads exceeds 2^31 - 1");
     const int kk = static_cast<int>(topk < n_blk ? topk : n_blk);
-    spans_reset();
     StageTimer tm(S3R_STAGE_TOPK, static_cast<hipStream_t>(stream));
     S3R_HIP(s3r::launch_topk(s_guide, ld_s, idx, n_blk, n_blk * heads, kk, static_cast<hipStream_t>(stream)),
             "topk kernel launch");
@@ -402,7 +392,6 @@ s3r_status speed3r_select_attn(const void *q, const void *k, const void *v, cons
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool mfma = mfma_ok(dtype, block);
     s3r::SelectArgs a{};
-    spans_reset();
     if (mfma) {
         const size_t blocked = align_up(static_cast<size_t>(heads) * n_blk * block * 64 * 2);
         void *ws = nullptr;
@@ -436,7 +425,6 @@ s3r_status speed3r_dense_attn(const void *q, const void *k, const void *v, void 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool mfma = mfma_ok(dtype, block);
     s3r::SelectArgs a{};
-    spans_reset();
     if (mfma) {
         const size_t blocked = align_up(static_cast<size_t>(heads) * n_blk * block * 64 * 2);
         void *ws = nullptr;

@@ -209,7 +209,8 @@ def speed3r_set_profiling(enable: bool):
 
 
 def speed3r_get_stage_ms():
-    """(ms, launches) dictionaries keyed by stage name for the last profiled call."""
+    """(ms, launches) dictionaries keyed by stage name, summed over the profiled calls since the
+    previous read."""
     ms = (_flt * len(STAGES))()
     n = (_int * len(STAGES))()
     _check(load().speed3r_get_stage_ms(ms, n))
