@@ -234,6 +234,26 @@ def test_config3_100_views_sampled_rows(s3r, oracle):
     end_to_end(s3r, oracle, wl, rows=rows, device_gen="cuda")
 
 
+@pytest.mark.timeout(600)
+def test_config4_1000_views_full_size_sampled_rows(s3r, oracle):
+    """The benchmark workload at full size, in the launch configuration bench.py times (caller
+    workspace, S_guide in head chunks): TopK sets and outputs of sampled query blocks, first and
+    last (ragged) blocks included, against the oracle."""
+    wl = workloads.config(4)
+    rng = np.random.default_rng(8)
+    rows = np.unique(np.concatenate([[0, 1, wl.n_blk - 2, wl.n_blk - 1], rng.choice(wl.n_blk, 20, replace=False)]))
+    end_to_end(s3r, oracle, wl, rows=rows, device_gen="cuda")
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("topk", [32, 64])
+def test_config5_pi3_300_views_full_size_sampled_rows(s3r, oracle, topk):
+    wl = workloads.config(5, topk=topk)
+    rng = np.random.default_rng(9)
+    rows = np.unique(np.concatenate([[0, wl.n_blk - 1], rng.choice(wl.n_blk, 14, replace=False)]))
+    end_to_end(s3r, oracle, wl, rows=rows, device_gen="cuda")
+
+
 @pytest.mark.parametrize("topk", [16, 128])
 def test_config5_pi3_block128_small(s3r, oracle, topk):
     wl = workloads.config(5, views=12, topk=topk)
