@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense denominator run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget-s", type=float, default=20.0)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel (a known-size reference "
+                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -119,6 +122,12 @@ def main():
     def step():
         s3r.speed3r_sparse_global_attn_ex(q, k, v, out, wl.block, wl.topk, topk_idx=idx, workspace=ws)
 
+    if args.pmc_calibration:
+        src = torch.ones(2 ** 29, dtype=torch.bfloat16, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -12,6 +12,7 @@
 // ds_read_b128 per MFMA operand.
 #include "s3r_device.h"
 #include "s3r_kernels.h"
+#include <cstdlib>
 
 namespace s3r {
 
@@ -24,7 +25,7 @@ __global__ __launch_bounds__(NWAVES * 64) void select_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ kb, const bf16_t *__restrict__ vb,
     const int32_t *__restrict__ idx, const float *__restrict__ o_comp, const bf16_t *__restrict__ gate,
     bf16_t *__restrict__ out, bf16_t *__restrict__ o_sel, float *__restrict__ lse, int64_t n_tok,
-    int64_t n_blk, int heads, int kk, float scale_log2, int64_t group_offset)
+    int64_t n_blk, int heads, int kk, float scale_log2, int64_t group_offset, int64_t n_groups, int map_mode)
 {
     constexpr int NT = B / 32;             // 32-key MFMA tiles per key block
     constexpr int TILE = B * 64;           // elements of one K (or V) tile
@@ -35,8 +36,25 @@ __global__ __launch_bounds__(NWAVES * 64) void select_mfma_kernel(
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5;
     const int64_t bid = blockIdx.x;
-    const int h = static_cast<int>(bid % heads);
-    const int64_t qgroup = bid / heads + group_offset;        // query block (selection) / row group
+    int h;
+    int64_t qgroup;
+    if (map_mode == 0) {
+        h = static_cast<int>(bid % heads);
+        qgroup = bid / heads + group_offset;        // query block (selection) / row group
+    } else if (map_mode == 1) {
+        const int64_t total = n_groups * heads, per = (total + 7) / 8;
+        const int64_t id = (bid % 8) * per + bid / 8;
+        if (id >= total) return;
+        h = static_cast<int>(id / n_groups);
+        qgroup = id % n_groups + group_offset;
+    } else {
+        const int64_t per = (n_groups + 7) / 8;
+        h = static_cast<int>(bid / (8 * per));
+        const int64_t r = bid % (8 * per);
+        const int64_t g_in = (r % 8) * per + r / 8;
+        if (g_in >= n_groups) return;
+        qgroup = g_in + group_offset;
+    }
     const int64_t t = qgroup * (32 * NWAVES) + wave * 32 + (lane & 31);
     const bool row_valid = t < n_tok;
 
@@ -201,15 +219,20 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
         per_launch = static_cast<int64_t>(2e14 / flops_per_group);
         if (per_launch < 1) per_launch = 1;
     }
-    if (per_launch * a.heads > 0x7fffffffLL) return hipErrorInvalidValue;
+    if ((per_launch + 8) * a.heads > 0x7fffffffLL) return hipErrorInvalidValue;
+    const char *mm = getenv("S3R_SELECT_MAP");
+    const int map_mode = mm ? atoi(mm) : 0;
     for (int64_t g0 = 0; g0 < groups; g0 += per_launch) {
         const int64_t ng = (groups - g0 < per_launch) ? groups - g0 : per_launch;
-        hipLaunchKernelGGL((select_mfma_kernel<B, NWAVES, DENSE>), dim3(static_cast<unsigned>(ng * a.heads)),
+        int64_t grid = ng * a.heads;
+        if (map_mode == 1) grid = (grid + 7) / 8 * 8;
+        if (map_mode == 2) grid = (ng + 7) / 8 * 8 * a.heads;
+        hipLaunchKernelGGL((select_mfma_kernel<B, NWAVES, DENSE>), dim3(static_cast<unsigned>(grid)),
                            dim3(NWAVES * 64), 0, stream, static_cast<const bf16_t *>(a.q),
                            static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
                            a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
                            static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.kk,
-                           a.scale * kLog2e, g0);
+                           a.scale * kLog2e, g0, ng, map_mode);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -2,18 +2,24 @@
 // indices of its k largest entries, equal scores resolved towards the smaller index, written in
 // ascending index order.  Integer output, deterministic (no result depends on atomic ordering).
 //
-// One 256-thread workgroup per row.  Fast path (k <= 256): the k-th largest of the 256 per-thread
-// maxima is a lower bound of the row's k-th largest value, so a second sweep (served by L2 / MALL)
-// keeps only the few entries at or above it; exact ranks are then resolved among those candidates
-// in LDS.  Rows that defeat the bound (long runs of equal values, adversarial layouts) or k > 256
-// take an exact bitwise threshold search plus an ordered compaction.  HBM-bound: one read of S.
+// One 256-thread workgroup per row, HBM-bound by design: S is read once.
+//  * topk_reg_kernel<NV> (rows of up to 32768 entries, k <= 256): the row is loaded once into
+//    registers, each wave owning a contiguous quarter.  The k-th largest of the 256 per-lane maxima
+//    is a lower bound of the row's k-th largest value; entries at or above it (typically ~1.2 k of
+//    them) are appended to LDS in index order with wave ballots; one wave then finds the exact k-th
+//    largest candidate by a bitwise search with ballots and writes the winners, already in order.
+//  * topk_stream_kernel (any row length, any k): same idea with two sweeps over global memory and
+//    rank counting, plus the exact path below.
+//  * exact path (rows that defeat the bound, e.g. long runs of equal values; k > 256): bitwise
+//    search of the k-th largest order-preserving key over the whole row, then an ordered
+//    ballot/popcount compaction.
 #include "s3r_device.h"
 #include "s3r_kernels.h"
 
 namespace s3r {
 
 constexpr int kTopkThreads = 256;
-constexpr int kTopkCap = 1024;  // candidate slots of the fast path
+constexpr int kTopkCap = 1024;  // candidate slots of the streaming fast path
 
 // Monotone map float -> uint32 (larger float <=> larger key); -0.0 is folded onto +0.0 first so
 // that equal scores compare equal.
@@ -35,7 +41,199 @@ __device__ __forceinline__ int block_sum(int v, int *scratch /*[4]*/)
     return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
-__global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restrict__ s_guide,
+__device__ __forceinline__ int lanes_below(unsigned long long mask)
+{
+    // number of set bits of `mask` below the calling lane
+    return __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));
+}
+
+// Exact selection over the whole row, all 256 threads: T = k-th largest key by a bitwise search,
+// then ordered compaction (entries above T, then the first ties at T in index order).
+__device__ void topk_exact_path(const float *__restrict__ row, int32_t *__restrict__ out, int n_blk, int k,
+                                int *scratch /*[4]*/, int (*wave_cnt)[4] /*[2][4]*/)
+{
+    const int tid = threadIdx.x;
+    uint32_t T = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t trial = T | (1u << bit);
+        int cnt = 0;
+        for (int j = tid; j < n_blk; j += kTopkThreads) cnt += order_key(row[j]) >= trial;
+        if (block_sum(cnt, scratch) >= k) T = trial;
+    }
+    int cnt_gt = 0;
+    for (int j = tid; j < n_blk; j += kTopkThreads) cnt_gt += order_key(row[j]) > T;
+    const int need_eq = k - block_sum(cnt_gt, scratch);  // ties at T to keep, smallest indices first
+
+    const int lane = tid & 63, wave = tid >> 6;
+    int base_sel = 0, base_eq = 0;
+    for (int j0 = 0; j0 < n_blk; j0 += kTopkThreads) {
+        const int j = j0 + tid;
+        uint32_t key = 0u;
+        const bool in = j < n_blk;
+        if (in) key = order_key(row[j]);
+        const bool eq = in && key == T, gtr = in && key > T;
+        const unsigned long long eq_mask = __ballot(eq);
+        if (lane == 0) wave_cnt[0][wave] = __popcll(eq_mask);
+        __syncthreads();
+        int eq_before = base_eq + lanes_below(eq_mask);
+        int eq_total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) eq_before += wave_cnt[0][w];
+            eq_total += wave_cnt[0][w];
+        }
+        const bool sel = gtr || (eq && eq_before < need_eq);
+        const unsigned long long sel_mask = __ballot(sel);
+        if (lane == 0) wave_cnt[1][wave] = __popcll(sel_mask);
+        __syncthreads();
+        int pos = base_sel + lanes_below(sel_mask);
+        int sel_total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) pos += wave_cnt[1][w];
+            sel_total += wave_cnt[1][w];
+        }
+        if (sel) out[pos] = j;
+        base_sel += sel_total;
+        base_eq += eq_total;
+        __syncthreads();
+    }
+}
+
+// NV = maximum row entries per lane; the four waves own equal contiguous shares of the row.
+// Requires n_blk <= NV * 256 and k <= 256.
+template <int NV>
+__global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float *__restrict__ s_guide, int64_t ld_s,
+                                                                 int32_t *__restrict__ idx, int n_blk, int k)
+{
+    constexpr int CAPW = 256;  // candidate slots per wave
+    __shared__ uint32_t lane_max[kTopkThreads];
+    __shared__ uint32_t cand_key[4][CAPW];
+    __shared__ int32_t cand_idx[4][CAPW];
+    __shared__ int n_w[4];
+    __shared__ uint32_t thr_sh;
+    __shared__ int scratch[4];
+    __shared__ int wave_cnt[2][4];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const float *row = s_guide + static_cast<int64_t>(blockIdx.x) * ld_s;
+    int32_t *out = idx + static_cast<int64_t>(blockIdx.x) * k;
+    // equal shares: each wave owns wave_len consecutive entries (a multiple of 64, <= NV * 64)
+    const int wave_len = ((n_blk + 3) / 4 + 63) / 64 * 64;
+    const int wave_base = __builtin_amdgcn_readfirstlane(wave) * wave_len;
+    const int wave_end = (wave_base + wave_len < n_blk) ? wave_base + wave_len : n_blk;
+    const int base = wave_base + lane;
+    const int leader = blockIdx.x & 3;  // the wave that does the serial parts rotates with the row
+
+    // Entries past the end of the row are NaN: v_max ignores them and every ordered compare fails.
+    float x[NV];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        if (wave_base + i * 64 + 64 <= wave_end) {  // wave-uniform: the 64 entries of this step all exist
+            x[i] = row[base + i * 64];
+        } else if (wave_base + i * 64 >= wave_end) {  // wave-uniform: none exists
+            x[i] = __builtin_nanf("");
+        } else {
+            const int j = base + i * 64;
+            const float v = row[j < wave_end ? j : wave_end - 1];  // clamped address, then masked
+            x[i] = (j < wave_end) ? v : __builtin_nanf("");
+        }
+        mx = fmaxf(mx, x[i]);
+    }
+    lane_max[tid] = order_key(mx);
+    __syncthreads();
+    if (wave == leader) {
+        // k-th largest of the 256 lane maxima: at least k row entries are >= it
+        const uint32_t m0 = lane_max[lane], m1 = lane_max[lane + 64], m2 = lane_max[lane + 128],
+                       m3 = lane_max[lane + 192];
+        uint32_t T = 0u;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t trial = T | (1u << bit);
+            const int c = __popcll(__ballot(m0 >= trial)) + __popcll(__ballot(m1 >= trial)) +
+                          __popcll(__ballot(m2 >= trial)) + __popcll(__ballot(m3 >= trial));
+            if (c >= k) T = trial;
+        }
+        if (lane == 0) thr_sh = T;
+    }
+    __syncthreads();
+    // The threshold as a float: x >= thr_f  <=>  order_key(x) >= thr (signed zeros compare equal
+    // either way; the key of -inf, reached only when fewer than k lanes hold data, maps back to -inf).
+    const uint32_t thr = thr_sh;
+    const float thr_f = __uint_as_float((thr & 0x80000000u) ? (thr & 0x7fffffffu) : ~thr);
+    int cnt = 0;
+    constexpr int GRP = (NV % 4 == 0) ? 4 : 1;
+#pragma unroll
+    for (int i0 = 0; i0 < NV; i0 += GRP) {
+        bool any = false;
+#pragma unroll
+        for (int i = i0; i < i0 + GRP; ++i) any = any || (x[i] >= thr_f);
+        if (__ballot(any) == 0ull) continue;  // wave-uniform: most groups hold no candidate
+#pragma unroll
+        for (int i = i0; i < i0 + GRP; ++i) {
+            const bool flag = x[i] >= thr_f;
+            const unsigned long long mask = __ballot(flag);
+            const int pos = cnt + lanes_below(mask);
+            if (flag && pos < CAPW) {
+                cand_key[wave][pos] = order_key(x[i]);
+                cand_idx[wave][pos] = base + i * 64;
+            }
+            cnt += __popcll(mask);
+        }
+    }
+    if (lane == 0) n_w[wave] = cnt;
+    __syncthreads();
+    const int n0 = n_w[0], n1 = n_w[1], n2 = n_w[2], n3 = n_w[3];
+    if (n0 > CAPW || n1 > CAPW || n2 > CAPW || n3 > CAPW) {  // uniform over the workgroup
+        topk_exact_path(row, out, n_blk, k, scratch, wave_cnt);
+        return;
+    }
+    if (wave != leader) return;
+
+    // Leader wave: exact k-th largest among the candidates (all entries >= thr, at least k of them).
+    const int nws[4] = {n0, n1, n2, n3};
+    uint32_t ck[4][CAPW / 64];
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int s = 0; s < CAPW / 64; ++s) ck[w][s] = (s * 64 + lane < nws[w]) ? cand_key[w][s * 64 + lane] : 0u;
+    uint32_t T = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t trial = T | (1u << bit);
+        int c = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int s = 0; s < CAPW / 64; ++s)
+                if (s * 64 < nws[w]) c += __popcll(__ballot(ck[w][s] >= trial));
+        if (c >= k) T = trial;
+    }
+    int cnt_gt = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int s = 0; s < CAPW / 64; ++s)
+            if (s * 64 < nws[w]) cnt_gt += __popcll(__ballot(ck[w][s] > T));
+    const int need_eq = k - cnt_gt;
+    int base_sel = 0, base_eq = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int s = 0; s < CAPW / 64; ++s) {
+            if (s * 64 >= nws[w]) continue;
+            const bool valid = s * 64 + lane < nws[w];
+            const bool eq = valid && ck[w][s] == T, gtr = valid && ck[w][s] > T;
+            const unsigned long long eq_mask = __ballot(eq);
+            const bool sel = gtr || (eq && base_eq + lanes_below(eq_mask) < need_eq);
+            const unsigned long long sel_mask = __ballot(sel);
+            if (sel) out[base_sel + lanes_below(sel_mask)] = cand_idx[w][s * 64 + lane];
+            base_sel += __popcll(sel_mask);
+            base_eq += __popcll(eq_mask);
+        }
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(const float *__restrict__ s_guide,
                                                              int64_t ld_s, int32_t *__restrict__ idx,
                                                              int n_blk, int k)
 {
@@ -107,61 +305,32 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float *__restr
         }
     }
 
-    // Exact path: T = k-th largest key by a bitwise search, then ordered compaction.
-    uint32_t T = 0u;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t trial = T | (1u << bit);
-        int cnt = 0;
-        for (int j = tid; j < n_blk; j += kTopkThreads) cnt += order_key(row[j]) >= trial;
-        if (block_sum(cnt, scratch) >= k) T = trial;
-    }
-    int cnt_gt = 0;
-    for (int j = tid; j < n_blk; j += kTopkThreads) cnt_gt += order_key(row[j]) > T;
-    const int need_eq = k - block_sum(cnt_gt, scratch);  // ties at T to keep, smallest indices first
-
-    const int lane = tid & 63, wave = tid >> 6;
-    int base_sel = 0, base_eq = 0;
-    for (int j0 = 0; j0 < n_blk; j0 += kTopkThreads) {
-        const int j = j0 + tid;
-        uint32_t key = 0u;
-        const bool in = j < n_blk;
-        if (in) key = order_key(row[j]);
-        const bool eq = in && key == T, gtr = in && key > T;
-        const unsigned long long eq_mask = __ballot(eq);
-        const unsigned long long below = (1ull << lane) - 1ull;
-        if (lane == 0) wave_cnt[0][wave] = __popcll(eq_mask);
-        __syncthreads();
-        int eq_before = base_eq + __popcll(eq_mask & below);
-        int eq_total = 0;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            if (w < wave) eq_before += wave_cnt[0][w];
-            eq_total += wave_cnt[0][w];
-        }
-        const bool sel = gtr || (eq && eq_before < need_eq);
-        const unsigned long long sel_mask = __ballot(sel);
-        if (lane == 0) wave_cnt[1][wave] = __popcll(sel_mask);
-        __syncthreads();
-        int pos = base_sel + __popcll(sel_mask & below);
-        int sel_total = 0;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            if (w < wave) pos += wave_cnt[1][w];
-            sel_total += wave_cnt[1][w];
-        }
-        if (sel) out[pos] = j;
-        base_sel += sel_total;
-        base_eq += eq_total;
-        __syncthreads();
-    }
+    topk_exact_path(row, out, n_blk, k, scratch, wave_cnt);
 }
 
 hipError_t launch_topk(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t n_blk,
                        int64_t n_rows, int k, hipStream_t stream)
 {
     if (n_rows > 0x7fffffffLL || n_blk > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(topk_kernel, dim3(static_cast<unsigned>(n_rows)), dim3(kTopkThreads), 0, stream,
-                       s_guide, ld_s, idx, static_cast<int>(n_blk), k);
+    const dim3 grid(static_cast<unsigned>(n_rows)), block(kTopkThreads);
+    const int nb = static_cast<int>(n_blk);
+#define S3R_TOPK_REG(NV)                                                                            \
+    if (k <= kTopkThreads && nb <= (NV) * 256) {                                                    \
+        hipLaunchKernelGGL(topk_reg_kernel<NV>, grid, block, 0, stream, s_guide, ld_s, idx, nb, k); \
+        return hipGetLastError();                                                                   \
+    }
+    S3R_TOPK_REG(1)
+    S3R_TOPK_REG(2)
+    S3R_TOPK_REG(4)
+    S3R_TOPK_REG(8)
+    S3R_TOPK_REG(16)
+    S3R_TOPK_REG(32)
+    S3R_TOPK_REG(48)
+    S3R_TOPK_REG(64)
+    S3R_TOPK_REG(96)
+    S3R_TOPK_REG(128)
+#undef S3R_TOPK_REG
+    hipLaunchKernelGGL(topk_stream_kernel, grid, block, 0, stream, s_guide, ld_s, idx, nb, k);
     return hipGetLastError();
 }
 
