@@ -15,7 +15,7 @@
 namespace s3r {
 
 template <bool SPLIT_PV>
-__global__ __launch_bounds__(256) void compress_kernel(
+__global__ __launch_bounds__(256, 2) void compress_kernel(
     const bf16_t *__restrict__ qs_hi, const bf16_t *__restrict__ qs_lo,
     const bf16_t *__restrict__ ks_hi, const bf16_t *__restrict__ ks_lo,
     const bf16_t *__restrict__ vt_hi, const bf16_t *__restrict__ vt_lo, float *__restrict__ s_guide,
