@@ -1,33 +1,41 @@
 // Selection attention + merge (Sec. 3.2 eq. 6, supplementary Alg. 2; eqs. 5, 7, 8) and dense
 // attention (eq. 2 form) on bf16 MFMA for gfx950.
 //
-// Layout of the work: a wave owns 32 query rows and keeps their Q operands in registers for the
-// whole item.  Per selected key block it computes the TRANSPOSED score tile S^T[key][query] =
-// K_j Q^T with v_mfma_f32_32x32x16_bf16 (A = K tile from LDS, B = Q^T registers), so a lane holds
-// keys of ONE query: the online-softmax row max / row sum are in-lane reductions plus one
-// exchange with the lane 32 positions away, and the probabilities already sit in the register
-// order of the B operand of the next MFMA, O^T = V^T P^T (A = V^T tile from LDS).
-// K and V tiles come from the operand-order copies written by the pooling kernel: each tile is one
-// contiguous run in HBM, copied to LDS as is, read back with one conflict-free ds_read_b128 per
-// MFMA operand.
+// Work layout.  A wave owns 32 query rows and keeps their Q operands in registers.  Keys are
+// processed in UNITS of 64 tokens (one key block of 64, or half a key block of 128).  Per unit the
+// wave computes the TRANSPOSED score tile S^T[key][query] = K Q^T with v_mfma_f32_32x32x16_bf16
+// (A = K rows from LDS, B = Q^T registers), so a lane holds keys of ONE query: the online-softmax
+// row max / row sum are in-lane reductions plus one exchange with the lane 32 positions away, and
+// the probabilities already sit in the register order of the B operand of the next MFMA,
+// O^T = V^T P^T (A = V^T from LDS).
 //
-// The gather of 16 KiB tiles is latency-bound unless several tiles per workgroup are in flight, so
-// tiles travel HBM -> registers -> LDS through a ring of NPF register sets: while tile a is being
-// multiplied out of LDS, tiles a+1 .. a+NPF are in flight (the register file, 512 KiB per CU, is
-// the deep buffer; LDS holds two tiles).
-// The running row maximum is only raised when a tile exceeds it by more than kRescaleSlack (in
-// log2 units), so the rescale of the output accumulators is skipped for almost every tile;
-// probabilities then range up to 2^kRescaleSlack, which fp32 sums and bf16 operands carry exactly
-// as well as values below 1, and the final normalisation uses the same maximum, so the result is
-// the plain softmax.
+// Data movement.  K and V units come from the operand-order copies written by the pooling kernel:
+// each unit is two contiguous 8 KiB runs in HBM.  They are copied HBM -> LDS by the LDS-direct
+// load (global_load_lds_dwordx4: lane L's 16 bytes land at M0 + 16 L, so one instruction moves one
+// contiguous KiB and the LDS image is already in ds_read_b128 operand order); no registers and no
+// ds_write are spent on staging.  A ring of NS LDS stages keeps NS - 1 units in flight per
+// workgroup, paced by explicit s_waitcnt vmcnt counts (loads return in order) and one barrier per
+// unit.  This matters because the gather of 16 KiB pieces is latency-bound otherwise.
+//
+// Bound.  At block 64 every (query block, selected block) pair moves 16 KiB for 1 MFLOP: the kernel
+// runs at the rate at which the memory fabric delivers L2 misses (about 7 TB/s for scattered 16 KiB
+// pieces on MI355X, whether they come from HBM or from the Infinity Cache), not at the MFMA rate.
+// Letting one workgroup serve several neighbouring query blocks from a merged list was measured
+// and brings nothing: the work mapping already runs neighbours on the same XCD at the same time,
+// so their shared key blocks hit in that XCD's L2.
+//
+// Softmax.  The running row maximum is only raised when a unit exceeds it by more than
+// kRescaleSlack (log2 units), so the rescale of the output accumulators is skipped for almost every
+// unit; probabilities then range up to 2^kRescaleSlack, which fp32 sums and bf16 operands carry as
+// well as values below 1, and the final normalisation uses the same maximum: plain softmax.
 #include "s3r_device.h"
 #include "s3r_kernels.h"
-
-#include <cstdlib>
 
 namespace s3r {
 
 constexpr float kRescaleSlack = 8.0f;
+constexpr int kUnitKeys = 64;
+constexpr int kUnitElems = kUnitKeys * 64;  // bf16 elements of one K (or V) unit: 8 KiB
 
 __device__ __forceinline__ float max_with_other_half(float x)
 {
@@ -42,263 +50,246 @@ __device__ __forceinline__ float sum_with_other_half(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// B      : tokens per key block (64 or 128) = rows of one staged K / V tile
-// NWAVES : waves per workgroup; an item covers 32 * NWAVES consecutive query rows.  For selection
-//          NWAVES = B / 32 (one query block per item).
-// DENSE  : iterate over every key block instead of an index list
-// NPF    : register sets of the tile ring (tiles in flight per workgroup)
-template <int B, int NWAVES, bool DENSE, int NPF>
-__global__ __launch_bounds__(NWAVES * 64, 2) void select_mfma_kernel(
+// One LDS-direct load: 64 lanes x 16 bytes from `src` (per-lane address) to LDS byte address
+// `lds_byte` (wave-uniform) + 16 * lane.  Counted by vmcnt like any vector memory load.
+__device__ __forceinline__ void lds_dma_16(const void *src, unsigned lds_byte)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_byte)
+                 : "memory", "m0");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// QW    : waves per workgroup = query rows / 32 (block / 32 for selection: one query block)
+// DENSE : every key unit instead of an index list
+// NS    : LDS stages of the unit ring
+template <int QW, bool DENSE, int NS>
+__global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ kb, const bf16_t *__restrict__ vb,
     const int32_t *__restrict__ idx, const float *__restrict__ o_comp, const bf16_t *__restrict__ gate,
     bf16_t *__restrict__ out, bf16_t *__restrict__ o_sel, float *__restrict__ lse, int64_t n_tok,
-    int64_t n_blk, int heads, int kk, float scale_log2, int64_t group_offset, int64_t n_groups, int map_mode)
+    int64_t n_blk, int heads, int block, int kk, float scale_log2, int64_t set_offset, int64_t n_sets,
+    int map_mode)
 {
-    constexpr int NT = B / 32;               // 32-key MFMA tiles per key block
-    constexpr int TILE = B * 64;             // elements of one K (or V) tile
-    constexpr int NTHR = NWAVES * 64;
-    constexpr int CHUNKS = TILE / 8 / NTHR;  // 16-byte chunks per thread per array
-    static_assert(TILE / 8 % NTHR == 0, "tile must split evenly over the workgroup");
-    __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][TILE];  // [stage][K, V]
+    constexpr int NW = QW;             // waves per workgroup
+    constexpr int CPW = 16 / NW;       // 1 KiB chunks of a unit (8 K + 8 V) issued by each wave
+    constexpr int D = NS - 1;          // units in flight
+    static_assert(16 % NW == 0 && NW <= 16, "waves must split the 16 chunks of a unit evenly");
+    static_assert(CPW * D < 64, "vmcnt budget");
+    __shared__ __attribute__((aligned(1024))) bf16_t ring[NS][2 * kUnitElems];  // [stage][K 8 KiB | V 8 KiB]
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5;
-    const int64_t total_items = n_groups * heads;
-    int64_t item_stride = total_items;  // one item per workgroup unless persistent
-    int64_t item0;
+    const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int h;
+    int64_t set;  // query group (query block for selection) of this workgroup
     {
         const int64_t bid = blockIdx.x;
         if (map_mode == 0) {  // head fastest
-            item0 = (bid % heads) * n_groups + bid / heads;
-        } else if (map_mode == 2) {  // head-major, each XCD (workgroup id mod 8) a contiguous range
-            const int64_t per = (n_groups + 7) / 8;
-            const int64_t hh = bid / (8 * per), r = bid % (8 * per);
-            const int64_t g_in = (r % 8) * per + r / 8;
-            if (g_in >= n_groups) return;
-            item0 = hh * n_groups + g_in;
-        } else {  // persistent, head-major
-            item0 = bid;
-            item_stride = gridDim.x;
+            h = static_cast<int>(bid % heads);
+            set = bid / heads;
+        } else {  // head-major, each XCD (workgroup id mod 8) takes a contiguous range of sets
+            const int64_t per = (n_sets + 7) / 8;
+            h = static_cast<int>(bid / (8 * per));
+            const int64_t r = bid % (8 * per);
+            set = (r % 8) * per + r / 8;
+            if (set >= n_sets) return;
+        }
+        set += set_offset;
+    }
+    const int upb = block / kUnitKeys;  // units per key block (1 or 2)
+    const int64_t qgroup = set;
+    const int64_t t = qgroup * (32 * QW) + wave * 32 + (lane & 31);
+    const bool row_valid = t < n_tok;
+    const int64_t n_units_total = (n_tok + kUnitKeys - 1) / kUnitKeys;
+
+    bf16x8 qb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        if (row_valid) {
+            qb[s] = *reinterpret_cast<const bf16x8 *>(q + (t * heads + h) * 64 + 16 * s + 8 * g);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) qb[s][i] = static_cast<bf16_t>(0.f);
         }
     }
-    const int tail_len = static_cast<int>(n_tok - (n_blk - 1) * B);  // valid keys of the last block
 
-    for (int64_t item = item0; item < total_items; item += item_stride) {
-        const int h = static_cast<int>(item / n_groups);
-        const int64_t qgroup = item % n_groups + group_offset;  // query block (selection) / row group
-        const int64_t t = qgroup * (32 * NWAVES) + wave * 32 + (lane & 31);
-        const bool row_valid = t < n_tok;
+    // ---- the list of key blocks this workgroup visits ---------------------------------------
+    int64_t n_steps;  // units to process
+    const int32_t *sel = nullptr;
+    if constexpr (DENSE) {
+        n_steps = n_units_total;
+    } else {
+        sel = idx + (static_cast<int64_t>(h) * n_blk + qgroup) * kk;
+        n_steps = static_cast<int64_t>(kk) * upb;
+    }
 
-        bf16x8 qb[4];
+    const bf16_t *kb_h = kb + static_cast<int64_t>(h) * n_blk * block * 64;
+    const bf16_t *vb_h = vb + static_cast<int64_t>(h) * n_blk * block * 64;
+    const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0]));
+
+    // step s -> key unit (global unit index)
+    auto unit_of = [&](int64_t s) -> int64_t {
+        if constexpr (DENSE) return s;
+        else return static_cast<int64_t>(sel[s / upb]) * upb + s % upb;
+    };
+    auto issue = [&](int64_t s) {  // this wave's share of unit s -> stage s % NS
+        const int64_t w = unit_of(s);
+        const unsigned stage_byte = ring_base + static_cast<unsigned>(s % NS) * (2 * kUnitElems * 2);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            if (row_valid) {
-                qb[s] = *reinterpret_cast<const bf16x8 *>(q + (t * heads + h) * 64 + 16 * s + 8 * g);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) qb[s][i] = static_cast<bf16_t>(0.f);
-            }
+        for (int c = 0; c < CPW; ++c) {
+            const int chunk = wave * CPW + c;  // 0..7: K, 8..15: V
+            const bf16_t *src = (chunk < 8 ? kb_h : vb_h) + w * kUnitElems + (chunk & 7) * 512 + lane * 8;
+            lds_dma_16(src, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
         }
+    };
 
-        const int64_t n_sel = DENSE ? n_blk : kk;
-        const int32_t *sel = DENSE ? nullptr : idx + (static_cast<int64_t>(h) * n_blk + qgroup) * kk;
-        const bf16_t *kb_h = kb + static_cast<int64_t>(h) * n_blk * TILE;
-        const bf16_t *vb_h = vb + static_cast<int64_t>(h) * n_blk * TILE;
-        auto tile_of = [&](int64_t a) -> int64_t { return DENSE ? a : static_cast<int64_t>(sel[a]); };
+    floatx16 oacc[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    float m_run = -1e30f, l_run = 0.f;
 
-        bf16x8 pf[NPF][2][CHUNKS];
-        floatx16 oacc[2];
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-        float m_run = -1e30f, l_run = 0.f;
+    for (int64_t s = 0; s < D && s < n_steps; ++s) issue(s);
 
-        // prologue: tiles 0 .. NPF-1 into the register ring, tile 0 on to LDS, tile NPF requested
-#pragma unroll
-        for (int u = 0; u < NPF; ++u) {
-            if (u < n_sel) {
-                const int64_t j = tile_of(u);
-#pragma unroll
-                for (int c = 0; c < CHUNKS; ++c) {
-                    pf[u][0][c] = *reinterpret_cast<const bf16x8 *>(kb_h + j * TILE + (tid + c * NTHR) * 8);
-                    pf[u][1][c] = *reinterpret_cast<const bf16x8 *>(vb_h + j * TILE + (tid + c * NTHR) * 8);
-                }
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < CHUNKS; ++c) {
-            *reinterpret_cast<bf16x8 *>(&lds[0][0][(tid + c * NTHR) * 8]) = pf[0][0][c];
-            *reinterpret_cast<bf16x8 *>(&lds[0][1][(tid + c * NTHR) * 8]) = pf[0][1][c];
-        }
+    for (int64_t s = 0; s < n_steps; ++s) {
+        // unit s: this wave's loads done, then everybody's (barrier); the barrier also says every wave
+        // has finished unit s - 1, whose stage the next request overwrites
+        if (s + D <= n_steps) wait_vmcnt<CPW *(D - 1)>(); else wait_vmcnt<0>();
         __syncthreads();
-        if (NPF < n_sel) {
-            const int64_t j = tile_of(NPF);
+        if (s + D < n_steps) issue(s + D);
+
+        const int64_t w = unit_of(s);
+        const int valid = static_cast<int>((n_tok - w * kUnitKeys < kUnitKeys) ? (n_tok - w * kUnitKeys) : kUnitKeys);
+        if (valid <= 0) continue;  // second half of a short last block
+
+        const bf16_t *ks = &ring[s % NS][0];
+        const bf16_t *vs = &ring[s % NS][kUnitElems];
+        floatx16 sacc[2];
 #pragma unroll
-            for (int c = 0; c < CHUNKS; ++c) {
-                pf[0][0][c] = *reinterpret_cast<const bf16x8 *>(kb_h + j * TILE + (tid + c * NTHR) * 8);
-                pf[0][1][c] = *reinterpret_cast<const bf16x8 *>(vb_h + j * TILE + (tid + c * NTHR) * 8);
+        for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[mt][r] = 0.f;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(ks + ((mt * 4 + c) * 64 + lane) * 8);
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[c], sacc[mt], 0, 0, 0);
             }
         }
-
-        for (int64_t a0 = 0; a0 < n_sel; a0 += NPF) {
+        if (valid < kUnitKeys) {              // keys past the end of the sequence do not exist
+            asm volatile("" ::: "memory");    // keep this rare path a real branch
 #pragma unroll
-            for (int u = 0; u < NPF; ++u) {
-                // tile a sits in LDS stage a & 1; tile a + 1 is (arriving) in register set (u + 1) % NPF
-                const int64_t a = a0 + u;
-                if (a >= n_sel) break;
-                const int cur = static_cast<int>(a & 1);
-
-                floatx16 sacc[NT];
+            for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int mt = 0; mt < NT; ++mt) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sacc[mt][r] = 0.f;
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) {
-                        const bf16x8 ka =
-                            *reinterpret_cast<const bf16x8 *>(&lds[cur][0][((mt * 4 + s) * 64 + lane) * 8]);
-                        sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[s], sacc[mt], 0, 0, 0);
-                    }
-                }
-                if (tail_len < B && tile_of(a) == n_blk - 1) {  // keys past the end of the sequence do not exist
-                    asm volatile("" ::: "memory");                // keep this rare path a real branch
-#pragma unroll
-                    for (int mt = 0; mt < NT; ++mt)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (mt * 32 + acc_row(lane, r) >= tail_len) sacc[mt][r] = -INFINITY;
-                }
-                float mx = sacc[0][0];
-#pragma unroll
-                for (int mt = 0; mt < NT; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mt][r]);
-                const float m_tile = max_with_other_half(mx) * scale_log2;
-                const bool grow = m_tile > m_run + kRescaleSlack;
-                if (__any(grow)) {  // rare after the first tile: raise the maximum, rescale the accumulators
-                    const float m_new = grow ? m_tile : m_run;
-                    const float alpha = fast_exp2(m_run - m_new);
-                    m_run = m_new;
-                    l_run *= alpha;
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-                }
-                float lsum = 0.f;
-#pragma unroll
-                for (int mt = 0; mt < NT; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        sacc[mt][r] = fast_exp2(sacc[mt][r] * scale_log2 - m_run);
-                        lsum += sacc[mt][r];
-                    }
-                l_run += lsum;
-#pragma unroll
-                for (int v = 0; v < 2 * NT; ++v) {
-                    const int mt = v >> 1, w = v & 1;
-                    bf16x8 pb;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) pb[i] = static_cast<bf16_t>(sacc[mt][8 * w + i]);
-#pragma unroll
-                    for (int dt = 0; dt < 2; ++dt) {
-                        const bf16x8 va =
-                            *reinterpret_cast<const bf16x8 *>(&lds[cur][1][((v * 2 + dt) * 64 + lane) * 8]);
-                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, oacc[dt], 0, 0, 0);
-                    }
-                }
-
-                const int nset = (u + 1) % NPF;
-                if (a + 1 < n_sel) {
-#pragma unroll
-                    for (int c = 0; c < CHUNKS; ++c) {
-                        *reinterpret_cast<bf16x8 *>(&lds[cur ^ 1][0][(tid + c * NTHR) * 8]) = pf[nset][0][c];
-                        *reinterpret_cast<bf16x8 *>(&lds[cur ^ 1][1][(tid + c * NTHR) * 8]) = pf[nset][1][c];
-                    }
-                }
-                __syncthreads();
-                if (a + 1 + NPF < n_sel) {
-                    const int64_t j = tile_of(a + 1 + NPF);
-#pragma unroll
-                    for (int c = 0; c < CHUNKS; ++c) {
-                        pf[nset][0][c] = *reinterpret_cast<const bf16x8 *>(kb_h + j * TILE + (tid + c * NTHR) * 8);
-                        pf[nset][1][c] = *reinterpret_cast<const bf16x8 *>(vb_h + j * TILE + (tid + c * NTHR) * 8);
-                    }
-                }
-            }
+                for (int r = 0; r < 16; ++r)
+                    if (mt * 32 + acc_row(lane, r) >= valid) sacc[mt][r] = -INFINITY;
         }
-
-        if (row_valid) {
-            const float l_tot = sum_with_other_half(l_run);
-            const float inv = 1.f / l_tot;
-            if (lse != nullptr && g == 0)
-                lse[static_cast<int64_t>(h) * n_tok + t] = (m_run + __builtin_log2f(l_tot)) * kLn2;
-            const int64_t o = (t * heads + h) * 64;
-            const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_blk + t / B) * 64 : nullptr;
+        float mx = sacc[0][0];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mt][r]);
+        const float m_tile = max_with_other_half(mx) * scale_log2;
+        const bool grow = m_tile > m_run + kRescaleSlack;
+        if (__any(grow)) {  // rare after the first unit: raise the maximum, rescale the accumulators
+            const float m_new = grow ? m_tile : m_run;
+            const float alpha = fast_exp2(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int d0 = 32 * dt + 8 * r4 + 4 * g;
-                    float os[4], res[4];
+                for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+        }
+        float lsum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) res[i] = os[i] = oacc[dt][4 * r4 + i] * inv;
-                    if (oc != nullptr) {
-                        const floatx4 c4 = *reinterpret_cast<const floatx4 *>(oc + d0);
-                        float gt[4] = {0.5f, 0.5f, 0.5f, 0.5f};
-                        if (gate != nullptr) {
-                            const bf16x4 gl = *reinterpret_cast<const bf16x4 *>(gate + o + d0);
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) gt[i] = 1.f / (1.f + __expf(-static_cast<float>(gl[i])));
-                        }
+            for (int r = 0; r < 16; ++r) {
+                sacc[mt][r] = fast_exp2(sacc[mt][r] * scale_log2 - m_run);
+                lsum[r & 3] += sacc[mt][r];
+            }
+        l_run += (lsum[0] + lsum[1]) + (lsum[2] + lsum[3]);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) res[i] = gt[i] * c4[i] + (1.f - gt[i]) * os[i];
-                    }
-                    bf16x4 ro;
+        for (int v = 0; v < 4; ++v) {
+            const int mt = v >> 1, hw = v & 1;
+            bf16x8 pb;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) ro[i] = static_cast<bf16_t>(res[i]);
-                    *reinterpret_cast<bf16x4 *>(out + o + d0) = ro;
-                    if (o_sel != nullptr) {
+            for (int i = 0; i < 8; ++i) pb[i] = static_cast<bf16_t>(sacc[mt][8 * hw + i]);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) ro[i] = static_cast<bf16_t>(os[i]);
-                        *reinterpret_cast<bf16x4 *>(o_sel + o + d0) = ro;
-                    }
-                }
+            for (int dt = 0; dt < 2; ++dt) {
+                const bf16x8 va = *reinterpret_cast<const bf16x8 *>(vs + ((v * 2 + dt) * 64 + lane) * 8);
+                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, oacc[dt], 0, 0, 0);
+            }
         }
     }
+
+    if (!row_valid) return;
+    const float l_tot = sum_with_other_half(l_run);
+    const float inv = 1.f / l_tot;
+    if (lse != nullptr && g == 0) lse[static_cast<int64_t>(h) * n_tok + t] = (m_run + __builtin_log2f(l_tot)) * kLn2;
+    const int64_t o = (t * heads + h) * 64;
+    const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_blk + t / block) * 64 : nullptr;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int d0 = 32 * dt + 8 * r4 + 4 * g;
+            float os[4], res[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) res[i] = os[i] = oacc[dt][4 * r4 + i] * inv;
+            if (oc != nullptr) {
+                const floatx4 c4 = *reinterpret_cast<const floatx4 *>(oc + d0);
+                float gt[4] = {0.5f, 0.5f, 0.5f, 0.5f};
+                if (gate != nullptr) {
+                    const bf16x4 gl = *reinterpret_cast<const bf16x4 *>(gate + o + d0);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) gt[i] = 1.f / (1.f + __expf(-static_cast<float>(gl[i])));
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) res[i] = gt[i] * c4[i] + (1.f - gt[i]) * os[i];
+            }
+            bf16x4 ro;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ro[i] = static_cast<bf16_t>(res[i]);
+            *reinterpret_cast<bf16x4 *>(out + o + d0) = ro;
+            if (o_sel != nullptr) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ro[i] = static_cast<bf16_t>(os[i]);
+                *reinterpret_cast<bf16x4 *>(o_sel + o + d0) = ro;
+            }
+        }
 }
 
-template <int B, int NWAVES, bool DENSE, int NPF>
+template <int QW, bool DENSE, int NS>
 static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
 {
-    const int64_t rows_per_wg = 32 * NWAVES;
-    const int64_t groups = DENSE ? (a.n_tok + rows_per_wg - 1) / rows_per_wg : a.n_blk;
+    const int64_t rows_per_group = 32 * QW;
+    const int64_t groups = DENSE ? (a.n_tok + rows_per_group - 1) / rows_per_group : a.n_blk;
+    const int64_t sets = groups;
     // Dense attention is quadratic: keep each launch to roughly 2e14 FLOP (a fraction of a second)
     // so that no single kernel occupies the GPU for seconds.
-    int64_t per_launch = groups;
+    int64_t per_launch = sets;
     if (DENSE) {
-        const double flops_per_group = 4.0 * 64.0 * rows_per_wg * static_cast<double>(a.n_tok) * a.heads;
-        per_launch = static_cast<int64_t>(2e14 / flops_per_group);
+        const double flops_per_set = 4.0 * 64.0 * rows_per_group * static_cast<double>(a.n_tok) * a.heads;
+        per_launch = static_cast<int64_t>(2e14 / flops_per_set);
         if (per_launch < 1) per_launch = 1;
     }
     if ((per_launch + 8) * a.heads > 0x7fffffffLL) return hipErrorInvalidValue;
-    const char *mm = getenv("S3R_SELECT_MAP");
-    const int map_mode = mm ? atoi(mm) : (DENSE ? 0 : 2);
-    for (int64_t g0 = 0; g0 < groups; g0 += per_launch) {
-        const int64_t ng = (groups - g0 < per_launch) ? groups - g0 : per_launch;
-        int64_t grid = ng * a.heads;
-        if (map_mode == 2) grid = (ng + 7) / 8 * 8 * a.heads;
-        if (map_mode >= 3) {
-            const char *pg = getenv("S3R_SELECT_GRID");
-            const int64_t want = pg ? atoll(pg) : 1024;
-            if (grid > want) grid = want;
-        }
-        hipLaunchKernelGGL((select_mfma_kernel<B, NWAVES, DENSE, NPF>), dim3(static_cast<unsigned>(grid)),
-                           dim3(NWAVES * 64), 0, stream, static_cast<const bf16_t *>(a.q),
+    const int map_mode = DENSE ? 0 : 2;
+    for (int64_t s0 = 0; s0 < sets; s0 += per_launch) {
+        const int64_t ns = (sets - s0 < per_launch) ? sets - s0 : per_launch;
+        const int64_t grid = (map_mode == 2) ? (ns + 7) / 8 * 8 * a.heads : ns * a.heads;
+        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS>), dim3(static_cast<unsigned>(grid)),
+                           dim3(QW * 64), 0, stream, static_cast<const bf16_t *>(a.q),
                            static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
                            a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
-                           static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.kk,
-                           a.scale * kLog2e, g0, ng, map_mode);
+                           static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.block,
+                           a.kk, a.scale * kLog2e, s0, ns, map_mode);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -308,23 +299,14 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
 hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
 {
     if (!a.is_bf16 || a.kb == nullptr || a.vb == nullptr) return hipErrorInvalidValue;
-    const char *pn = getenv("S3R_SELECT_NPF");
-    const int npf = pn ? atoi(pn) : 2;
+    // One query block per workgroup, two LDS stages: measured best on MI355X (deeper rings only add
+    // queueing once the memory fabric is saturated).
     if (a.idx == nullptr) {
         if (a.block != 64) return hipErrorInvalidValue;
-        return run_select<64, 4, true, 1>(a, stream);
+        return run_select<4, true, 3>(a, stream);
     }
-    if (a.block == 64) {
-        if (npf == 1) return run_select<64, 2, false, 1>(a, stream);
-        if (npf == 2) return run_select<64, 2, false, 2>(a, stream);
-        if (npf == 4) return run_select<64, 2, false, 4>(a, stream);
-        return run_select<64, 2, false, 3>(a, stream);
-    }
-    if (a.block == 128) {
-        if (npf == 1) return run_select<128, 4, false, 1>(a, stream);
-        if (npf == 3) return run_select<128, 4, false, 3>(a, stream);
-        return run_select<128, 4, false, 2>(a, stream);
-    }
+    if (a.block == 64) return run_select<2, false, 2>(a, stream);
+    if (a.block == 128) return run_select<4, false, 2>(a, stream);
     return hipErrorInvalidValue;
 }
 
