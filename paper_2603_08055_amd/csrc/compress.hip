@@ -2,45 +2,110 @@
 //   S_guide = Qc Kc^T (unscaled, written out for TopK) and Oc' = softmax(scale * S_guide) Vc,
 // one pass over the pooled keys with an online softmax.
 //
-// gfx950 design: each wave owns 32 pooled queries and computes the TRANSPOSED score tile
-// S^T[key][query] with v_mfma_f32_32x32x16_bf16 (A = pooled keys from LDS, B = pooled queries
-// held in registers).  In that orientation a lane holds 16 keys of ONE query per 32-key tile, so
-// row max / row sum are in-lane reductions plus one exchange with the lane 32 positions away, and
-// the probabilities already sit in the register order the next MFMA (O^T = Vc^T P^T) wants.
+// gfx950 design.  Each compute wave owns 32 pooled queries and computes the TRANSPOSED score tile
+// S^T[key][query] with v_mfma_f32_32x32x16_bf16 (A = pooled keys from LDS, B = pooled queries held
+// in registers).  In that orientation a lane holds 16 keys of ONE query per 32-key tile, so row
+// max / row sum are in-lane reductions plus one exchange with the lane 32 positions away, and the
+// probabilities already sit in the register order the next MFMA (O^T = Vc^T P^T) wants.
 // Scores use bf16 hi/lo operand pairs (hi*hi + hi*lo + lo*hi): about 2^-16 relative to |q||k|,
 // which keeps the TopK ordering at fp32 quality at bf16 MFMA rates.
+//
+// Waves are specialised.  The kernel streams 4 N_b^2 H bytes of scores out while it streams the
+// pooled keys in.  On this ISA vector loads and stores share one in-flight counter (vmcnt) and
+// return out of order with respect to each other, so a wave that both stores scores and waits for
+// its next key tile has to wait for its stores as well: every step would then cost a full
+// store-acknowledge latency.  Hence the compute waves never load inside the loop (their score
+// stores are fire-and-forget) and one more wave does nothing but move key/value operand tiles
+// HBM -> LDS with LDS-direct loads, a ring of NS stages ahead, pacing itself with exact vmcnt
+// counts (its counter only ever holds loads, which return in order).  One barrier per step.
 #include "s3r_device.h"
 #include "s3r_kernels.h"
 
 namespace s3r {
 
-template <bool SPLIT_PV>
-__global__ __launch_bounds__(256, 2) void compress_kernel(
+constexpr float kCompressRescaleSlack = 8.0f;  // see select_mfma.hip: lazy raise of the running maximum
+
+__device__ __forceinline__ void compress_lds_dma_16(const void *src, unsigned lds_byte)
+{
+    // 64 lanes x 16 bytes from per-lane `src` to LDS byte address lds_byte + 16 * lane
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_byte)
+                 : "memory", "m0");
+}
+
+template <int N> __device__ __forceinline__ void compress_wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ float compress_max_halves(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ __forceinline__ float compress_sum_halves(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// grid: (ceil(tiles / CW), heads); CW compute waves (32 pooled queries each) + 1 loader wave.
+template <bool SPLIT_PV, int NS, int CW>
+__global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
     const bf16_t *__restrict__ qs_hi, const bf16_t *__restrict__ qs_lo,
     const bf16_t *__restrict__ ks_hi, const bf16_t *__restrict__ ks_lo,
     const bf16_t *__restrict__ vt_hi, const bf16_t *__restrict__ vt_lo, float *__restrict__ s_guide,
     int64_t ld_s, float *__restrict__ o_comp, int64_t n_blk, int64_t tiles_padded, float scale_log2)
 {
-    constexpr int NARR = SPLIT_PV ? 4 : 3;         // ks_hi, ks_lo, vt_hi [, vt_lo]
-    constexpr int STAGE_ELEMS = 2 * kRowTileElems;  // 64 keys x 64 channels per array
-    __shared__ __attribute__((aligned(16))) bf16_t lds[2][NARR][STAGE_ELEMS];
+    constexpr int NARR = SPLIT_PV ? 4 : 3;          // ks_hi, ks_lo, vt_hi [, vt_lo]
+    constexpr int STAGE_ELEMS = 2 * kRowTileElems;   // 64 keys x 64 channels per array: 8 KiB
+    constexpr int CPS = NARR * 8;                    // 1 KiB chunks per step, all issued by the loader wave
+    constexpr int D = NS - 1;                        // steps in flight
+    static_assert(CPS * (D - 1) < 64, "vmcnt budget");
+    __shared__ __attribute__((aligned(1024))) bf16_t ring[NS][NARR][STAGE_ELEMS];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = blockIdx.y;
-    const int64_t qtile = static_cast<int64_t>(blockIdx.x) * 4 + wave;
-    const int64_t qrow = qtile * 32 + (lane & 31);
-    const bool wave_active = qtile * 32 < n_blk;
     const int64_t n_kt = (n_blk + 63) / 64;
     const int64_t head_tiles = static_cast<int64_t>(h) * tiles_padded;
 
-    const bf16_t *src[NARR];
-    src[0] = ks_hi + head_tiles * kRowTileElems;
-    src[1] = ks_lo + head_tiles * kRowTileElems;
-    src[2] = vt_hi + head_tiles * kRowTileElems;
-    if constexpr (SPLIT_PV) src[3] = vt_lo + head_tiles * kRowTileElems;
+    if (wave == CW) {
+        // ---- loader wave ---------------------------------------------------------------------
+        const bf16_t *src[NARR];
+        src[0] = ks_hi + head_tiles * kRowTileElems;
+        src[1] = ks_lo + head_tiles * kRowTileElems;
+        src[2] = vt_hi + head_tiles * kRowTileElems;
+        if constexpr (SPLIT_PV) src[3] = vt_lo + head_tiles * kRowTileElems;
+        const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
+        auto issue = [&](int64_t kt) {
+            const unsigned stage_byte = ring_base + static_cast<unsigned>(kt % NS) * (NARR * STAGE_ELEMS * 2);
+#pragma unroll
+            for (int a = 0; a < NARR; ++a)
+#pragma unroll
+                for (int c = 0; c < 8; ++c)
+                    compress_lds_dma_16(src[a] + kt * STAGE_ELEMS + c * 512 + lane * 8,
+                                        __builtin_amdgcn_readfirstlane(stage_byte + (a * 8 + c) * 1024));
+        };
+        for (int64_t kt = 0; kt < D && kt < n_kt; ++kt) issue(kt);
+        for (int64_t kt = 0; kt < n_kt; ++kt) {
+            // step kt landed (loads return in order), tell everybody; the barrier also says the
+            // compute waves are done with step kt - 1, whose stage the next request overwrites
+            if (kt + D <= n_kt) compress_wait_vmcnt<CPS *(D - 1)>(); else compress_wait_vmcnt<0>();
+            lds_barrier();
+            if (kt + D < n_kt) issue(kt + D);
+        }
+        return;
+    }
+
+    // ---- compute waves ---------------------------------------------------------------------------
+    const int64_t qtile = static_cast<int64_t>(blockIdx.x) * CW + wave;
+    const int64_t qrow = qtile * 32 + (lane & 31);
+    const bool wave_active = qtile * 32 < n_blk;
 
     bf16x8 qhi[4], qlo[4];
-    {
+    if (wave_active) {
         const int64_t qb = (head_tiles + qtile) * kRowTileElems;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
@@ -48,130 +113,114 @@ __global__ __launch_bounds__(256, 2) void compress_kernel(
             qlo[s] = *reinterpret_cast<const bf16x8 *>(qs_lo + qb + (s * 64 + lane) * 8);
         }
     }
-
-    bf16x8 pf[NARR][2];
-    auto fetch = [&](int64_t kt) {
-#pragma unroll
-        for (int a = 0; a < NARR; ++a)
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-                pf[a][c] = *reinterpret_cast<const bf16x8 *>(src[a] + kt * STAGE_ELEMS + (tid + c * 256) * 8);
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int a = 0; a < NARR; ++a)
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-                *reinterpret_cast<bf16x8 *>(&lds[buf][a][(tid + c * 256) * 8]) = pf[a][c];
-    };
-
     floatx16 oacc[2];
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
     float m_run = -1e30f, l_run = 0.f;
-
-    fetch(0);
-    stash(0);
-    __syncthreads();
+    float *srow = s_guide + (static_cast<int64_t>(h) * n_blk + (qrow < n_blk ? qrow : 0)) * ld_s;
 
     for (int64_t kt = 0; kt < n_kt; ++kt) {
-        const int cur = static_cast<int>(kt & 1);
-        if (kt + 1 < n_kt) fetch(kt + 1);
+        lds_barrier();
+        if (!wave_active) continue;
+        const bf16_t *k_hi = &ring[kt % NS][0][0];
+        const bf16_t *k_lo = &ring[kt % NS][1][0];
+        const bf16_t *v_hi = &ring[kt % NS][2][0];
+        const bf16_t *v_lo = &ring[kt % NS][NARR - 1][0];
 
-        if (wave_active) {
-            floatx16 sacc[2];
+        floatx16 sacc[2];
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
+        for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[mt][r] = 0.f;
+            for (int r = 0; r < 16; ++r) sacc[mt][r] = 0.f;
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const int off = mt * kRowTileElems + (s * 64 + lane) * 8;
-                    const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(&lds[cur][0][off]);
-                    const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(&lds[cur][1][off]);
-                    sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, qhi[s], sacc[mt], 0, 0, 0);
-                    sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qlo[s], sacc[mt], 0, 0, 0);
-                    sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[s], sacc[mt], 0, 0, 0);
-                }
+            for (int s = 0; s < 4; ++s) {
+                const int off = mt * kRowTileElems + (s * 64 + lane) * 8;
+                const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + off);
+                const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(k_lo + off);
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, qhi[s], sacc[mt], 0, 0, 0);
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qlo[s], sacc[mt], 0, 0, 0);
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[s], sacc[mt], 0, 0, 0);
             }
-            // eq. 4: raw scores out, 4 consecutive keys of one query row per store
-            if (qrow < n_blk) {
-                float *srow = s_guide + (static_cast<int64_t>(h) * n_blk + qrow) * ld_s;
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        const int64_t key0 = kt * 64 + mt * 32 + 8 * r4 + 4 * g;
-                        if (key0 < ld_s) {
-                            floatx4 o;
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) o[i] = sacc[mt][4 * r4 + i];
-                            *reinterpret_cast<floatx4 *>(srow + key0) = o;
-                        }
-                    }
-            }
-            if (kt * 64 + 64 > n_blk) {  // pooled keys past the end of the sequence do not exist
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (kt * 64 + mt * 32 + acc_row(lane, r) >= n_blk) sacc[mt][r] = -INFINITY;
-            }
-            // online softmax (eq. 3), base-2 exponent with the scale folded in
-            float mx = sacc[0][0];
+        }
+        // eq. 4: raw scores out, 4 consecutive keys of one query row per store; never waited for
+        if (qrow < n_blk) {
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mt][r]);
-            mx = fmaxf(mx, other_half(mx));
-            const float m_new = fmaxf(m_run, mx * scale_log2);
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int64_t key0 = kt * 64 + mt * 32 + 8 * r4 + 4 * g;
+                    if (key0 < ld_s) {
+                        floatx4 o;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) o[i] = sacc[mt][4 * r4 + i];
+                        *reinterpret_cast<floatx4 *>(srow + key0) = o;
+                    }
+                }
+        }
+        if (kt * 64 + 64 > n_blk) {           // pooled keys past the end of the sequence do not exist
+            asm volatile("" ::: "memory");    // keep this rare path a real branch
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (kt * 64 + mt * 32 + acc_row(lane, r) >= n_blk) sacc[mt][r] = -INFINITY;
+        }
+        // online softmax (eq. 3), base-2 exponent with the scale folded in
+        float mx = sacc[0][0];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mt][r]);
+        const float m_tile = compress_max_halves(mx) * scale_log2;
+        const bool grow = m_tile > m_run + kCompressRescaleSlack;
+        if (__any(grow)) {
+            const float m_new = grow ? m_tile : m_run;
             const float alpha = fast_exp2(m_run - m_new);
             m_run = m_new;
-            float lsum = 0.f;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    sacc[mt][r] = fast_exp2(sacc[mt][r] * scale_log2 - m_new);
-                    lsum += sacc[mt][r];
-                }
-            l_run = l_run * alpha + lsum;
+            l_run *= alpha;
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-            // O^T += Vc^T P^T, contraction over the 64 keys in four 16-key steps
+        }
+        float lsum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int mt = u >> 1, w = u & 1;
-                bf16x8 p_hi, p_lo;
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float p = sacc[mt][8 * w + i];
-                    p_hi[i] = static_cast<bf16_t>(p);
-                    if constexpr (SPLIT_PV) p_lo[i] = static_cast<bf16_t>(p - static_cast<float>(p_hi[i]));
-                }
+            for (int r = 0; r < 16; ++r) {
+                sacc[mt][r] = fast_exp2(sacc[mt][r] * scale_log2 - m_run);
+                lsum[r & 3] += sacc[mt][r];
+            }
+        l_run += (lsum[0] + lsum[1]) + (lsum[2] + lsum[3]);
+        // O^T += Vc^T P^T, contraction over the 64 keys in four 16-key steps
 #pragma unroll
-                for (int dt = 0; dt < 2; ++dt) {
-                    const int off = mt * kRowTileElems + ((w * 2 + dt) * 64 + lane) * 8;
-                    const bf16x8 v_hi = *reinterpret_cast<const bf16x8 *>(&lds[cur][2][off]);
-                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_hi, p_hi, oacc[dt], 0, 0, 0);
-                    if constexpr (SPLIT_PV) {
-                        const bf16x8 v_lo = *reinterpret_cast<const bf16x8 *>(&lds[cur][NARR - 1][off]);
-                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_lo, p_hi, oacc[dt], 0, 0, 0);
-                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_hi, p_lo, oacc[dt], 0, 0, 0);
-                    }
+        for (int u = 0; u < 4; ++u) {
+            const int mt = u >> 1, w = u & 1;
+            bf16x8 p_hi, p_lo;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float p = sacc[mt][8 * w + i];
+                p_hi[i] = static_cast<bf16_t>(p);
+                if constexpr (SPLIT_PV) p_lo[i] = static_cast<bf16_t>(p - static_cast<float>(p_hi[i]));
+            }
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt) {
+                const int off = mt * kRowTileElems + ((w * 2 + dt) * 64 + lane) * 8;
+                const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(v_hi + off);
+                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_hi, p_hi, oacc[dt], 0, 0, 0);
+                if constexpr (SPLIT_PV) {
+                    const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(v_lo + off);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_lo, p_hi, oacc[dt], 0, 0, 0);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_hi, p_lo, oacc[dt], 0, 0, 0);
                 }
             }
         }
-        if (kt + 1 < n_kt) stash(cur ^ 1);
-        __syncthreads();
     }
 
     if (wave_active && qrow < n_blk) {
-        const float inv = 1.f / (l_run + other_half(l_run));
+        const float inv = 1.f / compress_sum_halves(l_run);
         float *orow = o_comp + (static_cast<int64_t>(h) * n_blk + qrow) * 64;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
@@ -185,28 +234,33 @@ __global__ __launch_bounds__(256, 2) void compress_kernel(
     }
 }
 
+template <bool SPLIT_PV, int NS, int CW>
+static hipError_t run_compress(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
+                               const void *vt_hi, const void *vt_lo, float *s_guide, int64_t ld_s,
+                               float *o_comp, int64_t n_blk, int heads, float scale_log2, hipStream_t stream)
+{
+    const int64_t tiles = pooled_tiles_padded(n_blk);
+    const int64_t q_tiles = (n_blk + 31) / 32;
+    const dim3 grid(static_cast<unsigned>((q_tiles + CW - 1) / CW), heads);
+    hipLaunchKernelGGL((compress_kernel<SPLIT_PV, NS, CW>), grid, dim3((CW + 1) * 64), 0, stream,
+                       static_cast<const bf16_t *>(qs_hi), static_cast<const bf16_t *>(qs_lo),
+                       static_cast<const bf16_t *>(ks_hi), static_cast<const bf16_t *>(ks_lo),
+                       static_cast<const bf16_t *>(vt_hi), static_cast<const bf16_t *>(vt_lo), s_guide, ld_s,
+                       o_comp, n_blk, tiles, scale_log2);
+    return hipGetLastError();
+}
+
 hipError_t launch_compress(const void *qs_hi, const void *qs_lo, const void *ks_hi,
                            const void *ks_lo, const void *vt_hi, const void *vt_lo, float *s_guide,
                            int64_t ld_s, float *o_comp, int64_t n_blk, int heads, float scale,
                            hipStream_t stream)
 {
-    const int64_t tiles = pooled_tiles_padded(n_blk);
-    const dim3 grid(static_cast<unsigned>(tiles / 4), heads);
-    const float scale_log2 = scale * kLog2e;
-    if (vt_lo != nullptr) {
-        hipLaunchKernelGGL(compress_kernel<true>, grid, dim3(256), 0, stream,
-                           static_cast<const bf16_t *>(qs_hi), static_cast<const bf16_t *>(qs_lo),
-                           static_cast<const bf16_t *>(ks_hi), static_cast<const bf16_t *>(ks_lo),
-                           static_cast<const bf16_t *>(vt_hi), static_cast<const bf16_t *>(vt_lo),
-                           s_guide, ld_s, o_comp, n_blk, tiles, scale_log2);
-    } else {
-        hipLaunchKernelGGL(compress_kernel<false>, grid, dim3(256), 0, stream,
-                           static_cast<const bf16_t *>(qs_hi), static_cast<const bf16_t *>(qs_lo),
-                           static_cast<const bf16_t *>(ks_hi), static_cast<const bf16_t *>(ks_lo),
-                           static_cast<const bf16_t *>(vt_hi), static_cast<const bf16_t *>(vt_lo),
-                           s_guide, ld_s, o_comp, n_blk, tiles, scale_log2);
-    }
-    return hipGetLastError();
+    const float sl = scale * kLog2e;
+    if (vt_lo != nullptr)
+        return run_compress<true, 2, 3>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk, heads, sl, stream);
+    // 3 compute waves + 1 loader wave, 3 LDS stages (72 KiB): two workgroups per CU.  Measured
+    // best on MI355X against 4 + 1 waves and 2 or 4 stages.
+    return run_compress<false, 3, 3>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk, heads, sl, stream);
 }
 
 }  // namespace s3r

@@ -59,4 +59,10 @@ __device__ __forceinline__ float other_half(float x)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory, which
+// makes the compiler drain every outstanding vector load and store (s_waitcnt vmcnt(0)) before the
+// barrier; kernels that keep LDS-direct loads or fire-and-forget stores in flight across a barrier
+// pace those themselves and use this one instead.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 }  // namespace s3r

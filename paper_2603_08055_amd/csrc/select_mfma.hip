@@ -160,7 +160,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         // unit s: this wave's loads done, then everybody's (barrier); the barrier also says every wave
         // has finished unit s - 1, whose stage the next request overwrites
         if (s + D <= n_steps) wait_vmcnt<CPW *(D - 1)>(); else wait_vmcnt<0>();
-        __syncthreads();
+        lds_barrier();
         if (s + D < n_steps) issue(s + D);
 
         const int64_t w = unit_of(s);

@@ -6,7 +6,6 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
-#include <cstdlib>
 #include <mutex>
 #include <vector>
 
@@ -74,9 +73,7 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, s3r_dtype dtyp
     L.tiles = s3r::pooled_tiles_padded(L.n_blk);
     L.ld_s = (L.n_blk + 63) / 64 * 64;
     const size_t per_head_s = static_cast<size_t>(L.n_blk) * L.ld_s * sizeof(float);
-    const char *cap_env = getenv("S3R_SCORE_CAP_GIB");
-    const size_t cap = cap_env ? (size_t(atoi(cap_env)) << 30) : kScoreBytesCap;
-    int64_t hc = static_cast<int64_t>(cap / per_head_s);
+    int64_t hc = static_cast<int64_t>(kScoreBytesCap / per_head_s);
     if (hc < 1) hc = 1;
     if (hc > heads) hc = heads;
     L.head_chunk = static_cast<int>(hc);
