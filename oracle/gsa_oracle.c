@@ -134,10 +134,14 @@ static int by_int32(const void *a, const void *b)
 
 /* Sec. 3.2 "Selection Branch", TopKSelect on the raw rows of S_guide: the kk
  * largest entries of each row, equal scores resolved towards the smaller block
- * index; the chosen indices are stored in ascending order.
- * idx[h][r][0..kk)  (layout [heads][n_rows][kk]);  requires 1 <= kk <= n_blk. */
-void gsa_oracle_topk(const double *s, int64_t n_blk, int heads, int64_t n_rows, int kk,
-                     int32_t *idx)
+ * index; the chosen indices are stored in ascending order.  Blocks j with
+ * excluded[j] != 0 never compete (Sec. 3.3: the fixed global-context blocks of
+ * the VGGT variant are always attended, so the dynamic TopK runs over the rest;
+ * the supplementary's "mask the first frame token").  excluded == NULL: none.
+ * idx[h][r][0..kk)  (layout [heads][n_rows][kk]);
+ * requires 1 <= kk <= number of blocks that are not excluded. */
+void gsa_oracle_topk_excluding(const double *s, int64_t n_blk, int heads, int64_t n_rows, int kk,
+                               const uint8_t *excluded, int32_t *idx)
 {
 #pragma omp parallel
     {
@@ -146,8 +150,14 @@ void gsa_oracle_topk(const double *s, int64_t n_blk, int heads, int64_t n_rows, 
         for (int h = 0; h < heads; ++h) {
             for (int64_t r = 0; r < n_rows; ++r) {
                 const double *srow = s + ((int64_t)h * n_rows + r) * n_blk;
-                for (int64_t j = 0; j < n_blk; ++j) { tmp[j].s = srow[j]; tmp[j].j = (int32_t)j; }
-                qsort(tmp, (size_t)n_blk, sizeof(scored_t), by_score_desc_then_index);
+                int64_t n = 0;
+                for (int64_t j = 0; j < n_blk; ++j) {
+                    if (excluded && excluded[j]) continue;
+                    tmp[n].s = srow[j];
+                    tmp[n].j = (int32_t)j;
+                    ++n;
+                }
+                qsort(tmp, (size_t)n, sizeof(scored_t), by_score_desc_then_index);
                 int32_t *dst = idx + ((int64_t)h * n_rows + r) * kk;
                 for (int a = 0; a < kk; ++a) dst[a] = tmp[a].j;
                 qsort(dst, (size_t)kk, sizeof(int32_t), by_int32);
@@ -155,6 +165,12 @@ void gsa_oracle_topk(const double *s, int64_t n_blk, int heads, int64_t n_rows, 
         }
         free(tmp);
     }
+}
+
+void gsa_oracle_topk(const double *s, int64_t n_blk, int heads, int64_t n_rows, int kk,
+                     int32_t *idx)
+{
+    gsa_oracle_topk_excluding(s, n_blk, heads, n_rows, kk, NULL, idx);
 }
 
 /* Eq. 6 / Alg. 2: for every query token t of query block rows[r] and head h,

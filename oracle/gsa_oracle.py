@@ -54,6 +54,8 @@ def _load():
         lib.gsa_oracle_scores.argtypes = [_f64p, _f64p, _i64, _int, _int, _i64p, _i64, _f64p]
         lib.gsa_oracle_compressed_attn.argtypes = [_f64p, _f64p, _i64, _int, _int, _i64, _dbl, _f64p]
         lib.gsa_oracle_topk.argtypes = [_f64p, _i64, _int, _i64, _int, _i32p]
+        lib.gsa_oracle_topk_excluding.argtypes = [_f64p, _i64, _int, _i64, _int,
+                                                  ctypes.POINTER(ctypes.c_uint8), _i32p]
         lib.gsa_oracle_select_attn.argtypes = [_f32p, _f32p, _f32p, _i64, _int, _int, _int, _i64p,
                                                _i64, _i32p, _int, _dbl, _f64p, _f64p]
         lib.gsa_oracle_merge.argtypes = [_f64p, _f64p, _f32p, _i64, _int, _int, _int, _i64p, _i64,
@@ -61,7 +63,7 @@ def _load():
         lib.gsa_oracle_dense_attn.argtypes = [_f32p, _f32p, _f32p, _i64, _int, _int, _i64p, _i64,
                                               _dbl, _f64p, _f64p]
         for name in ("gsa_oracle_pool", "gsa_oracle_scores", "gsa_oracle_compressed_attn",
-                     "gsa_oracle_topk", "gsa_oracle_select_attn", "gsa_oracle_merge",
+                     "gsa_oracle_topk", "gsa_oracle_topk_excluding", "gsa_oracle_select_attn", "gsa_oracle_merge",
                      "gsa_oracle_dense_attn"):
             getattr(lib, name).restype = None
         _lib = lib
@@ -141,6 +143,35 @@ def topk(s, k: int) -> np.ndarray:
     return out
 
 
+def forced_mask(forced, n_blk: int) -> np.ndarray:
+    """uint8 [n_blk] mask of the always-attended blocks; `forced` = ascending distinct indices."""
+    forced = np.asarray(forced, dtype=np.int64).reshape(-1)
+    assert forced.size == 0 or (forced.min() >= 0 and forced.max() < n_blk)
+    assert np.all(np.diff(forced) > 0), "forced blocks must be ascending and distinct"
+    m = np.zeros(n_blk, dtype=np.uint8)
+    m[forced] = 1
+    return m
+
+
+def topk_with_forced(s, k: int, forced) -> np.ndarray:
+    """Sec. 3.3 hybrid selection set per row of s [heads, n_rows, n_blk]: the fixed blocks `forced`
+    plus the k_dyn = min(k, n_blk - len(forced)) best of the remaining blocks, merged ascending.
+    Returns int32 [heads, n_rows, len(forced) + k_dyn]."""
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    heads, n_rows, n_blk = s.shape
+    forced = np.asarray(forced, dtype=np.int32).reshape(-1)
+    mask = forced_mask(forced, n_blk)
+    k_dyn = min(int(k), n_blk - forced.size)
+    assert k_dyn >= 0
+    fixed = np.broadcast_to(forced, (heads, n_rows, forced.size))
+    if k_dyn == 0:
+        return np.ascontiguousarray(fixed)
+    dyn = np.empty((heads, n_rows, k_dyn), dtype=np.int32)
+    _load().gsa_oracle_topk_excluding(_ptr(s, _f64p), n_blk, heads, n_rows, k_dyn,
+                                      _ptr(mask, ctypes.POINTER(ctypes.c_uint8)), _ptr(dyn, _i32p))
+    return np.sort(np.concatenate([fixed, dyn], axis=2), axis=2).astype(np.int32)
+
+
 def select_attn(q, k, v, block: int, idx, scale: float, rows=None):
     """Eq. 6 with a given index set idx [heads, n_rows, kk].
 
@@ -201,12 +232,14 @@ def dense_attn(q, k, v, scale: float, q_tok=None, want_lse: bool = False):
 
 
 def gsa_forward(q, k, v, block: int, topk_blocks: int, gate=None, scale=None, rows=None,
-                idx_override=None) -> dict:
+                idx_override=None, forced=None) -> dict:
     """The whole GSA path of Sec. 3.2 for the query blocks `rows` (all if None).
 
     Steps, in the paper's order: pool (compression branch), S_guide (eq. 4),
     compressed attention (eq. 3), TopKSelect, selection attention (eq. 6),
-    upsample + gated merge (eqs. 5, 7, 8).  `idx_override` replaces the TopK
+    upsample + gated merge (eqs. 5, 7, 8).  `forced` (ascending block indices) switches
+    the selection set to the hybrid of Sec. 3.3: those blocks always, TopK over the
+    rest.  `idx_override` replaces the TopK
     result for the selection step (used to score a valid alternative resolution
     of a near-tie).  Returns every intermediate."""
     q = _f32(q)
@@ -219,7 +252,7 @@ def gsa_forward(q, k, v, block: int, topk_blocks: int, gate=None, scale=None, ro
     qc, kc, vc = pool(q, block), pool(k, block), pool(v, block)
     s = scores(qc, kc, rows)
     oc = compressed_attn(s, vc, scale)
-    idx = topk(s, kk)
+    idx = topk(s, kk) if forced is None else topk_with_forced(s, int(topk_blocks), forced)
     use_idx = idx if idx_override is None else np.ascontiguousarray(idx_override, dtype=np.int32)
     o_sel, lse = select_attn(q, k, v, block, use_idx, scale, rows)
     out = merge(oc, o_sel, gate, n_tok, block, rows)

@@ -201,6 +201,36 @@ def test_topk_planted_blocks_and_scale_invariance(oracle):
     assert np.array_equal(idx, oracle.topk(oracle.scores(oracle.pool(q * 8, b), kc), 4))
 
 
+def test_topk_with_forced_bruteforce_and_edges(oracle):
+    # Sec. 3.3: fixed blocks join every row's set and leave the TopK competition.
+    rng = np.random.default_rng(14)
+    s = rng.standard_normal((2, 9, 23))
+    for forced, k in (([0, 1, 2], 4), ([5], 1), ([0, 11, 22], 20), ([3, 4, 9, 10], 30), ([], 6)):
+        idx = oracle.topk_with_forced(s, k, forced)
+        k_dyn = min(k, 23 - len(forced))
+        assert idx.shape == (2, 9, len(forced) + k_dyn)
+        for h in range(2):
+            for r in range(9):
+                rest = [j for j in range(23) if j not in forced]
+                best = sorted(rest, key=lambda j: (-s[h, r, j], j))[:k_dyn]
+                assert list(idx[h, r]) == sorted(best + list(forced))
+    assert np.array_equal(oracle.topk_with_forced(s, 6, []), oracle.topk(s, 6))
+    every = list(range(23))
+    assert np.array_equal(oracle.topk_with_forced(s, 4, every)[1, 3], every)      # k_dyn = 0
+    # a forced block that would have won anyway frees its slot for the runner-up
+    t = np.array([[[9.0, 1.0, 8.0, 7.0, 2.0]]])
+    assert list(oracle.topk(t, 2)[0, 0]) == [0, 2]
+    assert list(oracle.topk_with_forced(t, 2, [0])[0, 0]) == [0, 2, 3]
+    assert list(oracle.topk_with_forced(t, 2, [4])[0, 0]) == [0, 2, 4]
+    # ties among the free blocks still go to the smaller index
+    u = np.array([[[5.0, 5.0, 5.0, 5.0, 5.0]]])
+    assert list(oracle.topk_with_forced(u, 2, [1])[0, 0]) == [0, 1, 2]
+    with pytest.raises(AssertionError):
+        oracle.topk_with_forced(s, 2, [4, 4])
+    with pytest.raises(AssertionError):
+        oracle.topk_with_forced(s, 2, [7, 3])
+
+
 # ------------------------------------------------------ selection attention --
 
 @pytest.mark.parametrize("n,block", [(48, 8), (45, 8), (50, 16)])
@@ -352,6 +382,32 @@ def test_forward_agrees_with_bruteforce_route(oracle):
         out_ref[:, hh] = g * ocomp[np.arange(n) // b] + (1 - g) * osel[:, 0]
     assert np.array_equal(res["idx"], idx_ref)
     assert np.allclose(flat_tokens(oracle, res["out"], n, b), out_ref, rtol=0, atol=1e-13)
+
+
+def test_forward_with_forced_blocks(oracle):
+    n, h, d, b = 90, 2, 8, 8                                   # 12 blocks, ragged tail
+    q, k, v = rnd((n, h, d), 40), rnd((n, h, d), 41), rnd((n, h, d), 42)
+    scale = 1 / math.sqrt(d)
+    forced = [0, 1, 7]
+    res = oracle.gsa_forward(q, k, v, b, 3, forced=forced)
+    plain = oracle.gsa_forward(q, k, v, b, 3)
+    assert res["idx"].shape == (h, 12, 6)
+    assert np.all(np.isin(forced, res["idx"]).reshape(-1))
+    for hh in range(h):
+        for r in range(12):
+            assert set(forced) <= set(res["idx"][hh, r])
+    # the compressed branch does not depend on the selection set
+    assert np.array_equal(res["o_comp"], plain["o_comp"])
+    # selection branch = masked dense attention over the united set
+    osel, _ = masked_dense_bruteforce(q, k, v, res["idx"], b, scale)
+    assert np.allclose(flat_tokens(oracle, res["o_sel"], n, b), osel, rtol=0, atol=1e-13)
+    # forcing every block is dense attention
+    full = oracle.gsa_forward(q, k, v, b, 1, forced=list(range(12)))
+    assert np.allclose(flat_tokens(oracle, full["o_sel"], n, b), sdpa64(q, k, v, scale), atol=1e-13)
+    # forcing exactly the blocks TopK picks anyway for one row adds the next-best ones there
+    row = plain["idx"][0, 4]
+    again = oracle.gsa_forward(q, k, v, b, 3, forced=list(row))
+    assert set(row) < set(again["idx"][0, 4]) and again["idx"].shape[2] == 6
 
 
 def test_paper_sparse_ratios(oracle):
