@@ -70,11 +70,18 @@ typedef struct s3r_params {
     const void *q, *k, *v;   /* in   [n_tok][heads][head_dim]                                   */
     void *out;               /* out  [n_tok][heads][head_dim], merged result (eq. 8)            */
     const void *gate_logits; /* in, optional (NULL: g = 1/2), same layout and dtype as q        */
+    /* Forced blocks (Sec. 3.3: the fixed global context of the VGGT variant, e.g. all blocks of the
+     * reference view): n_forced block indices in DEVICE memory that every query block attends in
+     * addition to its TopK, which then runs over the other blocks only.  The list must be
+     * ascending, distinct and within [0, n_blk); out-of-range entries are clamped, not diagnosed. */
+    const int32_t *forced_blocks; /* in, optional (NULL: none)                                   */
+    int n_forced;            /* 0 when forced_blocks is NULL                                    */
     int64_t n_tok;
     int heads, head_dim, block, topk;
     s3r_dtype dtype;
     float softmax_scale;     /* <= 0: 1/sqrt(head_dim).  Used by both branches.                 */
-    int32_t *topk_idx;       /* out, optional: [heads][n_blk][k] ascending block indices        */
+    /* w = speed3r_selected_per_row(n_tok, block, topk, n_forced) blocks per row: */
+    int32_t *topk_idx;       /* out, optional: [heads][n_blk][w] ascending block indices        */
     float *lse_sel;          /* out, optional: [heads][n_tok], Alg. 2's L (natural log)         */
     float *o_comp;           /* out, optional: [heads][n_blk][head_dim] fp32, Oc' of eq. 3      */
     void *o_sel;             /* out, optional: [n_tok][heads][head_dim], O_sel of eq. 6         */
@@ -83,9 +90,14 @@ typedef struct s3r_params {
     void *stream;            /* hipStream_t                                                     */
 } s3r_params;
 
-/* Bytes of device scratch speed3r_sparse_global_attn_ex needs (0 on invalid arguments). */
-size_t speed3r_workspace_bytes(int64_t n_tok, int heads, int head_dim, int block, int topk,
+/* Bytes of device scratch speed3r_sparse_global_attn_ex needs (0 on invalid arguments) for
+ * the given n_forced (0 without forced blocks). */
+size_t speed3r_workspace_bytes(int64_t n_tok, int heads, int head_dim, int block, int topk, int n_forced,
                                s3r_dtype dtype);
+
+/* Key blocks each query block attends: n_forced + min(topk, n_blk - n_forced) (Sec. 3.3), or
+ * min(topk, n_blk) without forced blocks; -1 on invalid arguments. */
+int speed3r_selected_per_row(int64_t n_tok, int block, int topk, int n_forced);
 
 /* The whole GSA path (steps 1-6 above; Sec. 3.2, eqs. 3-8).  Re-entrant across streams when each
  * call has its own workspace.  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */

@@ -56,7 +56,8 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
     const bf16_t *__restrict__ qs_hi, const bf16_t *__restrict__ qs_lo,
     const bf16_t *__restrict__ ks_hi, const bf16_t *__restrict__ ks_lo,
     const bf16_t *__restrict__ vt_hi, const bf16_t *__restrict__ vt_lo, float *__restrict__ s_guide,
-    int64_t ld_s, float *__restrict__ o_comp, int64_t n_blk, int64_t tiles_padded, float scale_log2)
+    int64_t ld_s, float *__restrict__ o_comp, int64_t n_blk, int64_t tiles_padded, float scale_log2,
+    const unsigned long long *__restrict__ forced_words)
 {
     constexpr int NARR = SPLIT_PV ? 4 : 3;          // ks_hi, ks_lo, vt_hi [, vt_lo]
     constexpr int STAGE_ELEMS = 2 * kRowTileElems;   // 64 keys x 64 channels per array: 8 KiB
@@ -145,6 +146,7 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
             }
         }
         // eq. 4: raw scores out, 4 consecutive keys of one query row per store; never waited for
+        const unsigned long long fw = (forced_words != nullptr) ? forced_words[kt] : 0ull;  // wave-uniform
         if (qrow < n_blk) {
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
@@ -155,6 +157,12 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
                         floatx4 o;
 #pragma unroll
                         for (int i = 0; i < 4; ++i) o[i] = sacc[mt][4 * r4 + i];
+                        if (fw != 0ull) {  // forced blocks leave the TopK competition (Sec. 3.3)
+                            const unsigned nib = static_cast<unsigned>(fw >> (mt * 32 + 8 * r4 + 4 * g)) & 0xFu;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (nib & (1u << i)) o[i] = -INFINITY;
+                        }
                         *reinterpret_cast<floatx4 *>(srow + key0) = o;
                     }
                 }
@@ -237,7 +245,8 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
 template <bool SPLIT_PV, int NS, int CW>
 static hipError_t run_compress(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
                                const void *vt_hi, const void *vt_lo, float *s_guide, int64_t ld_s,
-                               float *o_comp, int64_t n_blk, int heads, float scale_log2, hipStream_t stream)
+                               float *o_comp, int64_t n_blk, int heads, float scale_log2,
+                               const unsigned long long *forced_words, hipStream_t stream)
 {
     const int64_t tiles = pooled_tiles_padded(n_blk);
     const int64_t q_tiles = (n_blk + 31) / 32;
@@ -246,21 +255,21 @@ static hipError_t run_compress(const void *qs_hi, const void *qs_lo, const void 
                        static_cast<const bf16_t *>(qs_hi), static_cast<const bf16_t *>(qs_lo),
                        static_cast<const bf16_t *>(ks_hi), static_cast<const bf16_t *>(ks_lo),
                        static_cast<const bf16_t *>(vt_hi), static_cast<const bf16_t *>(vt_lo), s_guide, ld_s,
-                       o_comp, n_blk, tiles, scale_log2);
+                       o_comp, n_blk, tiles, scale_log2, forced_words);
     return hipGetLastError();
 }
 
 hipError_t launch_compress(const void *qs_hi, const void *qs_lo, const void *ks_hi,
                            const void *ks_lo, const void *vt_hi, const void *vt_lo, float *s_guide,
                            int64_t ld_s, float *o_comp, int64_t n_blk, int heads, float scale,
-                           hipStream_t stream)
+                           const unsigned long long *forced_words, hipStream_t stream)
 {
     const float sl = scale * kLog2e;
     if (vt_lo != nullptr)
-        return run_compress<true, 2, 3>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk, heads, sl, stream);
+        return run_compress<true, 2, 3>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk, heads, sl, forced_words, stream);
     // 3 compute waves + 1 loader wave, 3 LDS stages (72 KiB): two workgroups per CU.  Measured
     // best on MI355X against 4 + 1 waves and 2 or 4 stages.
-    return run_compress<false, 3, 3>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk, heads, sl, stream);
+    return run_compress<false, 3, 3>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk, heads, sl, forced_words, stream);
 }
 
 }  // namespace s3r

@@ -24,10 +24,21 @@ hipError_t launch_split(const float *qc, const float *kc, const float *vc, void 
                         int heads, hipStream_t stream);
 
 // S_guide rows + compressed attention for `heads` heads (operand tiles as written by launch_split).
+// forced_words (optional): bit b of word kt set = pooled key 64 kt + b is a forced block; its
+// score is written as -inf so that TopK never picks it (it still takes part in the softmax).
 hipError_t launch_compress(const void *qs_hi, const void *qs_lo, const void *ks_hi,
                            const void *ks_lo, const void *vt_hi, const void *vt_lo, float *s_guide,
                            int64_t ld_s, float *o_comp, int64_t n_blk, int heads, float scale,
-                           hipStream_t stream);
+                           const unsigned long long *forced_words, hipStream_t stream);
+
+// Forced (always attended) blocks: clamp the caller's list into `forced_clean` and build the
+// 64-key bit words for the compression kernel.
+hipError_t launch_forced_prepare(const int32_t *forced, int n_forced, int64_t n_blk, int32_t *forced_clean,
+                                 unsigned long long *forced_words, hipStream_t stream);
+
+// out[r][0 .. k_dyn + n_forced) = ascending merge of dyn[r][0 .. k_dyn) and forced_clean[0 .. n_forced).
+hipError_t launch_merge_forced(const int32_t *dyn, int k_dyn, const int32_t *forced_clean, int n_forced,
+                               int32_t *out, int64_t n_rows, hipStream_t stream);
 
 // TopK of each of n_rows rows of s_guide (row r at s_guide + r * ld_s, n_blk valid entries).
 hipError_t launch_topk(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t n_blk,

@@ -61,15 +61,19 @@ s3r_status check_shape(int64_t n_tok, int heads, int head_dim, int block, int to
 // ---- workspace layout of the full path -------------------------------------------------------
 struct Layout {
     int64_t n_blk, tiles, ld_s;
-    int kk, head_chunk;
-    size_t qc, kc, vc, oc, tile[6], idx, s, kb, vb, total;
+    int kk;      // blocks TopK picks per row (among the non-forced ones)
+    int width;   // blocks attended per row: kk + n_forced
+    int head_chunk;
+    size_t qc, kc, vc, oc, tile[6], idx, idx_merged, forced_clean, forced_words, s, kb, vb, total;
 };
 
-Layout make_layout(int64_t n_tok, int heads, int block, int topk, s3r_dtype dtype)
+Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, s3r_dtype dtype)
 {
     Layout L{};
     L.n_blk = (n_tok + block - 1) / block;
-    L.kk = static_cast<int>(topk < L.n_blk ? topk : L.n_blk);
+    const int64_t free_blk = L.n_blk - n_forced;
+    L.kk = static_cast<int>(topk < free_blk ? topk : free_blk);
+    L.width = L.kk + n_forced;
     L.tiles = s3r::pooled_tiles_padded(L.n_blk);
     L.ld_s = (L.n_blk + 63) / 64 * 64;
     const size_t per_head_s = static_cast<size_t>(L.n_blk) * L.ld_s * sizeof(float);
@@ -86,6 +90,9 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, s3r_dtype dtyp
     L.oc = take(pooled);
     for (int a = 0; a < 6; ++a) L.tile[a] = take(static_cast<size_t>(heads) * L.tiles * 32 * 64 * 2);
     L.idx = take(static_cast<size_t>(heads) * L.n_blk * L.kk * sizeof(int32_t));
+    L.idx_merged = take(n_forced > 0 ? static_cast<size_t>(heads) * L.n_blk * L.width * sizeof(int32_t) : 0);
+    L.forced_clean = take(static_cast<size_t>(n_forced) * sizeof(int32_t));
+    L.forced_words = take(n_forced > 0 ? static_cast<size_t>((L.n_blk + 63) / 64) * sizeof(unsigned long long) : 0);
     L.s = take(per_head_s * L.head_chunk);
     const size_t blocked = mfma_ok(dtype, block) ? static_cast<size_t>(heads) * L.n_blk * block * 64 * 2 : 0;
     L.kb = take(blocked);
@@ -166,7 +173,8 @@ char *at(void *base, size_t off) { return static_cast<char *>(base) + off; }
 s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, void *const tile[6],
                              float *s_buf, int64_t ld_s, int head_chunk, float *o_comp, int32_t *idx,
                              int64_t n_blk, int64_t tiles, int heads, int kk, float scale,
-                             bool accurate_pv, bool want_topk, hipStream_t stream)
+                             bool accurate_pv, bool want_topk, const unsigned long long *forced_words,
+                             hipStream_t stream)
 {
     {
         StageTimer tm(S3R_STAGE_SPLIT, stream);
@@ -184,10 +192,10 @@ s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, 
                                          at(tile[4], h0 * tile_head),
                                          accurate_pv ? at(tile[5], h0 * tile_head) : nullptr, s_buf, ld_s,
                                          o_comp + static_cast<size_t>(h0) * n_blk * 64, n_blk, hc, scale,
-                                         stream),
+                                         forced_words, stream),
                     "compress kernel launch");
         }
-        if (want_topk) {
+        if (want_topk && kk > 0) {
             StageTimer tm(S3R_STAGE_TOPK, stream);
             S3R_HIP(s3r::launch_topk(s_buf, ld_s, idx + static_cast<size_t>(h0) * n_blk * kk, n_blk,
                                      static_cast<int64_t>(hc) * n_blk, kk, stream),
@@ -251,10 +259,24 @@ s3r_status speed3r_release_scratch(void)
     return S3R_OK;
 }
 
-size_t speed3r_workspace_bytes(int64_t n_tok, int heads, int head_dim, int block, int topk, s3r_dtype dtype)
+size_t speed3r_workspace_bytes(int64_t n_tok, int heads, int head_dim, int block, int topk, int n_forced,
+                               s3r_dtype dtype)
 {
     if (check_shape(n_tok, heads, head_dim, block, topk, dtype) != S3R_OK) return 0;
-    return make_layout(n_tok, heads, block, topk, dtype).total;
+    if (n_forced < 0 || n_forced > (n_tok + block - 1) / block) {
+        fail(S3R_ERR_INVALID_ARG, "n_forced (%d) must lie in [0, n_blk]", n_forced);
+        return 0;
+    }
+    return make_layout(n_tok, heads, block, topk, n_forced, dtype).total;
+}
+
+int speed3r_selected_per_row(int64_t n_tok, int block, int topk, int n_forced)
+{
+    if (n_tok <= 0 || block <= 0 || topk <= 0 || n_forced < 0) return -1;
+    const int64_t n_blk = (n_tok + block - 1) / block;
+    if (n_forced > n_blk) return -1;
+    const int64_t free_blk = n_blk - n_forced;
+    return static_cast<int>(n_forced + (topk < free_blk ? topk : free_blk));
 }
 
 s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
@@ -268,7 +290,12 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
         !aligned16(p->topk_idx) || !aligned16(p->lse_sel))
         return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     if (p->out == p->q || p->out == p->k || p->out == p->v) return fail(S3R_ERR_INVALID_ARG, "out must not alias an input");
-    const Layout L = make_layout(p->n_tok, p->heads, p->block, p->topk, p->dtype);
+    const int n_forced = p->forced_blocks ? p->n_forced : 0;
+    if (p->n_forced < 0 || (p->n_forced > 0 && !p->forced_blocks) || (p->forced_blocks && p->n_forced == 0))
+        return fail(S3R_ERR_INVALID_ARG, "forced_blocks and n_forced (%d) must be given together", p->n_forced);
+    if (n_forced > (p->n_tok + p->block - 1) / p->block)
+        return fail(S3R_ERR_INVALID_ARG, "n_forced (%d) exceeds the number of blocks", n_forced);
+    const Layout L = make_layout(p->n_tok, p->heads, p->block, p->topk, n_forced, p->dtype);
     if (!p->workspace) return fail(S3R_ERR_WORKSPACE, "workspace is null (%zu bytes needed)", L.total);
     if ((reinterpret_cast<uintptr_t>(p->workspace) & (kAlign - 1)) != 0)
         return fail(S3R_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
@@ -284,7 +311,13 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     float *kc = reinterpret_cast<float *>(at(ws, L.kc));
     float *vc = reinterpret_cast<float *>(at(ws, L.vc));
     float *oc = p->o_comp ? p->o_comp : reinterpret_cast<float *>(at(ws, L.oc));
-    int32_t *idx = p->topk_idx ? p->topk_idx : reinterpret_cast<int32_t *>(at(ws, L.idx));
+    // idx_sel: what the selection kernel reads ([heads][n_blk][width]); idx_dyn: what TopK writes.
+    int32_t *idx_sel = p->topk_idx ? p->topk_idx
+                                   : reinterpret_cast<int32_t *>(at(ws, n_forced > 0 ? L.idx_merged : L.idx));
+    int32_t *idx_dyn = n_forced > 0 ? reinterpret_cast<int32_t *>(at(ws, L.idx)) : idx_sel;
+    int32_t *forced_clean = reinterpret_cast<int32_t *>(at(ws, L.forced_clean));
+    unsigned long long *forced_words =
+        n_forced > 0 ? reinterpret_cast<unsigned long long *>(at(ws, L.forced_words)) : nullptr;
     void *tile[6];
     for (int a = 0; a < 6; ++a) tile[a] = at(ws, L.tile[a]);
     void *kb = mfma ? at(ws, L.kb) : nullptr;
@@ -295,14 +328,25 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
         S3R_HIP(s3r::launch_pool(p->q, p->k, p->v, qc, kc, vc, kb, vb, p->n_tok, p->heads, p->block, is_bf16, stream),
                 "pool kernel launch");
     }
+    if (n_forced > 0) {
+        StageTimer tm(S3R_STAGE_TOPK, stream);
+        S3R_HIP(s3r::launch_forced_prepare(p->forced_blocks, n_forced, L.n_blk, forced_clean, forced_words, stream),
+                "forced-block prepare kernel launch");
+    }
     st = run_compress_topk(qc, kc, vc, tile, reinterpret_cast<float *>(at(ws, L.s)), L.ld_s, L.head_chunk, oc,
-                           idx, L.n_blk, L.tiles, p->heads, L.kk, scale, !is_bf16, true, stream);
+                           idx_dyn, L.n_blk, L.tiles, p->heads, L.kk, scale, !is_bf16, true, forced_words, stream);
     if (st != S3R_OK) return st;
+    if (n_forced > 0) {
+        StageTimer tm(S3R_STAGE_TOPK, stream);
+        S3R_HIP(s3r::launch_merge_forced(idx_dyn, L.kk, forced_clean, n_forced, idx_sel,
+                                         static_cast<int64_t>(p->heads) * L.n_blk, stream),
+                "forced-block merge kernel launch");
+    }
 
     s3r::SelectArgs a{};
-    a.q = p->q; a.k = p->k; a.v = p->v; a.kb = kb; a.vb = vb; a.idx = idx; a.o_comp = oc;
+    a.q = p->q; a.k = p->k; a.v = p->v; a.kb = kb; a.vb = vb; a.idx = idx_sel; a.o_comp = oc;
     a.gate = p->gate_logits; a.out = p->out; a.o_sel = p->o_sel; a.lse = p->lse_sel;
-    a.n_tok = p->n_tok; a.n_blk = L.n_blk; a.heads = p->heads; a.block = p->block; a.kk = L.kk;
+    a.n_tok = p->n_tok; a.n_blk = L.n_blk; a.heads = p->heads; a.block = p->block; a.kk = L.width;
     a.scale = scale; a.is_bf16 = is_bf16;
     {
         StageTimer tm(S3R_STAGE_SELECT, stream);
@@ -321,7 +365,7 @@ int speed3r_sparse_global_attn(const void *q, const void *k, const void *v, void
     p.q = q; p.k = k; p.v = v; p.out = out;
     p.n_tok = n_tok; p.heads = heads; p.head_dim = head_dim; p.block = block; p.topk = topk;
     p.dtype = S3R_BF16; p.softmax_scale = 0.f; p.stream = stream;
-    p.workspace_bytes = speed3r_workspace_bytes(n_tok, heads, head_dim, block, topk, S3R_BF16);
+    p.workspace_bytes = speed3r_workspace_bytes(n_tok, heads, head_dim, block, topk, 0, S3R_BF16);
     st = scratch_get(p.workspace_bytes, &p.workspace);
     if (st != S3R_OK) return st;
     return speed3r_sparse_global_attn_ex(&p);
@@ -358,7 +402,7 @@ s3r_status speed3r_compress_attn_scores(const float *qc, const float *kc, const 
     void *tile[6];
     for (int a = 0; a < 6; ++a) tile[a] = at(ws, a * arr);
     return run_compress_topk(qc, kc, vc, tile, s_guide, ld_s, heads, o_comp, nullptr, n_blk, tiles, heads, 0,
-                             resolve_scale(softmax_scale, head_dim), accurate_pv != 0, false,
+                             resolve_scale(softmax_scale, head_dim), accurate_pv != 0, false, nullptr,
                              static_cast<hipStream_t>(stream));
 }
 

@@ -308,6 +308,71 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(const float *
     topk_exact_path(row, out, n_blk, k, scratch, wave_cnt);
 }
 
+// Forced blocks (Sec. 3.3): one workgroup clamps the caller's list and sets the per-64-key bit words.
+__global__ __launch_bounds__(256) void forced_prepare_kernel(const int32_t *__restrict__ forced, int n_forced,
+                                                             int n_blk, int32_t *__restrict__ forced_clean,
+                                                             unsigned long long *__restrict__ words, int n_words)
+{
+    for (int w = threadIdx.x; w < n_words; w += 256) words[w] = 0ull;
+    __syncthreads();
+    for (int a = threadIdx.x; a < n_forced; a += 256) {
+        int j = forced[a];
+        j = j < 0 ? 0 : (j >= n_blk ? n_blk - 1 : j);
+        forced_clean[a] = j;
+        atomicOr(&words[j >> 6], 1ull << (j & 63));
+    }
+}
+
+// One thread per output entry: an element's place in the merged list is its own position plus the
+// number of elements of the other list that sort before it (forced entries first on equal values,
+// which only arises if the caller's list breaks its contract).
+__global__ __launch_bounds__(256) void merge_forced_kernel(const int32_t *__restrict__ dyn, int k_dyn,
+                                                           const int32_t *__restrict__ forced, int n_forced,
+                                                           int32_t *__restrict__ out, int64_t n_rows)
+{
+    const int w = k_dyn + n_forced;
+    const int64_t gid = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (gid >= n_rows * w) return;
+    const int64_t r = gid / w;
+    const int e = static_cast<int>(gid % w);
+    const int32_t *drow = dyn + r * k_dyn;
+    int32_t v;
+    int pos;
+    if (e < n_forced) {  // a forced entry: count dynamic entries strictly smaller
+        v = forced[e];
+        int lo = 0, hi = k_dyn;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (drow[mid] < v) lo = mid + 1; else hi = mid; }
+        pos = e + lo;
+    } else {  // a dynamic entry: count forced entries smaller or equal
+        const int d = e - n_forced;
+        v = drow[d];
+        int lo = 0, hi = n_forced;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (forced[mid] <= v) lo = mid + 1; else hi = mid; }
+        pos = d + lo;
+    }
+    out[r * w + pos] = v;
+}
+
+hipError_t launch_forced_prepare(const int32_t *forced, int n_forced, int64_t n_blk, int32_t *forced_clean,
+                                 unsigned long long *forced_words, hipStream_t stream)
+{
+    const int n_words = static_cast<int>((n_blk + 63) / 64);
+    hipLaunchKernelGGL(forced_prepare_kernel, dim3(1), dim3(256), 0, stream, forced, n_forced,
+                       static_cast<int>(n_blk), forced_clean, forced_words, n_words);
+    return hipGetLastError();
+}
+
+hipError_t launch_merge_forced(const int32_t *dyn, int k_dyn, const int32_t *forced_clean, int n_forced,
+                               int32_t *out, int64_t n_rows, hipStream_t stream)
+{
+    const int64_t total = n_rows * (k_dyn + n_forced);
+    const int64_t grid = (total + 255) / 256;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(merge_forced_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0, stream, dyn, k_dyn,
+                       forced_clean, n_forced, out, n_rows);
+    return hipGetLastError();
+}
+
 hipError_t launch_topk(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t n_blk,
                        int64_t n_rows, int k, hipStream_t stream)
 {

@@ -127,3 +127,16 @@ def make_gate_logits(wl: Workload, device="cpu"):
     g = torch.randn((wl.n_tok, wl.heads, wl.head_dim), generator=gen, device=device,
                     dtype=torch.float32)
     return g.to(wl.torch_dtype)
+
+
+def vggt_forced_blocks(wl: Workload, view_stride: int = 100):
+    """Block indices of the fixed global context of the VGGT variant (Sec. 3.3): every block that
+    holds a token of the reference view (view 0) or of a view at a multiple of `view_stride`.
+    Ascending, distinct, int32 numpy array."""
+    import numpy as np
+    blocks = []
+    for view in range(0, wl.views, view_stride):
+        first = view * wl.tokens_per_view // wl.block
+        last = ((view + 1) * wl.tokens_per_view - 1) // wl.block
+        blocks.extend(range(first, last + 1))
+    return np.unique(np.asarray(blocks, dtype=np.int32))

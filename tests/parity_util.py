@@ -68,7 +68,7 @@ def check_topk_sets(s_rows, gpu_idx, k):
                 n_exact += 1
                 continue
             tau = s[order[k - 1]]
-            s_next = s[order[k]] if k < n_blk else tau
+            s_next = s[order[k]] if k < n_blk and np.isfinite(s[order[k]]) else tau
             delta = TIE_REL * max(abs(tau), abs(s_next), 1e-30)
             chosen = np.zeros(n_blk, dtype=bool)
             chosen[got] = True
@@ -89,11 +89,14 @@ def to_host_f32(t: torch.Tensor) -> np.ndarray:
     return t.detach().to("cpu").to(torch.float32).numpy()
 
 
-def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "lse", "o_comp", "o_sel")):
-    """One call of the whole path through the C ABI; returns numpy results."""
+def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "lse", "o_comp", "o_sel"),
+               forced=None):
+    """One call of the whole path through the C ABI; returns device tensors.  `forced`: ascending
+    block indices (host array) every query block attends besides its TopK."""
     n_tok, heads, d = q.shape
     n_blk = (n_tok + block - 1) // block
-    kk = min(topk, n_blk)
+    n_forced = 0 if forced is None else len(forced)
+    kk = s3r.speed3r_selected_per_row(n_tok, block, topk, n_forced)
     dev = q.device
     out = torch.full_like(q, float("nan"))
     bufs = {}
@@ -105,8 +108,9 @@ def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "ls
         bufs["o_comp"] = torch.full((heads, n_blk, d), float("nan"), dtype=torch.float32, device=dev)
     if "o_sel" in want:
         bufs["o_sel"] = torch.full_like(q, float("nan"))
+    forced_t = None if n_forced == 0 else torch.from_numpy(np.asarray(forced, dtype=np.int32)).to(dev)
     s3r.speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, gate_logits=gate,
-                                      softmax_scale=scale, **bufs)
+                                      softmax_scale=scale, forced_blocks=forced_t, **bufs)
     torch.cuda.synchronize()
     res = {"out": out}
     res.update({"idx": bufs.get("topk_idx"), "lse": bufs.get("lse_sel"),
@@ -115,11 +119,13 @@ def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "ls
 
 
 def compare_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, dtype, rows=None, scale=None,
-                        label=""):
+                        label="", forced=None):
     """Element-by-element comparison of a device result (tensors from run_device) with the oracle
     on the query blocks `rows` (all when None).  qf, kf, vf, gate_f: host float32 arrays holding
     exactly the device inputs.  TopK sets are checked with the near-tie rule; selection outputs are
-    compared against the oracle evaluated on the device's (validated) index sets."""
+    compared against the oracle evaluated on the device's (validated) index sets.  With `forced`
+    blocks every device set must hold them all, and what remains is checked as the TopK of the
+    scores with the forced columns removed from the competition."""
     n_tok, heads, d = qf.shape
     n_blk = (n_tok + block - 1) // block
     kk = min(topk, n_blk)
@@ -142,7 +148,25 @@ def compare_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, dtype,
         stats["o_comp"] = assert_close(g, o_comp, tol, f"{label} o_comp")
     assert dev_res.get("idx") is not None
     gidx = dev_res["idx"][:, torch.from_numpy(rows).to(dev_res["idx"].device)].cpu().numpy()
-    n_exact, n_tie = check_topk_sets(s, gidx, kk)
+    if forced is None or len(forced) == 0:
+        n_exact, n_tie = check_topk_sets(s, gidx, kk)
+    else:
+        forced = np.asarray(forced, dtype=np.int64)
+        k_dyn = min(topk, n_blk - forced.size)
+        assert gidx.shape[2] == forced.size + k_dyn, (gidx.shape, forced.size, k_dyn)
+        assert np.all(np.diff(gidx, axis=2) > 0), "united index sets not strictly ascending"
+        assert gidx.min() >= 0 and gidx.max() < n_blk
+        is_forced = np.isin(gidx, forced)
+        assert np.all(is_forced.sum(axis=2) == forced.size), "a forced block is missing from a device set"
+        n_exact = n_tie = 0
+        if k_dyn > 0:
+            dyn = gidx[~is_forced].reshape(gidx.shape[0], gidx.shape[1], k_dyn)
+            s_free = s.copy()
+            s_free[:, :, forced] = -np.inf
+            n_exact, n_tie = check_topk_sets(s_free, dyn, k_dyn)
+            want = oracle.topk_with_forced(s, topk, forced)
+            if n_tie == 0:
+                assert np.array_equal(want, gidx)
     stats["topk_exact"], stats["topk_tie_resolved"] = n_exact, n_tie
     o_sel, lse = oracle.select_attn(qf, kf, vf, block, gidx, scale, rows)
     out = oracle.merge(o_comp, o_sel, gate_f, n_tok, block, rows)

@@ -64,6 +64,16 @@ def test_workspace_bytes_and_shape_validation(s3r):
     a = s3r.speed3r_workspace_bytes(10992, 16, 64, 64, 16, s3r.S3R_BF16)
     b = s3r.speed3r_workspace_bytes(137400, 16, 64, 64, 32, s3r.S3R_BF16)
     assert a < b < big
+    # forced blocks (Sec. 3.3) widen the index buffer; their count is bounded by n_blk
+    assert s3r.speed3r_workspace_bytes(10992, 16, 64, 64, 16, s3r.S3R_BF16, 22) > a
+    assert s3r.speed3r_workspace_bytes(1024, 2, 64, 64, 4, s3r.S3R_F32, 17) == 0
+    assert s3r.speed3r_workspace_bytes(1024, 2, 64, 64, 4, s3r.S3R_F32, -1) == 0
+    assert s3r.speed3r_selected_per_row(10992, 64, 16, 0) == 16
+    assert s3r.speed3r_selected_per_row(10992, 64, 16, 22) == 38
+    assert s3r.speed3r_selected_per_row(1000, 64, 16, 0) == 16          # 16 blocks
+    assert s3r.speed3r_selected_per_row(1000, 64, 16, 5) == 16          # 5 fixed + the 11 others
+    assert s3r.speed3r_selected_per_row(1000, 64, 4, 16) == 16          # nothing left to pick
+    assert lib.speed3r_selected_per_row(1000, 64, 4, 17) == -1
     # null / bad arguments are rejected before any device work
     assert lib.speed3r_sparse_global_attn_ex(None) == s3r.S3R_ERR_INVALID_ARG
     assert "null" in s3r.speed3r_last_error()
@@ -86,6 +96,11 @@ def test_workspace_bytes_and_shape_validation(s3r):
     assert "aligned" in s3r.speed3r_last_error()
     p.out = 0x2000
     assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_WORKSPACE       # no workspace
+    p.n_forced = 1                                                                            # count without a list
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_INVALID_ARG
+    p.forced_blocks, p.n_forced = 0x3000, 3                                                   # more than n_blk = 2
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_INVALID_ARG
+    p.forced_blocks, p.n_forced = None, 0
     assert lib.speed3r_topk_blocks(None, 8, None, 8, 1, 2, None) == s3r.S3R_ERR_INVALID_ARG
     assert lib.speed3r_compress_attn_scores(0x1000, 0x1000, 0x1000, 0x1000, 6, 0x1000, 8, 1, 64, 0.0, 0,
                                             None) == s3r.S3R_ERR_INVALID_ARG                  # ld_s < n_blk

@@ -193,7 +193,7 @@ def test_dense_attn(s3r, oracle, dtype, n_tok, choice):
 
 # ------------------------------------------------------------------------------- end to end --
 
-def end_to_end(s3r, oracle, wl, rows=None, with_gate=False, device_gen="cpu", label=None):
+def end_to_end(s3r, oracle, wl, rows=None, with_gate=False, device_gen="cpu", label=None, forced=None):
     label = label or wl.name
     log(f"{label}: drawing inputs n_tok={wl.n_tok} heads={wl.heads} block={wl.block} topk={wl.topk}")
     q, k, v = workloads.make_inputs(wl, device=device_gen)
@@ -201,11 +201,11 @@ def end_to_end(s3r, oracle, wl, rows=None, with_gate=False, device_gen="cpu", la
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
     gd = None if gate is None else gate.cuda()
     log(f"{label}: device path")
-    res = run_device(s3r, qd, kd, vd, wl.block, wl.topk, gate=gd)
+    res = run_device(s3r, qd, kd, vd, wl.block, wl.topk, gate=gd, forced=forced)
     log(f"{label}: oracle")
     stats = compare_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v),
                                 None if gate is None else to_host_f32(gate), wl.block, wl.topk,
-                                wl.dtype, rows=rows, label=label)
+                                wl.dtype, rows=rows, label=label, forced=forced)
     log(f"{label}: {stats}")
     return stats
 
@@ -260,6 +260,52 @@ def test_config5_pi3_block128_small(s3r, oracle, topk):
     rng = np.random.default_rng(6)
     rows = np.unique(np.concatenate([[0, wl.n_blk - 1], rng.choice(wl.n_blk, 22, replace=False)]))
     end_to_end(s3r, oracle, wl, rows=rows, with_gate=(topk == 16))
+
+
+# ------------------------------------------------- forced global-context blocks (Sec. 3.3) --
+
+def test_forced_blocks_vggt_8_views(s3r, oracle):
+    """Reference view always attended: its blocks join every row's set and leave the TopK."""
+    wl = workloads.config(2)
+    forced = workloads.vggt_forced_blocks(wl)
+    assert forced[0] == 0 and len(forced) == (wl.tokens_per_view - 1) // wl.block + 1
+    end_to_end(s3r, oracle, wl, with_gate=True, forced=forced, label="config2+reference view")
+
+
+def test_forced_blocks_view_stride_sampled_rows(s3r, oracle):
+    """Views at a stride (here every 10th of 30) forced, on top of TopK over the rest."""
+    wl = workloads.config(3, views=30)
+    forced = workloads.vggt_forced_blocks(wl, view_stride=10)
+    rng = np.random.default_rng(15)
+    rows = np.unique(np.concatenate([[0, int(forced[-1]), wl.n_blk - 1], rng.choice(wl.n_blk, 20, replace=False)]))
+    end_to_end(s3r, oracle, wl, rows=rows, forced=forced, device_gen="cuda", label="config3/30views+stride10")
+
+
+@pytest.mark.parametrize("dtype,block,n_tok,topk,forced", [
+    ("f32", 16, 333, 4, [0, 1, 20]),                 # generic kernels, ragged tail, last block forced
+    ("f32", 64, 1000, 3, [5]),
+    ("bf16", 64, 1000, 5, [0, 3, 4, 15]),            # 16 blocks; last (ragged) one forced
+    ("bf16", 64, 1000, 14, [1, 2]),                  # topk + forced = n_blk: every block attended
+    ("bf16", 64, 1000, 64, [0, 7, 9]),               # topk > free blocks: k_dyn clamps to 13
+    ("bf16", 64, 1024, 2, list(range(16))),          # everything forced: TopK has nothing to pick
+    ("bf16", 128, 1100, 2, [0, 8]),
+    ("bf16", 64, 70 * 64, 3, list(range(60, 70))),   # forced bits in the second 64-key word only
+    ("bf16", 64, 130 * 64 + 7, 6, [0, 63, 64, 127, 128, 130]),   # word boundaries
+])
+def test_forced_blocks_edge_cases(s3r, oracle, dtype, block, n_tok, topk, forced):
+    wl = workloads.Workload(f"forced_{dtype}_{block}_{n_tok}_{topk}", 1, n_tok, 2, 64, dtype, block, topk, 91,
+                            "normal")
+    end_to_end(s3r, oracle, wl, with_gate=True, forced=np.asarray(forced, dtype=np.int32))
+
+
+def test_forced_blocks_leave_compressed_branch_unchanged(s3r):
+    """The forced list only changes the selection set: Oc' is bit-identical with and without it."""
+    wl = workloads.config(2, views=4)
+    q, k, v = (t.cuda() for t in workloads.make_inputs(wl))
+    plain = run_device(s3r, q, k, v, wl.block, wl.topk)
+    forced = run_device(s3r, q, k, v, wl.block, wl.topk, forced=workloads.vggt_forced_blocks(wl))
+    assert torch.equal(plain["o_comp"], forced["o_comp"])
+    assert forced["idx"].shape[2] == plain["idx"].shape[2] + len(workloads.vggt_forced_blocks(wl))
 
 
 @pytest.mark.parametrize("n_tok,block,topk,dtype", [(1, 64, 4, "bf16"), (63, 64, 1, "bf16"), (65, 64, 2, "bf16"),
