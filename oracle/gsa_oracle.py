@@ -269,3 +269,46 @@ def rows_to_tokens(x_rows, rows, n_tok: int, block: int):
     vals = np.asarray(x_rows).reshape((tok.size,) + tuple(np.asarray(x_rows).shape[2:]))
     keep = tok < n_tok
     return tok[keep], vals[keep]
+
+
+def token_partition(n_tok: int, tokens_per_view: int, special_per_view: int):
+    """Row indices (spec_rows, img_rows) of the special and image tokens of a sequence made of
+    views of `tokens_per_view` rows whose first `special_per_view` rows are special tokens
+    (camera / register tokens, Sec. 3.2 eq. 1; one view holding everything is the paper's own
+    [X_spec; X_img] arrangement)."""
+    assert tokens_per_view > 0 and n_tok % tokens_per_view == 0
+    assert 0 <= special_per_view < tokens_per_view
+    pos = np.arange(n_tok, dtype=np.int64) % tokens_per_view
+    return np.nonzero(pos < special_per_view)[0], np.nonzero(pos >= special_per_view)[0]
+
+
+def gsa_layer(q, k, v, block: int, topk_blocks: int, tokens_per_view: int, special_per_view: int,
+              gate=None, scale=None, rows=None, forced=None, idx_override=None) -> dict:
+    """The whole layer of Sec. 3.2 on a sequence holding special and image tokens.
+
+    Special tokens: plain softmax attention over ALL tokens (eq. 2).  Image tokens: the sparse
+    two-branch path (eqs. 3-8) among the image tokens only, taken in their original order
+    (`rows`, `forced`, `idx_override` refer to blocks of that image-only sequence).  The
+    results go back to the rows they came from ("concatenating ... in their original order").
+
+    Returns {"spec_rows", "o_spec" [n_spec, heads, d], "img_rows", "img": gsa_forward's
+    dictionary on the image tokens, "out" [n_tok, heads, d] (only when rows is None)}."""
+    q = _f32(q)
+    k = _f32(k, q.shape)
+    v = _f32(v, q.shape)
+    n_tok, heads, d = q.shape
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(d)
+    spec_rows, img_rows = token_partition(n_tok, tokens_per_view, special_per_view)
+    o_spec = dense_attn(q, k, v, scale, q_tok=spec_rows) if spec_rows.size else np.zeros((0, heads, d))
+    g_img = None if gate is None else _f32(gate, q.shape)[img_rows]
+    img = gsa_forward(q[img_rows], k[img_rows], v[img_rows], block, topk_blocks, gate=g_img, scale=scale,
+                      rows=rows, forced=forced, idx_override=idx_override)
+    res = {"spec_rows": spec_rows, "o_spec": o_spec, "img_rows": img_rows, "img": img}
+    if rows is None:
+        out = np.empty((n_tok, heads, d), dtype=np.float64)
+        out[spec_rows] = o_spec
+        tok, vals = rows_to_tokens(img["out"], img["rows"], img_rows.size, block)
+        out[img_rows[tok]] = vals
+        res["out"] = out
+    return res

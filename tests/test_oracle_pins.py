@@ -410,6 +410,54 @@ def test_forward_with_forced_blocks(oracle):
     assert set(row) < set(again["idx"][0, 4]) and again["idx"].shape[2] == 6
 
 
+def test_layer_special_tokens_dense_and_concat_order(oracle):
+    # Eq. 2 for the special rows, eqs. 3-8 among the image rows, results back in place.
+    T, s_, views, h, d, b = 13, 2, 3, 2, 8, 4                  # 11 image tokens per view: blocks straddle views
+    n = T * views
+    q, k, v = rnd((n, h, d), 50), rnd((n, h, d), 51), rnd((n, h, d), 52)
+    gate = rnd((n, h, d), 53)
+    scale = 1 / math.sqrt(d)
+    res = oracle.gsa_layer(q, k, v, b, 3, T, s_, gate=gate)
+    spec = [t for t in range(n) if t % T < s_]
+    img = [t for t in range(n) if t % T >= s_]
+    assert list(res["spec_rows"]) == spec and list(res["img_rows"]) == img
+    dense = sdpa64(q, k, v, scale)                               # every row over every key
+    assert np.allclose(res["out"][spec], dense[spec], atol=1e-13)
+    # image rows: the plain path on the image tokens alone (special keys never enter it)
+    alone = oracle.gsa_forward(q[img], k[img], v[img], b, 3, gate=gate[img])
+    assert np.array_equal(res["img"]["idx"], alone["idx"])
+    assert np.allclose(res["out"][img], flat_tokens(oracle, alone["out"], len(img), b), atol=0)
+    # topk >= n_blk: the selection branch is dense attention among the image tokens only
+    full = oracle.gsa_layer(q, k, v, b, 100, T, s_)
+    o_sel = flat_tokens(oracle, full["img"]["o_sel"], len(img), b)
+    assert np.allclose(o_sel, sdpa64(q[img], k[img], v[img], scale), atol=1e-13)
+    assert not np.allclose(o_sel, dense[img], atol=1e-3)        # ... so it differs from attention over all keys
+    # no special tokens: the layer is the plain path
+    plain = oracle.gsa_layer(q, k, v, b, 3, T, 0, gate=gate)
+    ref = oracle.gsa_forward(q, k, v, b, 3, gate=gate)
+    assert plain["spec_rows"].size == 0
+    assert np.array_equal(plain["out"], flat_tokens(oracle, ref["out"], n, b))
+
+
+def test_layer_row_bookkeeping_closed_form(oracle):
+    # q = k = 0: every softmax is uniform and every TopK is an all-way tie (first k blocks win), so
+    # with v[t] = t the outputs are means of known row numbers: any slip in the special / image
+    # bookkeeping changes them.
+    T, s_, views, b, kk = 7, 2, 4, 3, 2
+    n = T * views
+    z = np.zeros((n, 1, 4), dtype=np.float32)
+    v = np.tile(np.arange(n, dtype=np.float32)[:, None, None], (1, 1, 4))
+    res = oracle.gsa_layer(z, z, v, b, kk, T, s_)
+    img = [t for t in range(n) if t % T >= s_]                   # 20 image rows -> 7 blocks of 3 (tail 2)
+    assert np.array_equal(res["img"]["idx"][0], np.tile([0, 1], (7, 1)))
+    o_sel = np.mean(img[:kk * b])                                # rows 2..6 and 9: first two image blocks
+    blk_means = [np.mean(img[j * b:(j + 1) * b]) for j in range(7)]
+    o_comp = np.mean(blk_means)                                  # uniform over the 7 pooled values
+    for t in range(n):
+        want = np.mean(np.arange(n)) if t % T < s_ else 0.5 * o_comp + 0.5 * o_sel
+        assert np.allclose(res["out"][t], want, atol=1e-12), t
+
+
 def test_paper_sparse_ratios(oracle):
     """Table 2 prints 94 % (pi3 variant) and 84 % (VGGT variant, reference view always
     attended) at 10 views and top-32; counted on the selection stage both follow from
