@@ -105,6 +105,10 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload (1..5); the metric is quoted on 4")
     ap.add_argument("--views", type=int, default=None, help="override the number of views")
     ap.add_argument("--topk", type=int, default=None)
+    ap.add_argument("--special", type=int, default=0,
+                    help="treat the first N tokens of every view as special tokens (dense rows); not the headline metric")
+    ap.add_argument("--forced-vggt", action="store_true",
+                    help="force the blocks of the reference view and of every 100th view; not the headline metric")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense denominator run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget-s", type=float, default=20.0)
@@ -129,15 +133,25 @@ def main():
     say(f"workload {wl.name}: n_tok={wl.n_tok} heads={wl.heads} block={wl.block} topk={wl.topk} {wl.dtype}")
     q, k, v = workloads.make_inputs(wl, device=dev)
     out = torch.empty_like(q)
-    kk = min(wl.topk, wl.n_blk)
-    idx = torch.empty((wl.heads, wl.n_blk, kk), dtype=torch.int32, device=dev)
+    # the sequence the sparse path works on: every token, or the image tokens when --special is given
+    seq = workloads.Workload(wl.name, wl.views, wl.tokens_per_view - args.special, wl.heads, wl.head_dim, wl.dtype,
+                             wl.block, wl.topk, wl.seed, wl.kind)
+    forced = None
+    if args.forced_vggt:
+        forced = torch.from_numpy(workloads.vggt_forced_blocks(seq)).to(dev)
+    n_forced = 0 if forced is None else forced.numel()
+    kk = s3r.speed3r_selected_per_row(seq.n_tok, wl.block, wl.topk, n_forced)
+    idx = torch.empty((wl.heads, seq.n_blk, kk), dtype=torch.int32, device=dev)
     dt_code = s3r.S3R_BF16 if wl.dtype == "bf16" else s3r.S3R_F32
-    ws_bytes = s3r.speed3r_workspace_bytes(wl.n_tok, wl.heads, wl.head_dim, wl.block, wl.topk, dt_code)
+    tpv = wl.tokens_per_view if args.special else 0
+    ws_bytes = s3r.speed3r_workspace_bytes_ex(wl.n_tok, wl.heads, wl.head_dim, wl.block, wl.topk, dt_code,
+                                              n_forced, tpv, args.special)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     say(f"workspace {ws_bytes / 2**30:.2f} GiB")
 
     def step():
-        s3r.speed3r_sparse_global_attn_ex(q, k, v, out, wl.block, wl.topk, topk_idx=idx, workspace=ws)
+        s3r.speed3r_sparse_global_attn_ex(q, k, v, out, wl.block, wl.topk, topk_idx=idx, workspace=ws,
+                                          forced_blocks=forced, tokens_per_view=tpv, special_per_view=args.special)
 
     if args.pmc_calibration:
         src = torch.ones(2 ** 29, dtype=torch.bfloat16, device=dev)      # 1 GiB read + 1 GiB written
@@ -163,17 +177,18 @@ def main():
         + ", ".join(f"{s}={stage_ms[s] / args.steps:.3f}" for s in ("pool", "split", "compress", "topk", "select")))
 
     # roofline of the dominant kernel (selection attention, bf16 MFMA): executed FLOPs only
-    pairs = valid_pairs(idx, wl.n_tok, wl.block)
+    pairs = valid_pairs(idx, seq.n_tok, wl.block)
     sel_flops = 4.0 * wl.head_dim * pairs
     sel_ms = stage_ms["select"] / max(stage_n["select"], 1)
     achieved = sel_flops / (sel_ms * 1e-3) / 1e12
     roofline = {"kernel": "select_mfma_kernel" if wl.dtype == "bf16" and wl.block in (64, 128) else "select_generic_kernel",
                 "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(wl),
+                "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": None if (args.special or n_forced) else measured_traffic(wl),
                 "kernel_ms": sel_ms, "flops_per_launch": sel_flops}
     # the same kernel seen from the memory side: K/V tiles of the selected blocks + Q read + out written, against what a bare gather of such pieces reaches
-    kv_bytes = float(wl.heads) * wl.n_blk * kk * 2 * wl.block * wl.head_dim * e_bytes(wl)
-    qo_bytes = 2.0 * wl.n_tok * wl.heads * wl.head_dim * e_bytes(wl)
+    kv_bytes = float(wl.heads) * seq.n_blk * kk * 2 * wl.block * wl.head_dim * e_bytes(wl)
+    qo_bytes = 2.0 * seq.n_tok * wl.heads * wl.head_dim * e_bytes(wl)
     roofline["memory_side"] = {"algorithmic_bytes_per_launch": kv_bytes + qo_bytes,
                                "achieved_GBps": (kv_bytes + qo_bytes) / (sel_ms * 1e-3) / 1e9,
                                "hbm_peak_GBps": 8000.0,
@@ -181,13 +196,16 @@ def main():
                                        "6.4-7.3 TB/s of L2-miss traffic on MI355X"}
     # HBM-side figures of the two bandwidth-bound stages (algorithmic bytes / measured time)
     e = 2 if wl.dtype == "bf16" else 4
-    pool_bytes = 3.0 * wl.n_tok * wl.heads * wl.head_dim * e + 3.0 * wl.n_blk * wl.heads * wl.head_dim * 4
-    topk_bytes = 4.0 * wl.n_blk * wl.n_blk * wl.heads + 4.0 * wl.n_blk * kk * wl.heads
+    pool_bytes = 3.0 * wl.n_tok * wl.heads * wl.head_dim * e + 3.0 * seq.n_blk * wl.heads * wl.head_dim * 4
+    topk_bytes = 4.0 * seq.n_blk * seq.n_blk * wl.heads + 4.0 * seq.n_blk * kk * wl.heads
     hbm = {"pool_GBps": pool_bytes / (stage_ms["pool"] / args.steps * 1e-3) / 1e9,
            "topk_GBps": topk_bytes / (stage_ms["topk"] / args.steps * 1e-3) / 1e9, "peak_GBps": 8000.0}
 
     result = {
-        "metric": ("sparse global-attn tokens/s at 1000 views" if wl.views == 1000 else "sparse global-attn tokens/s"),
+        "metric": ("sparse global-attn tokens/s at 1000 views" if wl.views == 1000 else "sparse global-attn tokens/s")
+                  + (" (VGGT-variant layer: " + ", ".join(x for x in (f"{args.special} special tokens per view" if args.special else "",
+                                                                       f"{n_forced} forced blocks" if n_forced else "") if x) + ")"
+                     if args.special or n_forced else ""),
         "value": wl.n_tok / (ms_per_step * 1e-3),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -201,6 +219,15 @@ def main():
         "hbm_stages": hbm,
         "paper_context": PAPER_CONTEXT,
     }
+    if args.special:
+        result["stage_ms_per_step"]["dense_special_rows"] = stage_ms["dense"] / args.steps
+        result["config"]["special_per_view"] = args.special
+        spec_flops = 4.0 * wl.head_dim * float(wl.views * args.special) * float(wl.n_tok) * wl.heads
+        result["special_rows"] = {"rows": wl.views * args.special,
+                                  "tflops": spec_flops / (stage_ms["dense"] / args.steps * 1e-3) / 1e12}
+    if n_forced:
+        result["config"]["forced_blocks"] = n_forced
+        result["config"]["blocks_per_query_block"] = kk
 
     if not args.no_dense:
         dense_out = torch.empty_like(q)
@@ -222,7 +249,7 @@ def main():
         say(f"dense {dense_s * 1e3:.1f} ms -> speed-up {result['speedup_vs_dense']:.1f}x")
         del dense_out
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.special and not n_forced:
         result["cpu_baseline"] = cpu_baseline(wl, q, k, v, idx, args.cpu_budget_s)
 
     print(json.dumps(result), flush=True)

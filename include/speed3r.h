@@ -76,13 +76,23 @@ typedef struct s3r_params {
      * ascending, distinct and within [0, n_blk); out-of-range entries are clamped, not diagnosed. */
     const int32_t *forced_blocks; /* in, optional (NULL: none)                                   */
     int n_forced;            /* 0 when forced_blocks is NULL                                    */
+    /* Special tokens (Sec. 3.2 eqs. 1-2 and "Final Output"): the n_tok rows come in views of
+     * tokens_per_view rows, the first special_per_view of each being special (camera / register)
+     * tokens.  Those rows get plain softmax attention over ALL n_tok rows; the remaining image rows,
+     * taken in order, form the sequence the sparse path works on (blocks, TopK, forced blocks and the
+     * optional block-level outputs all refer to that image-only sequence); every result is written to
+     * the row it belongs to.  Both 0: no special tokens.  tokens_per_view = n_tok with the special
+     * tokens first is the paper's own [X_spec; X_img] arrangement. */
+    int tokens_per_view;     /* 0, or a divisor of n_tok                                        */
+    int special_per_view;    /* 0 <= special_per_view < tokens_per_view                         */
     int64_t n_tok;
     int heads, head_dim, block, topk;
     s3r_dtype dtype;
     float softmax_scale;     /* <= 0: 1/sqrt(head_dim).  Used by both branches.                 */
     /* w = speed3r_selected_per_row(n_tok, block, topk, n_forced) blocks per row: */
     int32_t *topk_idx;       /* out, optional: [heads][n_blk][w] ascending block indices        */
-    float *lse_sel;          /* out, optional: [heads][n_tok], Alg. 2's L (natural log)         */
+    float *lse_sel;          /* out, optional: [heads][n_tok], Alg. 2's L (natural log); special
+                                rows are left untouched, and so are theirs in o_sel               */
     float *o_comp;           /* out, optional: [heads][n_blk][head_dim] fp32, Oc' of eq. 3      */
     void *o_sel;             /* out, optional: [n_tok][heads][head_dim], O_sel of eq. 6         */
     void *workspace;         /* caller-owned device scratch, 256-byte aligned                   */
@@ -94,6 +104,10 @@ typedef struct s3r_params {
  * the given n_forced (0 without forced blocks). */
 size_t speed3r_workspace_bytes(int64_t n_tok, int heads, int head_dim, int block, int topk, int n_forced,
                                s3r_dtype dtype);
+
+/* The same from a filled-in parameter block (only its shape fields are read: n_tok, heads, head_dim,
+ * block, topk, dtype, n_forced, tokens_per_view, special_per_view); needed with special tokens. */
+size_t speed3r_workspace_bytes_ex(const s3r_params *p);
 
 /* Key blocks each query block attends: n_forced + min(topk, n_blk - n_forced) (Sec. 3.3), or
  * min(topk, n_blk) without forced blocks; -1 on invalid arguments. */

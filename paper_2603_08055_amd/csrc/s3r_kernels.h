@@ -10,12 +10,28 @@ namespace s3r {
 // a 4-wave workgroup and a 64-key staging step never run past the allocation.
 inline int64_t pooled_tiles_padded(int64_t n_blk) { return ((n_blk + 31) / 32 + 3) / 4 * 4; }
 
+// Where the tokens of a sub-sequence sit in the caller's [rows][heads][64] tensors.  The rows come
+// in periods (views) of `period` rows; the sub-sequence takes the `count` consecutive rows that
+// start at row `first` of every period (image tokens: first = special tokens per view; special
+// tokens: first = 0).  period == 0 is the identity.  Sub-sequence indices must stay below 2^31.
+struct TokenMap {
+    int period = 0, first = 0, count = 0;
+    __host__ __device__ int64_t row(int64_t t) const
+    {
+        if (period == 0) return t;
+        const unsigned tt = static_cast<unsigned>(t);
+        const unsigned view = tt / static_cast<unsigned>(count);
+        return static_cast<int64_t>(view) * period + first + (tt - view * static_cast<unsigned>(count));
+    }
+};
+
 // Block means of q, k, v (fp32 [heads][n_blk][64]; any of qc/kc/vc may be null together) and,
 // when kb/vb are given (bf16 input, block 64 or 128), the per-(head, block) K and V tiles in
-// MFMA operand order: kb, vb are bf16 [heads][n_blk][block * 64].
+// MFMA operand order: kb, vb are bf16 [heads][n_blk][block * 64].  n_tok counts the tokens of the
+// sub-sequence `map` picks out of q, k, v; blocks are runs of that sub-sequence.
 hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, float *kc, float *vc,
                        void *kb, void *vb, int64_t n_tok, int heads, int block, bool is_bf16,
-                       hipStream_t stream);
+                       TokenMap map, hipStream_t stream);
 
 // Pooled fp32 -> bf16 hi/lo operand tiles ([heads][tiles_padded][32 * 64] each, zero padded).
 // vt_lo may be null.
@@ -45,16 +61,21 @@ hipError_t launch_topk(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t
                        int64_t n_rows, int k, hipStream_t stream);
 
 struct SelectArgs {
-    const void *q, *k, *v;     // [n_tok][heads][64], original layout
-    const void *kb, *vb;       // operand-order tiles (MFMA path only)
-    const int32_t *idx;        // [heads][n_blk][kk]; null = every block (dense attention)
+    const void *q, *k, *v;     // [rows][heads][64], the caller's layout
+    const void *kb, *vb;       // operand-order tiles of the keys (MFMA path only)
+    const void *kb2 = nullptr, *vb2 = nullptr;  // MFMA dense only: a second key segment, 64-key tiles
+    const int32_t *idx;        // [heads][n_blk][kk]; null = every key (dense attention)
     const float *o_comp;       // [heads][n_blk][64] or null (no merge)
-    const void *gate;          // [n_tok][heads][64] or null
-    void *out;                 // [n_tok][heads][64]
-    void *o_sel;               // optional
-    float *lse;                // optional [heads][n_tok]
-    int64_t n_tok;
-    int64_t n_blk;
+    const void *gate;          // [rows][heads][64] or null
+    void *out;                 // [rows][heads][64]
+    void *o_sel;               // optional, like out
+    float *lse;                // optional [heads][lse_stride], indexed by the caller's row
+    int64_t n_tok;             // query tokens (sub-sequence qmap picks)
+    int64_t n_keys;            // key tokens (tiles kb/vb; for the generic kernels the sub-sequence kmap picks)
+    int64_t n_keys2 = 0;       // keys of the second segment
+    int64_t n_blk;             // key blocks = ceil(n_keys / block); also the query blocks when idx is given
+    int64_t lse_stride;        // rows of the caller's tensors
+    TokenMap qmap, kmap;
     int heads, block, kk;
     float scale;
     bool is_bf16;

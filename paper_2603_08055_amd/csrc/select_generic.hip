@@ -16,8 +16,9 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
                                       const T *__restrict__ v, const int32_t *__restrict__ idx,
                                       const float *__restrict__ o_comp, const T *__restrict__ gate,
                                       T *__restrict__ out, T *__restrict__ o_sel, float *__restrict__ lse,
-                                      int64_t n_tok, int64_t n_blk, int heads, int block, int kk,
-                                      float scale_log2)
+                                      int64_t n_tok, int64_t n_qblk, int64_t n_keys, int heads, int block,
+                                      int kk, float scale_log2, TokenMap qmap, TokenMap kmap,
+                                      int64_t lse_stride)
 {
     __shared__ __attribute__((aligned(16))) float ks[kChunk][64];
     __shared__ __attribute__((aligned(16))) float vs[kChunk][64];
@@ -28,28 +29,30 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int64_t t = i * block + tid;
     const bool active = tid < block && t < n_tok;
+    const int64_t trow = qmap.row(active ? t : 0);  // the caller's row of this query
+    const int64_t n_kblk = (n_keys + block - 1) / block;
 
     float qr[64], acc[64];
 #pragma unroll
     for (int c = 0; c < 64; ++c) {
-        qr[c] = active ? to_float(q[(t * heads + h) * 64 + c]) : 0.f;
+        qr[c] = active ? to_float(q[(trow * heads + h) * 64 + c]) : 0.f;
         acc[c] = 0.f;
     }
     float m_run = -1e30f, l_run = 0.f;
 
-    const int64_t n_sel = (idx != nullptr) ? kk : n_blk;
-    const int32_t *sel = (idx != nullptr) ? idx + (static_cast<int64_t>(h) * n_blk + i) * kk : nullptr;
+    const int64_t n_sel = (idx != nullptr) ? kk : n_kblk;
+    const int32_t *sel = (idx != nullptr) ? idx + (static_cast<int64_t>(h) * n_qblk + i) * kk : nullptr;
 
     for (int64_t a = 0; a < n_sel; ++a) {
         const int64_t j = (sel != nullptr) ? sel[a] : a;
         const int64_t u0 = j * block;
-        const int len = static_cast<int>((n_tok - u0 < block) ? (n_tok - u0) : block);
+        const int len = static_cast<int>((n_keys - u0 < block) ? (n_keys - u0) : block);
         for (int c0 = 0; c0 < len; c0 += kChunk) {
             const int nk = (len - c0 < kChunk) ? (len - c0) : kChunk;
             __syncthreads();
             for (int e = tid; e < nk * 64; e += nthr) {
                 const int r = e >> 6, c = e & 63;
-                const int64_t src = ((u0 + c0 + r) * heads + h) * 64 + c;
+                const int64_t src = (kmap.row(u0 + c0 + r) * heads + h) * 64 + c;
                 ks[r][c] = to_float(k[src]);
                 vs[r][c] = to_float(v[src]);
             }
@@ -98,9 +101,9 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
 
     if (!active) return;
     const float inv = 1.f / l_run;
-    const int64_t o = (t * heads + h) * 64;
-    if (lse != nullptr) lse[static_cast<int64_t>(h) * n_tok + t] = (m_run + __builtin_log2f(l_run)) * kLn2;
-    const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_blk + i) * 64 : nullptr;
+    const int64_t o = (trow * heads + h) * 64;
+    if (lse != nullptr) lse[static_cast<int64_t>(h) * lse_stride + trow] = (m_run + __builtin_log2f(l_run)) * kLn2;
+    const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_qblk + i) * 64 : nullptr;
 #pragma unroll
     for (int c = 0; c < 64; ++c) {
         const float os = acc[c] * inv;
@@ -117,8 +120,12 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
 
 hipError_t launch_select_generic(const SelectArgs &a, hipStream_t stream)
 {
-    const int64_t grid = a.n_blk * a.heads;
+    const int64_t n_qblk = (a.n_tok + a.block - 1) / a.block;
+    const int64_t grid = n_qblk * a.heads;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if ((a.qmap.period != 0 && a.n_tok > 0x7fffffffLL) || (a.kmap.period != 0 && a.n_keys > 0x7fffffffLL))
+        return hipErrorInvalidValue;
+    if (a.idx != nullptr && a.n_keys != a.n_tok) return hipErrorInvalidValue;
     const int threads = a.block < 64 ? 64 : a.block;
     const float scale_log2 = a.scale * kLog2e;
     if (a.is_bf16) {
@@ -126,15 +133,15 @@ hipError_t launch_select_generic(const SelectArgs &a, hipStream_t stream)
                            0, stream, static_cast<const bf16_t *>(a.q), static_cast<const bf16_t *>(a.k),
                            static_cast<const bf16_t *>(a.v), a.idx, a.o_comp,
                            static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
-                           static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.block,
-                           a.kk, scale_log2);
+                           static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, n_qblk, a.n_keys, a.heads,
+                           a.block, a.kk, scale_log2, a.qmap, a.kmap, a.lse_stride);
     } else {
         hipLaunchKernelGGL(select_generic_kernel<float>, dim3(static_cast<unsigned>(grid)), dim3(threads),
                            0, stream, static_cast<const float *>(a.q), static_cast<const float *>(a.k),
                            static_cast<const float *>(a.v), a.idx, a.o_comp,
                            static_cast<const float *>(a.gate), static_cast<float *>(a.out),
-                           static_cast<float *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.block, a.kk,
-                           scale_log2);
+                           static_cast<float *>(a.o_sel), a.lse, a.n_tok, n_qblk, a.n_keys, a.heads, a.block,
+                           a.kk, scale_log2, a.qmap, a.kmap, a.lse_stride);
     }
     return hipGetLastError();
 }

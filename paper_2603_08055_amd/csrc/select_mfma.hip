@@ -73,7 +73,8 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const int32_t *__restrict__ idx, const float *__restrict__ o_comp, const bf16_t *__restrict__ gate,
     bf16_t *__restrict__ out, bf16_t *__restrict__ o_sel, float *__restrict__ lse, int64_t n_tok,
     int64_t n_blk, int heads, int block, int kk, float scale_log2, int64_t set_offset, int64_t n_sets,
-    int map_mode)
+    int map_mode, TokenMap qmap, int64_t n_keys, int64_t lse_stride, const bf16_t *__restrict__ kb2,
+    const bf16_t *__restrict__ vb2, int64_t n_keys2)
 {
     constexpr int NW = QW;             // waves per workgroup
     constexpr int CPW = 16 / NW;       // 1 KiB chunks of a unit (8 K + 8 V) issued by each wave
@@ -104,13 +105,15 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const int64_t qgroup = set;
     const int64_t t = qgroup * (32 * QW) + wave * 32 + (lane & 31);
     const bool row_valid = t < n_tok;
-    const int64_t n_units_total = (n_tok + kUnitKeys - 1) / kUnitKeys;
+    const int64_t trow = qmap.row(row_valid ? t : 0);  // the caller's row of this query
+    const int64_t n_units1 = (n_keys + kUnitKeys - 1) / kUnitKeys;     // units of the first key segment
+    const int64_t n_units2 = (n_keys2 + kUnitKeys - 1) / kUnitKeys;    // dense only: second segment
 
     bf16x8 qb[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         if (row_valid) {
-            qb[s] = *reinterpret_cast<const bf16x8 *>(q + (t * heads + h) * 64 + 16 * s + 8 * g);
+            qb[s] = *reinterpret_cast<const bf16x8 *>(q + (trow * heads + h) * 64 + 16 * s + 8 * g);
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) qb[s][i] = static_cast<bf16_t>(0.f);
@@ -121,7 +124,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     int64_t n_steps;  // units to process
     const int32_t *sel = nullptr;
     if constexpr (DENSE) {
-        n_steps = n_units_total;
+        n_steps = n_units1 + n_units2;
     } else {
         sel = idx + (static_cast<int64_t>(h) * n_blk + qgroup) * kk;
         n_steps = static_cast<int64_t>(kk) * upb;
@@ -129,6 +132,8 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
 
     const bf16_t *kb_h = kb + static_cast<int64_t>(h) * n_blk * block * 64;
     const bf16_t *vb_h = vb + static_cast<int64_t>(h) * n_blk * block * 64;
+    const bf16_t *kb2_h = DENSE ? kb2 + static_cast<int64_t>(h) * n_units2 * kUnitElems : nullptr;
+    const bf16_t *vb2_h = DENSE ? vb2 + static_cast<int64_t>(h) * n_units2 * kUnitElems : nullptr;
     const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0]));
 
     // step s -> key unit (global unit index)
@@ -142,7 +147,11 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
             const int chunk = wave * CPW + c;  // 0..7: K, 8..15: V
-            const bf16_t *src = (chunk < 8 ? kb_h : vb_h) + w * kUnitElems + (chunk & 7) * 512 + lane * 8;
+            const bf16_t *src;
+            if (DENSE && w >= n_units1)
+                src = (chunk < 8 ? kb2_h : vb2_h) + (w - n_units1) * kUnitElems + (chunk & 7) * 512 + lane * 8;
+            else
+                src = (chunk < 8 ? kb_h : vb_h) + w * kUnitElems + (chunk & 7) * 512 + lane * 8;
             lds_dma_16(src, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
         }
     };
@@ -164,7 +173,8 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         if (s + D < n_steps) issue(s + D);
 
         const int64_t w = unit_of(s);
-        const int valid = static_cast<int>((n_tok - w * kUnitKeys < kUnitKeys) ? (n_tok - w * kUnitKeys) : kUnitKeys);
+        const int64_t left = (DENSE && w >= n_units1) ? n_keys2 - (w - n_units1) * kUnitKeys : n_keys - w * kUnitKeys;
+        const int valid = static_cast<int>(left < kUnitKeys ? left : kUnitKeys);
         if (valid <= 0) continue;  // second half of a short last block
 
         const bf16_t *ks = &ring[s % NS][0];
@@ -231,8 +241,8 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     if (!row_valid) return;
     const float l_tot = sum_with_other_half(l_run);
     const float inv = 1.f / l_tot;
-    if (lse != nullptr && g == 0) lse[static_cast<int64_t>(h) * n_tok + t] = (m_run + __builtin_log2f(l_tot)) * kLn2;
-    const int64_t o = (t * heads + h) * 64;
+    if (lse != nullptr && g == 0) lse[static_cast<int64_t>(h) * lse_stride + trow] = (m_run + __builtin_log2f(l_tot)) * kLn2;
+    const int64_t o = (trow * heads + h) * 64;
     const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_blk + t / block) * 64 : nullptr;
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
@@ -275,7 +285,7 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
     // so that no single kernel occupies the GPU for seconds.
     int64_t per_launch = sets;
     if (DENSE) {
-        const double flops_per_set = 4.0 * 64.0 * rows_per_group * static_cast<double>(a.n_tok) * a.heads;
+        const double flops_per_set = 4.0 * 64.0 * rows_per_group * static_cast<double>(a.n_keys + a.n_keys2) * a.heads;
         per_launch = static_cast<int64_t>(2e14 / flops_per_set);
         if (per_launch < 1) per_launch = 1;
     }
@@ -289,7 +299,8 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
                            static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
                            a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
                            static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.block,
-                           a.kk, a.scale * kLog2e, s0, ns, map_mode);
+                           a.kk, a.scale * kLog2e, s0, ns, map_mode, a.qmap, a.n_keys, a.lse_stride,
+                           static_cast<const bf16_t *>(a.kb2), static_cast<const bf16_t *>(a.vb2), a.n_keys2);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -301,10 +312,13 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
     if (!a.is_bf16 || a.kb == nullptr || a.vb == nullptr) return hipErrorInvalidValue;
     // One query block per workgroup, two LDS stages: measured best on MI355X (deeper rings only add
     // queueing once the memory fabric is saturated).
+    if (a.qmap.period != 0 && a.n_tok > 0x7fffffffLL) return hipErrorInvalidValue;
     if (a.idx == nullptr) {
-        if (a.block != 64) return hipErrorInvalidValue;
+        if (a.block != 64 && a.block != 128) return hipErrorInvalidValue;
+        if (a.n_keys2 > 0 && (a.kb2 == nullptr || a.vb2 == nullptr)) return hipErrorInvalidValue;
         return run_select<4, true, 3>(a, stream);
     }
+    if (a.n_keys != a.n_tok || a.n_keys2 != 0) return hipErrorInvalidValue;  // selection: keys = the query sequence
     if (a.block == 64) return run_select<2, false, 2>(a, stream);
     if (a.block == 128) return run_select<4, false, 2>(a, stream);
     return hipErrorInvalidValue;

@@ -64,10 +64,12 @@ struct Layout {
     int kk;      // blocks TopK picks per row (among the non-forced ones)
     int width;   // blocks attended per row: kk + n_forced
     int head_chunk;
-    size_t qc, kc, vc, oc, tile[6], idx, idx_merged, forced_clean, forced_words, s, kb, vb, total;
+    size_t qc, kc, vc, oc, tile[6], idx, idx_merged, forced_clean, forced_words, s, kb, vb, kb_spec, vb_spec, total;
 };
 
-Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, s3r_dtype dtype)
+// n_tok: tokens on the sparse path (the image tokens); n_spec: special tokens (dense rows).
+Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, s3r_dtype dtype,
+                   int64_t n_spec = 0)
 {
     Layout L{};
     L.n_blk = (n_tok + block - 1) / block;
@@ -97,6 +99,9 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, 
     const size_t blocked = mfma_ok(dtype, block) ? static_cast<size_t>(heads) * L.n_blk * block * 64 * 2 : 0;
     L.kb = take(blocked);
     L.vb = take(blocked);
+    const size_t spec_tiles = mfma_ok(dtype, block) ? static_cast<size_t>(heads) * ((n_spec + 63) / 64) * 64 * 64 * 2 : 0;
+    L.kb_spec = take(spec_tiles);
+    L.vb_spec = take(spec_tiles);
     L.total = off;
     return L;
 }
@@ -205,6 +210,35 @@ s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, 
     return S3R_OK;
 }
 
+// Special / image token split of a sequence of `n_tok` rows in views of `period` rows whose first
+// `special` rows are special tokens (0, 0: no special tokens).
+struct Split {
+    int64_t n_img, n_spec;
+    s3r::TokenMap img, spec;
+};
+
+s3r_status make_split(int64_t n_tok, int period, int special, Split *out)
+{
+    Split sp{};
+    sp.n_img = n_tok;
+    sp.n_spec = 0;
+    if (period == 0 && special == 0) { *out = sp; return S3R_OK; }
+    if (period <= 0 || special < 0 || special >= period)
+        return fail(S3R_ERR_INVALID_ARG, "special_per_view (%d) must lie in [0, tokens_per_view = %d)", special, period);
+    if (n_tok % period != 0)
+        return fail(S3R_ERR_INVALID_ARG, "n_tok (%lld) is not a multiple of tokens_per_view (%d)",
+                    static_cast<long long>(n_tok), period);
+    if (n_tok > 0x7fffffffLL) return fail(S3R_ERR_UNSUPPORTED, "n_tok exceeds 2^31 - 1 with special tokens");
+    if (special == 0) { *out = sp; return S3R_OK; }
+    const int64_t views = n_tok / period;
+    sp.n_spec = views * special;
+    sp.n_img = n_tok - sp.n_spec;
+    sp.img.period = period; sp.img.first = special; sp.img.count = period - special;
+    sp.spec.period = period; sp.spec.first = 0; sp.spec.count = special;
+    *out = sp;
+    return S3R_OK;
+}
+
 float resolve_scale(float s, int head_dim) { return s > 0.f ? s : 1.f / std::sqrt(static_cast<float>(head_dim)); }
 
 }  // namespace
@@ -270,6 +304,19 @@ size_t speed3r_workspace_bytes(int64_t n_tok, int heads, int head_dim, int block
     return make_layout(n_tok, heads, block, topk, n_forced, dtype).total;
 }
 
+size_t speed3r_workspace_bytes_ex(const s3r_params *p)
+{
+    if (!p) { fail(S3R_ERR_INVALID_ARG, "params is null"); return 0; }
+    if (check_shape(p->n_tok, p->heads, p->head_dim, p->block, p->topk, p->dtype) != S3R_OK) return 0;
+    Split sp{};
+    if (make_split(p->n_tok, p->tokens_per_view, p->special_per_view, &sp) != S3R_OK) return 0;
+    if (p->n_forced < 0 || p->n_forced > (sp.n_img + p->block - 1) / p->block) {
+        fail(S3R_ERR_INVALID_ARG, "n_forced (%d) must lie in [0, n_blk]", p->n_forced);
+        return 0;
+    }
+    return make_layout(sp.n_img, p->heads, p->block, p->topk, p->n_forced, p->dtype, sp.n_spec).total;
+}
+
 int speed3r_selected_per_row(int64_t n_tok, int block, int topk, int n_forced)
 {
     if (n_tok <= 0 || block <= 0 || topk <= 0 || n_forced < 0) return -1;
@@ -293,9 +340,12 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     const int n_forced = p->forced_blocks ? p->n_forced : 0;
     if (p->n_forced < 0 || (p->n_forced > 0 && !p->forced_blocks) || (p->forced_blocks && p->n_forced == 0))
         return fail(S3R_ERR_INVALID_ARG, "forced_blocks and n_forced (%d) must be given together", p->n_forced);
-    if (n_forced > (p->n_tok + p->block - 1) / p->block)
+    Split sp{};
+    st = make_split(p->n_tok, p->tokens_per_view, p->special_per_view, &sp);
+    if (st != S3R_OK) return st;
+    if (n_forced > (sp.n_img + p->block - 1) / p->block)
         return fail(S3R_ERR_INVALID_ARG, "n_forced (%d) exceeds the number of blocks", n_forced);
-    const Layout L = make_layout(p->n_tok, p->heads, p->block, p->topk, n_forced, p->dtype);
+    const Layout L = make_layout(sp.n_img, p->heads, p->block, p->topk, n_forced, p->dtype, sp.n_spec);
     if (!p->workspace) return fail(S3R_ERR_WORKSPACE, "workspace is null (%zu bytes needed)", L.total);
     if ((reinterpret_cast<uintptr_t>(p->workspace) & (kAlign - 1)) != 0)
         return fail(S3R_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
@@ -325,7 +375,8 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
 
     {
         StageTimer tm(S3R_STAGE_POOL, stream);
-        S3R_HIP(s3r::launch_pool(p->q, p->k, p->v, qc, kc, vc, kb, vb, p->n_tok, p->heads, p->block, is_bf16, stream),
+        S3R_HIP(s3r::launch_pool(p->q, p->k, p->v, qc, kc, vc, kb, vb, sp.n_img, p->heads, p->block, is_bf16,
+                                 sp.img, stream),
                 "pool kernel launch");
     }
     if (n_forced > 0) {
@@ -346,12 +397,38 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     s3r::SelectArgs a{};
     a.q = p->q; a.k = p->k; a.v = p->v; a.kb = kb; a.vb = vb; a.idx = idx_sel; a.o_comp = oc;
     a.gate = p->gate_logits; a.out = p->out; a.o_sel = p->o_sel; a.lse = p->lse_sel;
-    a.n_tok = p->n_tok; a.n_blk = L.n_blk; a.heads = p->heads; a.block = p->block; a.kk = L.width;
+    a.n_tok = sp.n_img; a.n_keys = sp.n_img; a.n_blk = L.n_blk; a.lse_stride = p->n_tok;
+    a.qmap = sp.img; a.kmap = sp.img;
+    a.heads = p->heads; a.block = p->block; a.kk = L.width;
     a.scale = scale; a.is_bf16 = is_bf16;
     {
         StageTimer tm(S3R_STAGE_SELECT, stream);
         S3R_HIP(mfma ? s3r::launch_select_mfma(a, stream) : s3r::launch_select_generic(a, stream),
                 "select kernel launch");
+    }
+    if (sp.n_spec > 0) {
+        // Special tokens (Sec. 3.2 eq. 2): plain attention of those rows over every token.
+        s3r::SelectArgs d{};
+        d.q = p->q; d.k = p->k; d.v = p->v; d.idx = nullptr; d.o_comp = nullptr; d.gate = nullptr;
+        d.out = p->out; d.o_sel = nullptr; d.lse = nullptr;
+        d.n_tok = sp.n_spec; d.qmap = sp.spec; d.lse_stride = p->n_tok;
+        d.heads = p->heads; d.block = p->block; d.kk = 0; d.scale = scale; d.is_bf16 = is_bf16;
+        if (mfma) {
+            void *kb_s = at(ws, L.kb_spec), *vb_s = at(ws, L.vb_spec);
+            {
+                StageTimer tm(S3R_STAGE_POOL, stream);
+                S3R_HIP(s3r::launch_pool(p->q, p->k, p->v, nullptr, nullptr, nullptr, kb_s, vb_s, sp.n_spec, p->heads,
+                                         64, true, sp.spec, stream),
+                        "pool kernel launch (special tokens)");
+            }
+            d.kb = kb; d.vb = vb; d.n_keys = sp.n_img; d.n_blk = L.n_blk;      // image keys, then special keys
+            d.kb2 = kb_s; d.vb2 = vb_s; d.n_keys2 = sp.n_spec;
+        } else {
+            d.n_keys = p->n_tok; d.n_blk = (p->n_tok + p->block - 1) / p->block;  // every row, in place
+        }
+        StageTimer tm(S3R_STAGE_DENSE, stream);
+        S3R_HIP(mfma ? s3r::launch_select_mfma(d, stream) : s3r::launch_select_generic(d, stream),
+                "dense kernel launch (special tokens)");
     }
     return S3R_OK;
 }
@@ -380,7 +457,7 @@ s3r_status speed3r_pool_blocks(const void *q, const void *k, const void *v, floa
     if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     StageTimer tm(S3R_STAGE_POOL, static_cast<hipStream_t>(stream));
     S3R_HIP(s3r::launch_pool(q, k, v, qc, kc, vc, nullptr, nullptr, n_tok, heads, block, dtype == S3R_BF16,
-                             static_cast<hipStream_t>(stream)),
+                             s3r::TokenMap{}, static_cast<hipStream_t>(stream)),
             "pool kernel launch");
     return S3R_OK;
 }
@@ -445,11 +522,12 @@ s3r_status speed3r_select_attn(const void *q, const void *k, const void *v, cons
         a.vb = at(ws, blocked);
         StageTimer tm(S3R_STAGE_POOL, s);
         S3R_HIP(s3r::launch_pool(q, k, v, nullptr, nullptr, nullptr, const_cast<void *>(a.kb),
-                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s),
+                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s3r::TokenMap{}, s),
                 "pool kernel launch");
     }
     a.q = q; a.k = k; a.v = v; a.idx = idx; a.o_comp = o_comp; a.gate = gate_logits; a.out = out;
-    a.o_sel = o_sel; a.lse = lse; a.n_tok = n_tok; a.n_blk = n_blk; a.heads = heads; a.block = block;
+    a.o_sel = o_sel; a.lse = lse; a.n_tok = n_tok; a.n_keys = n_tok; a.lse_stride = n_tok; a.n_blk = n_blk;
+    a.heads = heads; a.block = block;
     a.kk = kk; a.scale = resolve_scale(softmax_scale, head_dim); a.is_bf16 = dtype == S3R_BF16;
     StageTimer tm(S3R_STAGE_SELECT, s);
     S3R_HIP(mfma ? s3r::launch_select_mfma(a, s) : s3r::launch_select_generic(a, s), "select kernel launch");
@@ -478,11 +556,12 @@ s3r_status speed3r_dense_attn(const void *q, const void *k, const void *v, void 
         a.vb = at(ws, blocked);
         StageTimer tm(S3R_STAGE_POOL, s);
         S3R_HIP(s3r::launch_pool(q, k, v, nullptr, nullptr, nullptr, const_cast<void *>(a.kb),
-                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s),
+                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s3r::TokenMap{}, s),
                 "pool kernel launch");
     }
     a.q = q; a.k = k; a.v = v; a.idx = nullptr; a.o_comp = nullptr; a.gate = nullptr; a.out = out;
-    a.o_sel = nullptr; a.lse = lse; a.n_tok = n_tok; a.n_blk = n_blk; a.heads = heads; a.block = block;
+    a.o_sel = nullptr; a.lse = lse; a.n_tok = n_tok; a.n_keys = n_tok; a.lse_stride = n_tok; a.n_blk = n_blk;
+    a.heads = heads; a.block = block;
     a.kk = 0; a.scale = resolve_scale(softmax_scale, head_dim); a.is_bf16 = dtype == S3R_BF16;
     StageTimer tm(S3R_STAGE_DENSE, s);
     S3R_HIP(mfma ? s3r::launch_select_mfma(a, s) : s3r::launch_select_generic(a, s), "dense kernel launch");

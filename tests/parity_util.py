@@ -90,13 +90,15 @@ def to_host_f32(t: torch.Tensor) -> np.ndarray:
 
 
 def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "lse", "o_comp", "o_sel"),
-               forced=None):
+               forced=None, tokens_per_view=0, special_per_view=0):
     """One call of the whole path through the C ABI; returns device tensors.  `forced`: ascending
-    block indices (host array) every query block attends besides its TopK."""
+    block indices (host array) every query block attends besides its TopK.  With special tokens
+    the block-level outputs are sized for the image-only sequence."""
     n_tok, heads, d = q.shape
-    n_blk = (n_tok + block - 1) // block
+    n_img = n_tok - (n_tok // tokens_per_view) * special_per_view if special_per_view else n_tok
+    n_blk = (n_img + block - 1) // block
     n_forced = 0 if forced is None else len(forced)
-    kk = s3r.speed3r_selected_per_row(n_tok, block, topk, n_forced)
+    kk = s3r.speed3r_selected_per_row(n_img, block, topk, n_forced)
     dev = q.device
     out = torch.full_like(q, float("nan"))
     bufs = {}
@@ -110,7 +112,8 @@ def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "ls
         bufs["o_sel"] = torch.full_like(q, float("nan"))
     forced_t = None if n_forced == 0 else torch.from_numpy(np.asarray(forced, dtype=np.int32)).to(dev)
     s3r.speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, gate_logits=gate,
-                                      softmax_scale=scale, forced_blocks=forced_t, **bufs)
+                                      softmax_scale=scale, forced_blocks=forced_t,
+                                      tokens_per_view=tokens_per_view, special_per_view=special_per_view, **bufs)
     torch.cuda.synchronize()
     res = {"out": out}
     res.update({"idx": bufs.get("topk_idx"), "lse": bufs.get("lse_sel"),
@@ -182,4 +185,29 @@ def compare_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, dtype,
         assert err <= tol, f"{label} lse abs err {err:.3e} > {tol:.1e}"
         stats["lse_abs"] = err
     stats["out"] = assert_close(tok_sel(dev_res["out"]), out_v, tol, f"{label} out")
+    return stats
+
+
+def compare_layer_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, dtype, tokens_per_view,
+                              special_per_view, rows=None, spec_sample=None, forced=None, label=""):
+    """Layer with special tokens: the image rows go through compare_with_oracle on the image-only
+    sequence (device outputs gathered from their original rows), the special rows (all, or the
+    sample `spec_sample` of them) against the oracle's dense attention over every row."""
+    n_tok = qf.shape[0]
+    spec_rows, img_rows = oracle.token_partition(n_tok, tokens_per_view, special_per_view)
+    img_t = torch.from_numpy(img_rows).to(dev_res["out"].device)
+    sub = dict(dev_res)
+    sub["out"] = dev_res["out"].index_select(0, img_t)
+    if dev_res.get("o_sel") is not None:
+        sub["o_sel"] = dev_res["o_sel"].index_select(0, img_t)
+    if dev_res.get("lse") is not None:
+        sub["lse"] = dev_res["lse"].index_select(1, img_t).contiguous()
+    stats = compare_with_oracle(oracle, sub, qf[img_rows], kf[img_rows], vf[img_rows],
+                                None if gate_f is None else gate_f[img_rows], block, topk, dtype, rows=rows,
+                                label=label, forced=forced)
+    pick = spec_rows if spec_sample is None else spec_rows[np.asarray(spec_sample, dtype=np.int64)]
+    if pick.size:
+        ref = oracle.dense_attn(qf, kf, vf, 1.0 / math.sqrt(qf.shape[2]), q_tok=pick)
+        got = to_host_f32(dev_res["out"].index_select(0, torch.from_numpy(pick).to(dev_res["out"].device)))
+        stats["o_spec"] = assert_close(got, ref, TOL[dtype], f"{label} special rows")
     return stats

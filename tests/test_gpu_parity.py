@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2603_08055_amd import workloads
-from tests.parity_util import (TOL, assert_close, check_topk_sets, compare_with_oracle, log,
+from tests.parity_util import (TOL, assert_close, check_topk_sets, compare_layer_with_oracle, compare_with_oracle, log,
                                rel_errors, run_device, to_host_f32)
 
 pytestmark = pytest.mark.gpu
@@ -306,6 +306,93 @@ def test_forced_blocks_leave_compressed_branch_unchanged(s3r):
     forced = run_device(s3r, q, k, v, wl.block, wl.topk, forced=workloads.vggt_forced_blocks(wl))
     assert torch.equal(plain["o_comp"], forced["o_comp"])
     assert forced["idx"].shape[2] == plain["idx"].shape[2] + len(workloads.vggt_forced_blocks(wl))
+
+
+# ------------------------------------- special tokens: dense rows + concat (Sec. 3.2 eqs. 1-2) --
+
+def layer_case(s3r, oracle, wl, special, rows=None, spec_sample=None, with_gate=False, forced=None,
+               device_gen="cpu", label=None):
+    label = label or f"{wl.name}+{special} special"
+    log(f"{label}: drawing inputs n_tok={wl.n_tok} views={wl.views} block={wl.block} topk={wl.topk}")
+    q, k, v = workloads.make_inputs(wl, device=device_gen)
+    gate = workloads.make_gate_logits(wl, device=device_gen) if with_gate else None
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    gd = None if gate is None else gate.cuda()
+    res = run_device(s3r, qd, kd, vd, wl.block, wl.topk, gate=gd, forced=forced,
+                     tokens_per_view=wl.tokens_per_view, special_per_view=special)
+    log(f"{label}: oracle")
+    stats = compare_layer_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v),
+                                      None if gate is None else to_host_f32(gate), wl.block, wl.topk, wl.dtype,
+                                      wl.tokens_per_view, special, rows=rows, spec_sample=spec_sample,
+                                      forced=forced, label=label)
+    log(f"{label}: {stats}")
+    return res, stats
+
+
+def test_special_tokens_vggt_8_views(s3r, oracle):
+    """5 special tokens lead each of 8 views of 1374: their rows get dense attention over all rows,
+    the 1369 x 8 image rows the sparse path."""
+    layer_case(s3r, oracle, workloads.config(2), 5, with_gate=True)
+
+
+@pytest.mark.parametrize("dtype,block,views,tpv,special,topk", [
+    ("f32", 16, 3, 111, 2, 3),           # generic kernels, blocks straddle views, ragged tail
+    ("f32", 64, 2, 300, 7, 2),
+    ("bf16", 64, 4, 333, 5, 4),          # image sequence 1312 = 20.5 blocks; 20 special rows (< one unit)
+    ("bf16", 64, 1, 1000, 100, 3),       # the paper's [spec; img] arrangement, 100 special rows (two units)
+    ("bf16", 128, 3, 700, 5, 2),         # block 128: dense rows walk half-block units, odd unit count
+    ("bf16", 64, 70, 65, 1, 2),          # one special token per view; image blocks = views
+    ("bf16", 64, 2, 200, 136, 1),        # more special than image rows
+])
+def test_special_tokens_edge_cases(s3r, oracle, dtype, block, views, tpv, special, topk):
+    wl = workloads.Workload(f"special_{dtype}_{block}_{views}x{tpv}_{special}", views, tpv, 2, 64, dtype, block,
+                            topk, 92, "normal")
+    layer_case(s3r, oracle, wl, special, with_gate=True)
+
+
+def test_special_tokens_with_forced_reference_view(s3r, oracle):
+    wl = workloads.config(2, views=6)
+    img = workloads.Workload("img_only", wl.views, wl.tokens_per_view - 5, wl.heads, 64, wl.dtype, wl.block,
+                             wl.topk, wl.seed, wl.kind)
+    forced = workloads.vggt_forced_blocks(img)          # blocks of the image-only sequence
+    layer_case(s3r, oracle, wl, 5, forced=forced, label="config2/6views+special+reference view")
+
+
+def test_special_tokens_sampled_100_views(s3r, oracle):
+    wl = workloads.config(3)
+    n_blk_img = (wl.views * (wl.tokens_per_view - 5) + wl.block - 1) // wl.block
+    rng = np.random.default_rng(16)
+    rows = np.unique(np.concatenate([[0, n_blk_img - 1], rng.choice(n_blk_img, 14, replace=False)]))
+    spec = np.unique(np.concatenate([[0, 4, 5, 499], rng.choice(500, 12, replace=False)]))
+    layer_case(s3r, oracle, wl, 5, rows=rows, spec_sample=spec, device_gen="cuda")
+
+
+@pytest.mark.timeout(600)
+def test_special_tokens_config4_full_size_sampled(s3r, oracle):
+    """The 1000-view workload read as the VGGT layout (5 special tokens lead every view): sampled
+    image query blocks and sampled special rows (each attends all 1,374,000 keys) against the oracle."""
+    wl = workloads.config(4)
+    n_blk_img = (wl.views * (wl.tokens_per_view - 5) + wl.block - 1) // wl.block
+    rng = np.random.default_rng(17)
+    rows = np.unique(np.concatenate([[0, n_blk_img - 1], rng.choice(n_blk_img, 10, replace=False)]))
+    spec = np.unique(np.concatenate([[0, 4999], rng.choice(5000, 6, replace=False)]))
+    layer_case(s3r, oracle, wl, 5, rows=rows, spec_sample=spec, device_gen="cuda")
+
+
+def test_special_tokens_untouched_outputs_and_zero_special(s3r):
+    """special_per_view = 0 with a period is the plain path bit for bit; with special tokens the
+    optional per-token outputs of the special rows are left as they were."""
+    wl = workloads.config(2, views=3)
+    q, k, v = (t.cuda() for t in workloads.make_inputs(wl))
+    plain = run_device(s3r, q, k, v, wl.block, wl.topk)
+    same = run_device(s3r, q, k, v, wl.block, wl.topk, tokens_per_view=wl.tokens_per_view, special_per_view=0)
+    for key in ("out", "idx", "lse", "o_comp", "o_sel"):
+        assert torch.equal(plain[key], same[key]), key
+    res = run_device(s3r, q, k, v, wl.block, wl.topk, tokens_per_view=wl.tokens_per_view, special_per_view=5)
+    spec = torch.arange(wl.n_tok, device="cuda") % wl.tokens_per_view < 5
+    assert torch.isnan(res["o_sel"][spec].float()).all() and torch.isnan(res["lse"][:, spec]).all()
+    assert torch.isfinite(res["out"].float()).all()
+    assert torch.isfinite(res["o_sel"][~spec].float()).all() and torch.isfinite(res["lse"][:, ~spec]).all()
 
 
 @pytest.mark.parametrize("n_tok,block,topk,dtype", [(1, 64, 4, "bf16"), (63, 64, 1, "bf16"), (65, 64, 2, "bf16"),
