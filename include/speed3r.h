@@ -60,7 +60,7 @@ enum {
     S3R_STAGE_POOL = 0,     /* block pooling (+ K/V tile re-layout for the MFMA path) */
     S3R_STAGE_SPLIT = 1,    /* pooled fp32 -> bf16 hi/lo operand tiles                */
     S3R_STAGE_COMPRESS = 2, /* S_guide + compressed attention                         */
-    S3R_STAGE_TOPK = 3,     /* per-query-block TopK                                   */
+    S3R_STAGE_TOPK = 3,     /* per-query-block TopK (incl. its filter sweep)          */
     S3R_STAGE_SELECT = 4,   /* block-sparse attention + merge                         */
     S3R_STAGE_DENSE = 5,    /* dense attention                                        */
     S3R_N_STAGES = 6
@@ -177,8 +177,10 @@ s3r_status speed3r_set_profiling(int enable);
  * switched on); the record is cleared.  Waits for the recorded events, so call it after the work. */
 s3r_status speed3r_get_stage_ms(float *ms, int *launches);
 
-/* Selects the selection/dense kernel family: 0 = automatic (MFMA kernels for bf16 with block 64
- * or 128, the generic kernel otherwise), 1 = always the generic kernel.  Process-wide. */
+/* Selects kernel families, process-wide.  0 = automatic: MFMA attention kernels for bf16 with block
+ * 64 or 128 (the generic kernel otherwise), and for up to 64 TopK blocks per row the TopK that runs
+ * inside the compression sweep without writing S_guide to memory (supplementary Sec. 1).  1 = always
+ * the generic attention kernel.  2 = like 0 but TopK always from S_guide written to memory. */
 s3r_status speed3r_set_kernel_choice(int choice);
 
 /* Frees the library-held scratch (synchronises the device). */

@@ -18,6 +18,19 @@
 // stores are fire-and-forget) and one more wave does nothing but move key/value operand tiles
 // HBM -> LDS with LDS-direct loads, a ring of NS stages ahead, pacing itself with exact vmcnt
 // counts (its counter only ever holds loads, which return in order).  One barrier per step.
+//
+// TopK without S_guide in memory (supplementary Sec. 1: selection fused with the compression
+// sweep; here as a threshold filter that suits 64-wide waves better than a per-tile sort).
+//   THRESHOLD mode: same sweep, no score stores.  Each lane keeps the running maximum of each of its
+//     32 score registers, even and odd steps apart: 128 buckets per query (two lanes), every pooled
+//     key falling in exactly one.  The maxima are kept as packed fp16 rounded down (32 registers):
+//     a value below a bucket's true maximum is still a valid bound.  The k-th largest of the 128 bucket maxima is a lower bound of the
+//     query's k-th largest score (k <= 64: that many distinct keys reach it); it is written out per
+//     query.
+//   FILTER mode: the scores are recomputed (same MFMA sequence, so the same bits) and the index of
+//     every score at or above the query's bound is appended to that lane's private candidate list
+//     (a few hundred per query instead of N_b).  No softmax, no Vc, no atomics, deterministic.
+// The exact TopK among the candidates is a small kernel of its own (topk.hip).
 #include "s3r_device.h"
 #include "s3r_kernels.h"
 
@@ -50,16 +63,37 @@ __device__ __forceinline__ float compress_sum_halves(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// grid: (ceil(tiles / CW), heads); CW compute waves (32 pooled queries each) + 1 loader wave.
-template <bool SPLIT_PV, int NS, int CW>
-__global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+// Two floats to packed fp16, rounded toward zero (out-of-range values clamp to the largest finite).
+__device__ __forceinline__ half2_t pack_rtz(float a, float b)
+{
+    return __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(a, b));
+}
+
+enum CompressMode { kStoreScores = 0, kThreshold = 1, kFilter = 2 };
+
+// What the TopK-in-the-sweep modes read and write besides the operands.
+struct FusedTopkArgs {
+    float *thr;            // [heads][n_blk]: lower bound of each query's k-th largest score
+    int32_t *cand;         // [heads][n_blk][2][cap] candidate key indices, one list per lane of a query
+    int *cand_count;       // [heads][n_blk][2] entries asked for (may exceed cap: the list is then cut)
+    int *overflow;         // set to 1 when any list was cut (the caller then redoes TopK the plain way)
+    const int *run_flag;   // kStoreScores only: when given and 0, the launch does nothing
+    int cap;
+    int k;                 // 1..64
+};
+
+// One workgroup's share: query tiles bx * CW .. + CW - 1 of head by.
+template <bool SPLIT_PV, int NS, int CW, int MODE>
+__device__ __forceinline__ void compress_block(
     const bf16_t *__restrict__ qs_hi, const bf16_t *__restrict__ qs_lo,
     const bf16_t *__restrict__ ks_hi, const bf16_t *__restrict__ ks_lo,
     const bf16_t *__restrict__ vt_hi, const bf16_t *__restrict__ vt_lo, float *__restrict__ s_guide,
     int64_t ld_s, float *__restrict__ o_comp, int64_t n_blk, int64_t tiles_padded, float scale_log2,
-    const unsigned long long *__restrict__ forced_words)
+    const unsigned long long *__restrict__ forced_words, const FusedTopkArgs &ft, unsigned bx, unsigned by)
 {
-    constexpr int NARR = SPLIT_PV ? 4 : 3;          // ks_hi, ks_lo, vt_hi [, vt_lo]
+    constexpr int NARR = (MODE == kFilter) ? 2 : (SPLIT_PV ? 4 : 3);  // ks_hi, ks_lo [, vt_hi [, vt_lo]]
     constexpr int STAGE_ELEMS = 2 * kRowTileElems;   // 64 keys x 64 channels per array: 8 KiB
     constexpr int CPS = NARR * 8;                    // 1 KiB chunks per step, all issued by the loader wave
     constexpr int D = NS - 1;                        // steps in flight
@@ -68,8 +102,11 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int h = blockIdx.y;
+    const int h = by;
     const int64_t n_kt = (n_blk + 63) / 64;
+    if constexpr (MODE == kThreshold) {
+        if (bx == 0 && by == 0 && tid == 0) *ft.overflow = 0;  // the filter launch comes later in the stream
+    }
     const int64_t head_tiles = static_cast<int64_t>(h) * tiles_padded;
 
     if (wave == CW) {
@@ -77,8 +114,8 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
         const bf16_t *src[NARR];
         src[0] = ks_hi + head_tiles * kRowTileElems;
         src[1] = ks_lo + head_tiles * kRowTileElems;
-        src[2] = vt_hi + head_tiles * kRowTileElems;
-        if constexpr (SPLIT_PV) src[3] = vt_lo + head_tiles * kRowTileElems;
+        if constexpr (NARR >= 3) src[2] = vt_hi + head_tiles * kRowTileElems;
+        if constexpr (NARR == 4) src[3] = vt_lo + head_tiles * kRowTileElems;
         const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
         auto issue = [&](int64_t kt) {
             const unsigned stage_byte = ring_base + static_cast<unsigned>(kt % NS) * (NARR * STAGE_ELEMS * 2);
@@ -101,7 +138,7 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
     }
 
     // ---- compute waves ---------------------------------------------------------------------------
-    const int64_t qtile = static_cast<int64_t>(blockIdx.x) * CW + wave;
+    const int64_t qtile = static_cast<int64_t>(bx) * CW + wave;
     const int64_t qrow = qtile * 32 + (lane & 31);
     const bool wave_active = qtile * 32 < n_blk;
 
@@ -121,14 +158,29 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
         for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
     float m_run = -1e30f, l_run = 0.f;
     float *srow = s_guide + (static_cast<int64_t>(h) * n_blk + (qrow < n_blk ? qrow : 0)) * ld_s;
+    const int64_t row_id = static_cast<int64_t>(h) * n_blk + (qrow < n_blk ? qrow : 0);
+
+    half2_t bmax[2][16];         // kThreshold: running maxima of the score registers (pairs, fp16 rounded
+                                 // toward zero), even and odd steps apart
+    float thr_f = 0.f;           // kFilter: this query's bound (NaN for rows that do not exist: nothing passes)
+    int32_t *cand_row = nullptr; // kFilter: this lane's candidate list
+    int n_cand = 0;
+    if constexpr (MODE == kThreshold) {
+#pragma unroll
+        for (int par = 0; par < 2; ++par)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) bmax[par][i] = half2_t{-INFINITY, -INFINITY};
+    }
+    if constexpr (MODE == kFilter) {
+        thr_f = (qrow < n_blk) ? ft.thr[row_id] : __builtin_nanf("");
+        cand_row = ft.cand + (row_id * 2 + g) * ft.cap;
+    }
 
     for (int64_t kt = 0; kt < n_kt; ++kt) {
         lds_barrier();
         if (!wave_active) continue;
         const bf16_t *k_hi = &ring[kt % NS][0][0];
         const bf16_t *k_lo = &ring[kt % NS][1][0];
-        const bf16_t *v_hi = &ring[kt % NS][2][0];
-        const bf16_t *v_lo = &ring[kt % NS][NARR - 1][0];
 
         floatx16 sacc[2];
 #pragma unroll
@@ -145,27 +197,55 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
                 sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[s], sacc[mt], 0, 0, 0);
             }
         }
-        // eq. 4: raw scores out, 4 consecutive keys of one query row per store; never waited for
         const unsigned long long fw = (forced_words != nullptr) ? forced_words[kt] : 0ull;  // wave-uniform
-        if (qrow < n_blk) {
+        if constexpr (MODE == kStoreScores) {
+            // eq. 4: raw scores out, 4 consecutive keys of one query row per store; never waited for
+            if (qrow < n_blk) {
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const int64_t key0 = kt * 64 + mt * 32 + 8 * r4 + 4 * g;
+                        if (key0 < ld_s) {
+                            floatx4 o;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) o[i] = sacc[mt][4 * r4 + i];
+                            if (fw != 0ull) {  // forced blocks leave the TopK competition (Sec. 3.3)
+                                const unsigned nib = static_cast<unsigned>(fw >> (mt * 32 + 8 * r4 + 4 * g)) & 0xFu;
+#pragma unroll
+                                for (int i = 0; i < 4; ++i)
+                                    if (nib & (1u << i)) o[i] = -INFINITY;
+                            }
+                            *reinterpret_cast<floatx4 *>(srow + key0) = o;
+                        }
+                    }
+            }
+        }
+        if constexpr (MODE == kFilter) {
+            // keys that do not exist or are forced never become candidates: NaN fails every compare
+            if (kt * 64 + 64 > n_blk || fw != 0ull) {
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int b = mt * 32 + acc_row(lane, r);
+                        if (kt * 64 + b >= n_blk || ((fw >> b) & 1ull)) sacc[mt][r] = __builtin_nanf("");
+                    }
+            }
+            unsigned pass = 0u;  // register (mt, r) -> bit 31 - (16 mt + r): ascending key = descending bit
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int64_t key0 = kt * 64 + mt * 32 + 8 * r4 + 4 * g;
-                    if (key0 < ld_s) {
-                        floatx4 o;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) o[i] = sacc[mt][4 * r4 + i];
-                        if (fw != 0ull) {  // forced blocks leave the TopK competition (Sec. 3.3)
-                            const unsigned nib = static_cast<unsigned>(fw >> (mt * 32 + 8 * r4 + 4 * g)) & 0xFu;
-#pragma unroll
-                            for (int i = 0; i < 4; ++i)
-                                if (nib & (1u << i)) o[i] = -INFINITY;
-                        }
-                        *reinterpret_cast<floatx4 *>(srow + key0) = o;
-                    }
-                }
+                for (int r = 0; r < 16; ++r) pass = (pass << 1) | (sacc[mt][r] >= thr_f ? 1u : 0u);
+            while (pass != 0u) {
+                const int b = __clz(pass);
+                pass &= ~(0x80000000u >> b);
+                const int key = static_cast<int>(kt) * 64 + 32 * (b >> 4) + acc_row(lane, b & 15);
+                if (n_cand < ft.cap) cand_row[n_cand] = key;
+                ++n_cand;
+            }
+            continue;
         }
         if (kt * 64 + 64 > n_blk) {           // pooled keys past the end of the sequence do not exist
             asm volatile("" ::: "memory");    // keep this rare path a real branch
@@ -175,6 +255,31 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
                 for (int r = 0; r < 16; ++r)
                     if (kt * 64 + mt * 32 + acc_row(lane, r) >= n_blk) sacc[mt][r] = -INFINITY;
         }
+        if constexpr (MODE == kThreshold) {
+            auto raise = [&](half2_t (&bm)[16]) {
+                if (fw == 0ull) {
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int r2 = 0; r2 < 8; ++r2)
+                            bm[mt * 8 + r2] = __builtin_elementwise_max(
+                                bm[mt * 8 + r2], pack_rtz(sacc[mt][2 * r2], sacc[mt][2 * r2 + 1]));
+                } else {  // forced blocks do not compete (Sec. 3.3)
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int r2 = 0; r2 < 8; ++r2) {
+                            const unsigned two = static_cast<unsigned>(fw >> (mt * 32 + acc_row(lane, 2 * r2))) & 3u;
+                            bm[mt * 8 + r2] = __builtin_elementwise_max(
+                                bm[mt * 8 + r2], pack_rtz((two & 1u) ? -INFINITY : sacc[mt][2 * r2],
+                                                          (two & 2u) ? -INFINITY : sacc[mt][2 * r2 + 1]));
+                        }
+                }
+            };
+            if (kt & 1) raise(bmax[1]); else raise(bmax[0]);  // wave-uniform
+        }
+        const bf16_t *v_hi = &ring[kt % NS][NARR >= 3 ? 2 : 0][0];
+        const bf16_t *v_lo = &ring[kt % NS][NARR - 1][0];
         // online softmax (eq. 3), base-2 exponent with the scale folded in
         float mx = sacc[0][0];
 #pragma unroll
@@ -227,6 +332,48 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
         }
     }
 
+    if constexpr (MODE == kFilter) {
+        if (wave_active && qrow < n_blk) {
+            ft.cand_count[row_id * 2 + g] = n_cand;
+            if (n_cand > ft.cap) atomicOr(ft.overflow, 1);
+        }
+        return;
+    }
+    if constexpr (MODE == kThreshold) {
+        if (wave_active) {
+            // k-th largest of the query's 128 bucket maxima (64 here, 64 in the lane 32 positions away),
+            // by a bitwise search over order-preserving keys.  Buckets that saw no key hold -inf; with
+            // fewer than k real maxima the bound is -inf and every key becomes a candidate.
+            // The stored maxima were rounded toward zero: step the negative ones one fp16 down so that
+            // every bucket value is at most the bucket's true maximum.
+            float bm[64];
+#pragma unroll
+            for (int par = 0; par < 2; ++par)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        unsigned short bits = __builtin_bit_cast(unsigned short, static_cast<_Float16>(bmax[par][i][e]));
+                        if ((bits & 0x8000u) && bits != 0xfc00u) bits += 1;  // -65504 steps to -inf
+                        bm[par * 32 + i * 2 + e] = static_cast<float>(__builtin_bit_cast(_Float16, bits));
+                    }
+            uint32_t T = 0u;
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t trial = T | (1u << bit);
+                const float trial_f = key_to_float(trial);  // x >= trial_f  <=>  order_key(x) >= trial
+                int c = 0;
+                if (trial_f == trial_f) {  // keys above +inf's are NaN patterns: nothing reaches them
+#pragma unroll
+                    for (int i = 0; i < 64; ++i) c += bm[i] >= trial_f ? 1 : 0;
+                }
+                const auto sw = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(c), static_cast<unsigned>(c), false, false);
+                if (static_cast<int>(sw[0] + sw[1]) >= ft.k) T = trial;
+            }
+            // trial keys below the key of -inf are NaN patterns and never taken: T stays under it exactly
+            // when fewer than k buckets hold a real maximum
+            if (qrow < n_blk && g == 0) ft.thr[row_id] = T < 0x007fffffu ? -INFINITY : key_to_float(T);
+        }
+    }
     if (wave_active && qrow < n_blk) {
         const float inv = 1.f / compress_sum_halves(l_run);
         float *orow = o_comp + (static_cast<int64_t>(h) * n_blk + qrow) * 64;
@@ -242,34 +389,91 @@ __global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
     }
 }
 
-template <bool SPLIT_PV, int NS, int CW>
+// grid: (ceil(tiles / CW), heads); CW compute waves (32 pooled queries each) + 1 loader wave.  With a
+// run flag (kStoreScores only): a small 1-D grid that does nothing when the device word is 0 and
+// walks over the (gx, gy) shares otherwise.
+template <bool SPLIT_PV, int NS, int CW, int MODE>
+__global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
+    const bf16_t *__restrict__ qs_hi, const bf16_t *__restrict__ qs_lo,
+    const bf16_t *__restrict__ ks_hi, const bf16_t *__restrict__ ks_lo,
+    const bf16_t *__restrict__ vt_hi, const bf16_t *__restrict__ vt_lo, float *__restrict__ s_guide,
+    int64_t ld_s, float *__restrict__ o_comp, int64_t n_blk, int64_t tiles_padded, float scale_log2,
+    const unsigned long long *__restrict__ forced_words, FusedTopkArgs ft, unsigned gx, unsigned gy)
+{
+    if (MODE != kStoreScores || ft.run_flag == nullptr) {
+        compress_block<SPLIT_PV, NS, CW, MODE>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk,
+                                               tiles_padded, scale_log2, forced_words, ft, blockIdx.x, blockIdx.y);
+        return;
+    }
+    if (*ft.run_flag == 0) return;  // uniform over the grid
+    for (unsigned v = blockIdx.x; v < gx * gy; v += gridDim.x) {
+        compress_block<SPLIT_PV, NS, CW, MODE>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk,
+                                               tiles_padded, scale_log2, forced_words, ft, v % gx, v / gx);
+        __syncthreads();
+    }
+}
+
+template <bool SPLIT_PV, int NS, int CW, int MODE>
 static hipError_t run_compress(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
                                const void *vt_hi, const void *vt_lo, float *s_guide, int64_t ld_s,
                                float *o_comp, int64_t n_blk, int heads, float scale_log2,
-                               const unsigned long long *forced_words, hipStream_t stream)
+                               const unsigned long long *forced_words, const FusedTopkArgs &ft,
+                               hipStream_t stream)
 {
     const int64_t tiles = pooled_tiles_padded(n_blk);
     const int64_t q_tiles = (n_blk + 31) / 32;
-    const dim3 grid(static_cast<unsigned>((q_tiles + CW - 1) / CW), heads);
-    hipLaunchKernelGGL((compress_kernel<SPLIT_PV, NS, CW>), grid, dim3((CW + 1) * 64), 0, stream,
+    const unsigned gx = static_cast<unsigned>((q_tiles + CW - 1) / CW), gy = static_cast<unsigned>(heads);
+    dim3 grid(gx, gy);
+    if (MODE == kStoreScores && ft.run_flag != nullptr) {
+        const unsigned long long total = static_cast<unsigned long long>(gx) * gy;
+        if (total > 0xffffffffull) return hipErrorInvalidValue;
+        grid = dim3(total > kFlaggedGrid ? kFlaggedGrid : static_cast<unsigned>(total), 1);
+    }
+    hipLaunchKernelGGL((compress_kernel<SPLIT_PV, NS, CW, MODE>), grid, dim3((CW + 1) * 64), 0, stream,
                        static_cast<const bf16_t *>(qs_hi), static_cast<const bf16_t *>(qs_lo),
                        static_cast<const bf16_t *>(ks_hi), static_cast<const bf16_t *>(ks_lo),
                        static_cast<const bf16_t *>(vt_hi), static_cast<const bf16_t *>(vt_lo), s_guide, ld_s,
-                       o_comp, n_blk, tiles, scale_log2, forced_words);
+                       o_comp, n_blk, tiles, scale_log2, forced_words, ft, gx, gy);
     return hipGetLastError();
 }
 
 hipError_t launch_compress(const void *qs_hi, const void *qs_lo, const void *ks_hi,
                            const void *ks_lo, const void *vt_hi, const void *vt_lo, float *s_guide,
                            int64_t ld_s, float *o_comp, int64_t n_blk, int heads, float scale,
-                           const unsigned long long *forced_words, hipStream_t stream)
+                           const unsigned long long *forced_words, const int *run_flag, hipStream_t stream)
 {
     const float sl = scale * kLog2e;
+    FusedTopkArgs ft{};
+    ft.run_flag = run_flag;
     if (vt_lo != nullptr)
-        return run_compress<true, 2, 3>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk, heads, sl, forced_words, stream);
+        return run_compress<true, 2, 3, kStoreScores>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk, heads, sl, forced_words, ft, stream);
     // 3 compute waves + 1 loader wave, 3 LDS stages (72 KiB): two workgroups per CU.  Measured
     // best on MI355X against 4 + 1 waves and 2 or 4 stages.
-    return run_compress<false, 3, 3>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk, heads, sl, forced_words, stream);
+    return run_compress<false, 3, 3, kStoreScores>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, s_guide, ld_s, o_comp, n_blk, heads, sl, forced_words, ft, stream);
+}
+
+hipError_t launch_compress_threshold(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
+                                     const void *vt_hi, const void *vt_lo, float *o_comp, int64_t n_blk,
+                                     int heads, float scale, const unsigned long long *forced_words, int k,
+                                     float *thr, int *overflow, hipStream_t stream)
+{
+    if (k < 1 || k > kFusedTopkMaxK) return hipErrorInvalidValue;
+    const float sl = scale * kLog2e;
+    FusedTopkArgs ft{};
+    ft.thr = thr; ft.overflow = overflow; ft.k = k;
+    if (vt_lo != nullptr)
+        return run_compress<true, 2, 3, kThreshold>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
+    return run_compress<false, 3, 3, kThreshold>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
+}
+
+hipError_t launch_compress_filter(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
+                                  int64_t n_blk, int heads, const unsigned long long *forced_words,
+                                  const float *thr, int32_t *cand, int *cand_count, int cap, int *overflow,
+                                  hipStream_t stream)
+{
+    FusedTopkArgs ft{};
+    ft.thr = const_cast<float *>(thr); ft.cand = cand; ft.cand_count = cand_count; ft.cap = cap; ft.overflow = overflow;
+    return run_compress<false, 4, 3, kFilter>(qs_hi, qs_lo, ks_hi, ks_lo, nullptr, nullptr, nullptr, 0, nullptr, n_blk, heads, 0.f, forced_words, ft, stream);
 }
 
 }  // namespace s3r

@@ -59,6 +59,28 @@ __device__ __forceinline__ float other_half(float x)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Monotone map float -> uint32 (larger float <=> larger key); -0.0 is folded onto +0.0 first so
+// that equal scores compare equal.  Keys of real numbers are never 0.
+__device__ __forceinline__ uint32_t order_key(float x)
+{
+    x += 0.f;
+    const uint32_t b = __float_as_uint(x);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Inverse of order_key (the key of -inf maps back to -inf).
+__device__ __forceinline__ float key_to_float(uint32_t key)
+{
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
+// Number of set bits of `mask` below the calling lane.
+__device__ __forceinline__ int lanes_below(unsigned long long mask)
+{
+    return __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory, which
 // makes the compiler drain every outstanding vector load and store (s_waitcnt vmcnt(0)) before the
 // barrier; kernels that keep LDS-direct loads or fire-and-forget stores in flight across a barrier

@@ -42,10 +42,34 @@ hipError_t launch_split(const float *qc, const float *kc, const float *vc, void 
 // S_guide rows + compressed attention for `heads` heads (operand tiles as written by launch_split).
 // forced_words (optional): bit b of word kt set = pooled key 64 kt + b is a forced block; its
 // score is written as -inf so that TopK never picks it (it still takes part in the softmax).
+// Launches that take a run flag use a grid of at most this many workgroups, which walk over the work.
+constexpr unsigned kFlaggedGrid = 1024;
+
+// run_flag (optional, device): when given and 0 at run time the launch does nothing.
 hipError_t launch_compress(const void *qs_hi, const void *qs_lo, const void *ks_hi,
                            const void *ks_lo, const void *vt_hi, const void *vt_lo, float *s_guide,
                            int64_t ld_s, float *o_comp, int64_t n_blk, int heads, float scale,
-                           const unsigned long long *forced_words, hipStream_t stream);
+                           const unsigned long long *forced_words, const int *run_flag, hipStream_t stream);
+
+// TopK without S_guide in memory, k <= kFusedTopkMaxK, in three launches:
+//  threshold: the compression sweep (writes o_comp) that also leaves, per query row, a lower bound
+//             thr [heads][n_blk] of its k-th largest non-forced score, and clears *overflow;
+//  filter:    recomputes the scores and appends the index of every one >= the bound to
+//             cand [heads][n_blk][2][cap] (counts in cand_count [heads][n_blk][2], which may exceed
+//             cap: the list is then cut and *overflow set);
+//  candidates (launch_topk_candidates): exact TopK among the candidates from fp32 dot products.
+constexpr int kFusedTopkMaxK = 64;
+hipError_t launch_compress_threshold(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
+                                     const void *vt_hi, const void *vt_lo, float *o_comp, int64_t n_blk,
+                                     int heads, float scale, const unsigned long long *forced_words, int k,
+                                     float *thr, int *overflow, hipStream_t stream);
+hipError_t launch_compress_filter(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
+                                  int64_t n_blk, int heads, const unsigned long long *forced_words,
+                                  const float *thr, int32_t *cand, int *cand_count, int cap, int *overflow,
+                                  hipStream_t stream);
+// qc, kc: fp32 [heads][n_blk][64] of the same heads; idx [heads * n_blk][k].
+hipError_t launch_topk_candidates(const float *qc, const float *kc, const int32_t *cand, const int *cand_count,
+                                  int cap, int32_t *idx, int64_t n_blk, int heads, int k, hipStream_t stream);
 
 // Forced (always attended) blocks: clamp the caller's list into `forced_clean` and build the
 // 64-key bit words for the compression kernel.
@@ -57,8 +81,9 @@ hipError_t launch_merge_forced(const int32_t *dyn, int k_dyn, const int32_t *for
                                int32_t *out, int64_t n_rows, hipStream_t stream);
 
 // TopK of each of n_rows rows of s_guide (row r at s_guide + r * ld_s, n_blk valid entries).
+// run_flag (optional, device): when given and 0 at run time the launch does nothing.
 hipError_t launch_topk(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t n_blk,
-                       int64_t n_rows, int k, hipStream_t stream);
+                       int64_t n_rows, int k, const int *run_flag, hipStream_t stream);
 
 struct SelectArgs {
     const void *q, *k, *v;     // [rows][heads][64], the caller's layout

@@ -39,9 +39,11 @@ constexpr size_t kScoreBytesCap = size_t(8) << 30;  // S_guide is processed in h
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int g_kernel_choice = 0;  // 0 auto, 1 generic only
+int g_kernel_choice = 0;  // 0 auto, 1 generic attention kernels only, 2 TopK from scores written to memory
 
-bool mfma_ok(s3r_dtype dtype, int block) { return g_kernel_choice == 0 && dtype == S3R_BF16 && (block == 64 || block == 128); }
+bool mfma_ok(s3r_dtype dtype, int block) { return g_kernel_choice != 1 && dtype == S3R_BF16 && (block == 64 || block == 128); }
+
+constexpr int kCandCap = 512;  // candidate slots per list of the TopK-in-the-sweep path (two lists per row)
 
 s3r_status check_shape(int64_t n_tok, int heads, int head_dim, int block, int topk, int dtype)
 {
@@ -64,7 +66,8 @@ struct Layout {
     int kk;      // blocks TopK picks per row (among the non-forced ones)
     int width;   // blocks attended per row: kk + n_forced
     int head_chunk;
-    size_t qc, kc, vc, oc, tile[6], idx, idx_merged, forced_clean, forced_words, s, kb, vb, kb_spec, vb_spec, total;
+    size_t qc, kc, vc, oc, tile[6], idx, idx_merged, forced_clean, forced_words, s, kb, vb, kb_spec, vb_spec;
+    size_t thr, cand, cand_count, overflow, total;
 };
 
 // n_tok: tokens on the sparse path (the image tokens); n_spec: special tokens (dense rows).
@@ -102,6 +105,12 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, 
     const size_t spec_tiles = mfma_ok(dtype, block) ? static_cast<size_t>(heads) * ((n_spec + 63) / 64) * 64 * 64 * 2 : 0;
     L.kb_spec = take(spec_tiles);
     L.vb_spec = take(spec_tiles);
+    // TopK-in-the-sweep buffers, per head chunk like S
+    const size_t chunk_rows = static_cast<size_t>(L.head_chunk) * L.n_blk;
+    L.thr = take(chunk_rows * sizeof(float));
+    L.cand = take(chunk_rows * 2 * kCandCap * sizeof(int32_t));
+    L.cand_count = take(chunk_rows * 2 * sizeof(int));
+    L.overflow = take(sizeof(int));
     L.total = off;
     return L;
 }
@@ -174,13 +183,25 @@ struct StageTimer {
 
 char *at(void *base, size_t off) { return static_cast<char *>(base) + off; }
 
+// Buffers of the TopK-in-the-sweep path (all null: TopK from scores written to s_buf).
+struct FusedBufs {
+    float *thr = nullptr;
+    int32_t *cand = nullptr;
+    int *cand_count = nullptr;
+    int *overflow = nullptr;
+};
+
 // pooled fp32 -> operand tiles -> S_guide / Oc' -> TopK, in head chunks bounded by the S buffer
 s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, void *const tile[6],
                              float *s_buf, int64_t ld_s, int head_chunk, float *o_comp, int32_t *idx,
                              int64_t n_blk, int64_t tiles, int heads, int kk, float scale,
                              bool accurate_pv, bool want_topk, const unsigned long long *forced_words,
-                             hipStream_t stream)
+                             const FusedBufs &fb, hipStream_t stream)
 {
+    // Without S_guide in memory when k allows it.  Should a candidate list run over (long runs of
+    // equal scores), the overflow word makes the two plain launches that follow redo the chunk;
+    // otherwise they return at once.
+    const bool fused = want_topk && fb.thr != nullptr && kk >= 1 && kk <= s3r::kFusedTopkMaxK && g_kernel_choice != 2;
     {
         StageTimer tm(S3R_STAGE_SPLIT, stream);
         S3R_HIP(s3r::launch_split(qc, kc, vc, tile[0], tile[1], tile[2], tile[3], tile[4],
@@ -190,6 +211,30 @@ s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, 
     const size_t tile_head = static_cast<size_t>(tiles) * 32 * 64 * 2;  // bytes per head per array
     for (int h0 = 0; h0 < heads; h0 += head_chunk) {
         const int hc = (heads - h0 < head_chunk) ? heads - h0 : head_chunk;
+        if (fused) {
+            {
+                StageTimer tm(S3R_STAGE_COMPRESS, stream);
+                S3R_HIP(s3r::launch_compress_threshold(at(tile[0], h0 * tile_head), at(tile[1], h0 * tile_head),
+                                                       at(tile[2], h0 * tile_head), at(tile[3], h0 * tile_head),
+                                                       at(tile[4], h0 * tile_head),
+                                                       accurate_pv ? at(tile[5], h0 * tile_head) : nullptr,
+                                                       o_comp + static_cast<size_t>(h0) * n_blk * 64, n_blk, hc, scale,
+                                                       forced_words, kk, fb.thr, fb.overflow, stream),
+                        "compress (threshold) kernel launch");
+            }
+            StageTimer tm(S3R_STAGE_TOPK, stream);
+            S3R_HIP(s3r::launch_compress_filter(at(tile[0], h0 * tile_head), at(tile[1], h0 * tile_head),
+                                                at(tile[2], h0 * tile_head), at(tile[3], h0 * tile_head), n_blk, hc,
+                                                forced_words, fb.thr, fb.cand, fb.cand_count, kCandCap, fb.overflow,
+                                                stream),
+                    "compress (filter) kernel launch");
+            S3R_HIP(s3r::launch_topk_candidates(qc + static_cast<size_t>(h0) * n_blk * 64,
+                                                kc + static_cast<size_t>(h0) * n_blk * 64, fb.cand, fb.cand_count,
+                                                kCandCap, idx + static_cast<size_t>(h0) * n_blk * kk, n_blk, hc, kk,
+                                                stream),
+                    "candidate topk kernel launch");
+        }
+        const int *run_flag = fused ? fb.overflow : nullptr;
         {
             StageTimer tm(S3R_STAGE_COMPRESS, stream);
             S3R_HIP(s3r::launch_compress(at(tile[0], h0 * tile_head), at(tile[1], h0 * tile_head),
@@ -197,13 +242,13 @@ s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, 
                                          at(tile[4], h0 * tile_head),
                                          accurate_pv ? at(tile[5], h0 * tile_head) : nullptr, s_buf, ld_s,
                                          o_comp + static_cast<size_t>(h0) * n_blk * 64, n_blk, hc, scale,
-                                         forced_words, stream),
+                                         forced_words, run_flag, stream),
                     "compress kernel launch");
         }
         if (want_topk && kk > 0) {
             StageTimer tm(S3R_STAGE_TOPK, stream);
             S3R_HIP(s3r::launch_topk(s_buf, ld_s, idx + static_cast<size_t>(h0) * n_blk * kk, n_blk,
-                                     static_cast<int64_t>(hc) * n_blk, kk, stream),
+                                     static_cast<int64_t>(hc) * n_blk, kk, run_flag, stream),
                     "topk kernel launch");
         }
     }
@@ -256,7 +301,7 @@ s3r_status speed3r_set_profiling(int enable)
 
 s3r_status speed3r_set_kernel_choice(int choice)
 {
-    if (choice != 0 && choice != 1) return fail(S3R_ERR_INVALID_ARG, "kernel choice %d unknown", choice);
+    if (choice < 0 || choice > 2) return fail(S3R_ERR_INVALID_ARG, "kernel choice %d unknown", choice);
     g_kernel_choice = choice;
     return S3R_OK;
 }
@@ -379,13 +424,18 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
                                  sp.img, stream),
                 "pool kernel launch");
     }
+    FusedBufs fb;
+    fb.thr = reinterpret_cast<float *>(at(ws, L.thr));
+    fb.cand = reinterpret_cast<int32_t *>(at(ws, L.cand));
+    fb.cand_count = reinterpret_cast<int *>(at(ws, L.cand_count));
+    fb.overflow = reinterpret_cast<int *>(at(ws, L.overflow));
     if (n_forced > 0) {
         StageTimer tm(S3R_STAGE_TOPK, stream);
         S3R_HIP(s3r::launch_forced_prepare(p->forced_blocks, n_forced, L.n_blk, forced_clean, forced_words, stream),
                 "forced-block prepare kernel launch");
     }
     st = run_compress_topk(qc, kc, vc, tile, reinterpret_cast<float *>(at(ws, L.s)), L.ld_s, L.head_chunk, oc,
-                           idx_dyn, L.n_blk, L.tiles, p->heads, L.kk, scale, !is_bf16, true, forced_words, stream);
+                           idx_dyn, L.n_blk, L.tiles, p->heads, L.kk, scale, !is_bf16, true, forced_words, fb, stream);
     if (st != S3R_OK) return st;
     if (n_forced > 0) {
         StageTimer tm(S3R_STAGE_TOPK, stream);
@@ -479,7 +529,7 @@ s3r_status speed3r_compress_attn_scores(const float *qc, const float *kc, const 
     void *tile[6];
     for (int a = 0; a < 6; ++a) tile[a] = at(ws, a * arr);
     return run_compress_topk(qc, kc, vc, tile, s_guide, ld_s, heads, o_comp, nullptr, n_blk, tiles, heads, 0,
-                             resolve_scale(softmax_scale, head_dim), accurate_pv != 0, false, nullptr,
+                             resolve_scale(softmax_scale, head_dim), accurate_pv != 0, false, nullptr, FusedBufs{},
                              static_cast<hipStream_t>(stream));
 }
 
@@ -492,7 +542,7 @@ s3r_status speed3r_topk_blocks(const float *s_guide, int64_t ld_s, int32_t *idx,
     if (n_blk * heads > 0x7fffffffLL) return fail(S3R_ERR_UNSUPPORTED, "n_blk * heads exceeds 2^31 - 1");
     const int kk = static_cast<int>(topk < n_blk ? topk : n_blk);
     StageTimer tm(S3R_STAGE_TOPK, static_cast<hipStream_t>(stream));
-    S3R_HIP(s3r::launch_topk(s_guide, ld_s, idx, n_blk, n_blk * heads, kk, static_cast<hipStream_t>(stream)),
+    S3R_HIP(s3r::launch_topk(s_guide, ld_s, idx, n_blk, n_blk * heads, kk, nullptr, static_cast<hipStream_t>(stream)),
             "topk kernel launch");
     return S3R_OK;
 }

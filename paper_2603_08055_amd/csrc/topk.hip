@@ -21,15 +21,6 @@ namespace s3r {
 constexpr int kTopkThreads = 256;
 constexpr int kTopkCap = 1024;  // candidate slots of the streaming fast path
 
-// Monotone map float -> uint32 (larger float <=> larger key); -0.0 is folded onto +0.0 first so
-// that equal scores compare equal.
-__device__ __forceinline__ uint32_t order_key(float x)
-{
-    x += 0.f;
-    const uint32_t b = __float_as_uint(x);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-
 __device__ __forceinline__ int block_sum(int v, int *scratch /*[4]*/)
 {
     // sum over the 256 threads; every thread gets the result
@@ -39,13 +30,6 @@ __device__ __forceinline__ int block_sum(int v, int *scratch /*[4]*/)
     if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
     __syncthreads();
     return scratch[0] + scratch[1] + scratch[2] + scratch[3];
-}
-
-__device__ __forceinline__ int lanes_below(unsigned long long mask)
-{
-    // number of set bits of `mask` below the calling lane
-    return __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),
-                                     __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));
 }
 
 // Exact selection over the whole row, all 256 threads: T = k-th largest key by a bitwise search,
@@ -104,8 +88,8 @@ __device__ void topk_exact_path(const float *__restrict__ row, int32_t *__restri
 // NV = maximum row entries per lane; the four waves own equal contiguous shares of the row.
 // Requires n_blk <= NV * 256 and k <= 256.
 template <int NV>
-__global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float *__restrict__ s_guide, int64_t ld_s,
-                                                                 int32_t *__restrict__ idx, int n_blk, int k)
+__device__ __forceinline__ void topk_reg_row(const float *__restrict__ s_guide, int64_t ld_s,
+                                             int32_t *__restrict__ idx, int n_blk, int k, unsigned row_id)
 {
     constexpr int CAPW = 256;  // candidate slots per wave
     __shared__ uint32_t lane_max[kTopkThreads];
@@ -117,14 +101,14 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float *__r
     __shared__ int wave_cnt[2][4];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const float *row = s_guide + static_cast<int64_t>(blockIdx.x) * ld_s;
-    int32_t *out = idx + static_cast<int64_t>(blockIdx.x) * k;
+    const float *row = s_guide + static_cast<int64_t>(row_id) * ld_s;
+    int32_t *out = idx + static_cast<int64_t>(row_id) * k;
     // equal shares: each wave owns wave_len consecutive entries (a multiple of 64, <= NV * 64)
     const int wave_len = ((n_blk + 3) / 4 + 63) / 64 * 64;
     const int wave_base = __builtin_amdgcn_readfirstlane(wave) * wave_len;
     const int wave_end = (wave_base + wave_len < n_blk) ? wave_base + wave_len : n_blk;
     const int base = wave_base + lane;
-    const int leader = blockIdx.x & 3;  // the wave that does the serial parts rotates with the row
+    const int leader = row_id & 3;  // the wave that does the serial parts rotates with the row
 
     // Entries past the end of the row are NaN: v_max ignores them and every ordered compare fails.
     float x[NV];
@@ -161,7 +145,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float *__r
     // The threshold as a float: x >= thr_f  <=>  order_key(x) >= thr (signed zeros compare equal
     // either way; the key of -inf, reached only when fewer than k lanes hold data, maps back to -inf).
     const uint32_t thr = thr_sh;
-    const float thr_f = __uint_as_float((thr & 0x80000000u) ? (thr & 0x7fffffffu) : ~thr);
+    const float thr_f = key_to_float(thr);
     int cnt = 0;
     constexpr int GRP = (NV % 4 == 0) ? 4 : 1;
 #pragma unroll
@@ -233,9 +217,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float *__r
         }
 }
 
-__global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(const float *__restrict__ s_guide,
-                                                             int64_t ld_s, int32_t *__restrict__ idx,
-                                                             int n_blk, int k)
+__device__ __forceinline__ void topk_stream_row(const float *__restrict__ s_guide, int64_t ld_s,
+                                                int32_t *__restrict__ idx, int n_blk, int k, unsigned row_id)
 {
     __shared__ uint32_t tmax[kTopkThreads];
     __shared__ uint32_t cand_key[kTopkCap];
@@ -247,8 +230,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(const float *
     __shared__ int wave_cnt[2][4];
 
     const int tid = threadIdx.x;
-    const float *row = s_guide + static_cast<int64_t>(blockIdx.x) * ld_s;
-    int32_t *out = idx + static_cast<int64_t>(blockIdx.x) * k;
+    const float *row = s_guide + static_cast<int64_t>(row_id) * ld_s;
+    int32_t *out = idx + static_cast<int64_t>(row_id) * k;
 
     bool slow = k > kTopkThreads;
     if (!slow) {
@@ -306,6 +289,144 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(const float *
     }
 
     topk_exact_path(row, out, n_blk, k, scratch, wave_cnt);
+}
+
+// One workgroup per row; or, with a run flag (device word), a small grid that does nothing when the
+// word is 0 and walks over all rows otherwise (the rarely needed second route of a caller that
+// cannot read the word on the host: launching one workgroup per row just to return costs
+// hundreds of microseconds at 10^5 rows).
+template <int NV>
+__global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float *__restrict__ s_guide, int64_t ld_s,
+                                                                 int32_t *__restrict__ idx, int n_blk, int k,
+                                                                 unsigned n_rows, const int *__restrict__ run_flag)
+{
+    if (run_flag == nullptr) {
+        topk_reg_row<NV>(s_guide, ld_s, idx, n_blk, k, blockIdx.x);
+        return;
+    }
+    if (*run_flag == 0) return;  // uniform over the grid
+    for (unsigned r = blockIdx.x; r < n_rows; r += gridDim.x) {
+        topk_reg_row<NV>(s_guide, ld_s, idx, n_blk, k, r);
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(const float *__restrict__ s_guide, int64_t ld_s,
+                                                                    int32_t *__restrict__ idx, int n_blk, int k,
+                                                                    unsigned n_rows, const int *__restrict__ run_flag)
+{
+    if (run_flag == nullptr) {
+        topk_stream_row(s_guide, ld_s, idx, n_blk, k, blockIdx.x);
+        return;
+    }
+    if (*run_flag == 0) return;  // uniform over the grid
+    for (unsigned r = blockIdx.x; r < n_rows; r += gridDim.x) {
+        topk_stream_row(s_guide, ld_s, idx, n_blk, k, r);
+        __syncthreads();
+    }
+}
+
+// Exact TopK among the candidates the filter sweep of the compression kernel left for a row (two
+// lists per row, see compress.hip).  One wave per row.  The scores are recomputed here as plain fp32
+// dot products of the pooled query and key (channels in order, fused multiply-add), so the result
+// does not depend on how the filter computed its own copy beyond which keys became candidates.
+// Ties go to the smaller index; output ascending.  Requires k <= 64 and at most 2 * cap <= 2048
+// candidates (lists that were cut are read up to cap: the caller redoes such launches).
+constexpr int kCandSlots = 32;  // candidates per lane
+__global__ __launch_bounds__(64) void topk_candidates_kernel(const float *__restrict__ qc, const float *__restrict__ kc,
+                                                            const int32_t *__restrict__ cand,
+                                                            const int *__restrict__ cand_count, int cap,
+                                                            int32_t *__restrict__ idx, int n_blk, int k)
+{
+    __shared__ __attribute__((aligned(16))) float qs[64];
+    __shared__ int32_t ties[kCandSlots * 64];
+    __shared__ int32_t win[64];
+    const int lane = threadIdx.x;
+    const int64_t row = blockIdx.x;           // head * n_blk + query block
+    const int64_t head = row / n_blk;
+    const int c0 = cand_count[row * 2], c1 = cand_count[row * 2 + 1];
+    const int n0 = c0 < cap ? c0 : cap, n1 = c1 < cap ? c1 : cap;
+    const int n = n0 + n1;
+    const int32_t *l0 = cand + row * 2 * cap, *l1 = l0 + cap;
+    const float *kh = kc + head * n_blk * 64;
+    qs[lane] = qc[row * 64 + lane];
+    __syncthreads();
+    const int kk = k < n ? k : n;
+
+    uint32_t key[kCandSlots];
+    int32_t id[kCandSlots];
+#pragma unroll
+    for (int s = 0; s < kCandSlots; ++s) {
+        key[s] = 0u;  // below the key of every real number
+        id[s] = 0;
+        if (s * 64 < n) {  // wave-uniform
+            const int c = s * 64 + lane;
+            if (c < n) {
+                const int32_t j = c < n0 ? l0[c] : l1[c - n0];
+                const floatx4 *kr = reinterpret_cast<const floatx4 *>(kh + static_cast<int64_t>(j) * 64);
+                float acc = 0.f;
+#pragma unroll
+                for (int d4 = 0; d4 < 16; ++d4) {
+                    const floatx4 kv = kr[d4];
+                    const floatx4 qv = *reinterpret_cast<const floatx4 *>(&qs[4 * d4]);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc = __builtin_fmaf(qv[i], kv[i], acc);
+                }
+                key[s] = order_key(acc);
+                id[s] = j;
+            }
+        }
+    }
+    // k-th largest key by a bitwise search with wave ballots
+    uint32_t T = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t trial = T | (1u << bit);
+        int c = 0;
+#pragma unroll
+        for (int s = 0; s < kCandSlots; ++s)
+            if (s * 64 < n) c += __popcll(__ballot(key[s] >= trial));
+        if (c >= kk) T = trial;
+    }
+    // winners above T, in any order; ties at T collected for the index rule
+    int n_win = 0, n_tie = 0;
+#pragma unroll
+    for (int s = 0; s < kCandSlots; ++s)
+        if (s * 64 < n) {
+            const bool gt = key[s] > T, eq = key[s] == T;
+            const unsigned long long gm = __ballot(gt), em = __ballot(eq);
+            if (gt) win[n_win + lanes_below(gm)] = id[s];
+            if (eq) ties[n_tie + lanes_below(em)] = id[s];
+            n_win += __popcll(gm);
+            n_tie += __popcll(em);
+        }
+    __syncthreads();
+    const int need = kk - n_win;  // ties to keep: the `need` smallest indices among them
+#pragma unroll
+    for (int s = 0; s < kCandSlots; ++s)
+        if (s * 64 < n && __ballot(key[s] == T) != 0ull) {
+            int rank = 0;
+            for (int o = 0; o < n_tie; ++o) rank += ties[o] < id[s] ? 1 : 0;
+            if (key[s] == T && rank < need) win[n_win + rank] = id[s];
+        }
+    __syncthreads();
+    // ascending order: place = number of winners with a smaller index
+    if (lane < kk) {
+        const int32_t v = win[lane];
+        int place = 0;
+        for (int o = 0; o < kk; ++o) place += win[o] < v ? 1 : 0;
+        idx[row * k + place] = v;
+    }
+}
+
+hipError_t launch_topk_candidates(const float *qc, const float *kc, const int32_t *cand, const int *cand_count,
+                                  int cap, int32_t *idx, int64_t n_blk, int heads, int k, hipStream_t stream)
+{
+    const int64_t rows = n_blk * heads;
+    if (rows > 0x7fffffffLL || n_blk > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (k < 1 || k > 64 || cap < 1 || 2 * cap > kCandSlots * 64) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(topk_candidates_kernel, dim3(static_cast<unsigned>(rows)), dim3(64), 0, stream, qc, kc, cand,
+                       cand_count, cap, idx, static_cast<int>(n_blk), k);
+    return hipGetLastError();
 }
 
 // Forced blocks (Sec. 3.3): one workgroup clamps the caller's list and sets the per-64-key bit words.
@@ -374,14 +495,15 @@ hipError_t launch_merge_forced(const int32_t *dyn, int k_dyn, const int32_t *for
 }
 
 hipError_t launch_topk(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t n_blk,
-                       int64_t n_rows, int k, hipStream_t stream)
+                       int64_t n_rows, int k, const int *run_flag, hipStream_t stream)
 {
     if (n_rows > 0x7fffffffLL || n_blk > 0x7fffffffLL) return hipErrorInvalidValue;
-    const dim3 grid(static_cast<unsigned>(n_rows)), block(kTopkThreads);
+    const unsigned rows = static_cast<unsigned>(n_rows);
+    const dim3 grid(run_flag != nullptr && rows > kFlaggedGrid ? kFlaggedGrid : rows), block(kTopkThreads);
     const int nb = static_cast<int>(n_blk);
 #define S3R_TOPK_REG(NV)                                                                            \
     if (k <= kTopkThreads && nb <= (NV) * 256) {                                                    \
-        hipLaunchKernelGGL(topk_reg_kernel<NV>, grid, block, 0, stream, s_guide, ld_s, idx, nb, k); \
+        hipLaunchKernelGGL(topk_reg_kernel<NV>, grid, block, 0, stream, s_guide, ld_s, idx, nb, k, rows, run_flag); \
         return hipGetLastError();                                                                   \
     }
     S3R_TOPK_REG(1)
@@ -395,7 +517,7 @@ hipError_t launch_topk(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t
     S3R_TOPK_REG(96)
     S3R_TOPK_REG(128)
 #undef S3R_TOPK_REG
-    hipLaunchKernelGGL(topk_stream_kernel, grid, block, 0, stream, s_guide, ld_s, idx, nb, k);
+    hipLaunchKernelGGL(topk_stream_kernel, grid, block, 0, stream, s_guide, ld_s, idx, nb, k, rows, run_flag);
     return hipGetLastError();
 }
 

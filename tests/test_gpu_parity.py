@@ -262,6 +262,60 @@ def test_config5_pi3_block128_small(s3r, oracle, topk):
     end_to_end(s3r, oracle, wl, rows=rows, with_gate=(topk == 16))
 
 
+# ------------------------------------ TopK inside the compression sweep vs from stored scores --
+
+@pytest.mark.parametrize("cfg,over", [(2, {}), (3, {"views": 20}), (5, {"views": 12, "topk": 64}),
+                                      (1, {})])
+def test_topk_from_stored_scores_path(s3r, oracle, cfg, over):
+    """The default path selects without S_guide in memory whenever k <= 64; this keeps the
+    stored-score TopK covered end to end on the same workloads."""
+    s3r.speed3r_set_kernel_choice(2)
+    try:
+        end_to_end(s3r, oracle, workloads.config(cfg, **over), with_gate=True, label=f"config{cfg}/stored scores")
+    finally:
+        s3r.speed3r_set_kernel_choice(0)
+
+
+def test_topk_in_sweep_candidate_overflow_falls_back(s3r, oracle):
+    """All-zero queries make every score of a row equal: every key passes the filter, the candidate
+    lists run over, and the call must redo TopK from stored scores (first k blocks win the tie)."""
+    wl = workloads.Workload("ties_2000_blocks", 1, 2000 * 64, 2, 64, "bf16", 64, 8, 93, "normal")
+    q, k, v = workloads.make_inputs(wl, device="cuda")
+    q.zero_()
+    res = run_device(s3r, q, k, v, wl.block, wl.topk)
+    want = torch.arange(8, dtype=torch.int32, device="cuda").expand(2, 2000, 8)
+    assert torch.equal(res["idx"], want)
+    rows = np.array([0, 1, 777, 1999])
+    compare_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v), None, wl.block, wl.topk,
+                        wl.dtype, rows=rows, label="all-tie rows")
+    # half the rows tie, half do not: the fallback redoes the whole call consistently
+    q2, _, _ = workloads.make_inputs(wl, device="cuda")
+    q2[: wl.n_tok // 2].zero_()
+    res2 = run_device(s3r, q2, k, v, wl.block, wl.topk)
+    assert torch.equal(res2["idx"][:, :1000], want[:, :1000])
+    rows2 = np.array([0, 999, 1000, 1500, 1999])
+    compare_with_oracle(oracle, res2, to_host_f32(q2), to_host_f32(k), to_host_f32(v), None, wl.block, wl.topk,
+                        wl.dtype, rows=rows2, label="half-tie rows")
+
+
+def test_topk_in_sweep_is_deterministic_and_agrees_with_stored_scores(s3r):
+    """Two runs agree bit for bit; the stored-score route picks the same sets except where the two
+    roundings of a score resolve a near-tie differently (rare), and Oc' is the same either way."""
+    wl = workloads.Workload("two_routes", 1, 700 * 64, 2, 64, "bf16", 64, 12, 95, "normal")
+    q, kx, v = workloads.make_inputs(wl, device="cuda")
+    a = run_device(s3r, q, kx, v, wl.block, wl.topk)
+    b = run_device(s3r, q, kx, v, wl.block, wl.topk)
+    assert torch.equal(a["idx"], b["idx"]) and torch.equal(a["out"], b["out"])
+    s3r.speed3r_set_kernel_choice(2)
+    try:
+        c = run_device(s3r, q, kx, v, wl.block, wl.topk)
+    finally:
+        s3r.speed3r_set_kernel_choice(0)
+    same_rows = (a["idx"] == c["idx"]).all(dim=2).float().mean().item()
+    assert same_rows > 0.99, same_rows
+    assert torch.equal(a["o_comp"], c["o_comp"])
+
+
 # ------------------------------------------------- forced global-context blocks (Sec. 3.3) --
 
 def test_forced_blocks_vggt_8_views(s3r, oracle):
