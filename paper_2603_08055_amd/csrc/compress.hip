@@ -72,6 +72,7 @@ __device__ __forceinline__ half2_t pack_rtz(float a, float b)
 }
 
 enum CompressMode { kStoreScores = 0, kThreshold = 1, kFilter = 2 };
+constexpr int kFilterQT = 1;  // query tiles (of 32 pooled queries) per wave of the filter sweep
 
 // What the TopK-in-the-sweep modes read and write besides the operands.
 struct FusedTopkArgs {
@@ -138,6 +139,103 @@ __device__ __forceinline__ void compress_block(
     }
 
     // ---- compute waves ---------------------------------------------------------------------------
+    if constexpr (MODE == kFilter) {
+        // Scores only, kFilterQT query tiles per wave.  (Two tiles per wave, which halves the LDS reads
+        // per MFMA, measured no faster on MI355X: the sweep is bound by neither.)
+        constexpr int QT = kFilterQT;
+        const int64_t qtile0 = (static_cast<int64_t>(bx) * CW + wave) * QT;
+        const bool wave_active = qtile0 * 32 < n_blk;
+        bf16x8 qhi[QT][4], qlo[QT][4];
+        float thr_f[QT];           // NaN for rows that do not exist: nothing passes
+        int32_t *cand_row[QT];
+        int n_cand[QT];
+        int64_t row_id[QT];
+        bool row_ok[QT];
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+            const int64_t qrow = (qtile0 + t) * 32 + (lane & 31);
+            row_ok[t] = qrow < n_blk;
+            row_id[t] = static_cast<int64_t>(h) * n_blk + (row_ok[t] ? qrow : 0);
+            thr_f[t] = row_ok[t] ? ft.thr[row_id[t]] : __builtin_nanf("");
+            cand_row[t] = ft.cand + (row_id[t] * 2 + g) * ft.cap;
+            n_cand[t] = 0;
+            if (wave_active) {
+                // tiles past the end of the head's padded range are never read: clamp to the last one
+                const int64_t qt = (qtile0 + t < tiles_padded) ? qtile0 + t : tiles_padded - 1;
+                const int64_t qb = (head_tiles + qt) * kRowTileElems;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    qhi[t][s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
+                    qlo[t][s] = *reinterpret_cast<const bf16x8 *>(qs_lo + qb + (s * 64 + lane) * 8);
+                }
+            }
+        }
+        for (int64_t kt = 0; kt < n_kt; ++kt) {
+            lds_barrier();
+            if (!wave_active) continue;
+            const bf16_t *k_hi = &ring[kt % NS][0][0];
+            const bf16_t *k_lo = &ring[kt % NS][1][0];
+            const unsigned long long fw = (forced_words != nullptr) ? forced_words[kt] : 0ull;  // wave-uniform
+            floatx16 sacc[QT][2];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+                for (int t = 0; t < QT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sacc[t][mt][r] = 0.f;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int off = mt * kRowTileElems + (s * 64 + lane) * 8;
+                    const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + off);
+                    const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(k_lo + off);
+#pragma unroll
+                    for (int t = 0; t < QT; ++t) {  // same MFMA order as the threshold sweep: same bits
+                        sacc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, qhi[t][s], sacc[t][mt], 0, 0, 0);
+                        sacc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qlo[t][s], sacc[t][mt], 0, 0, 0);
+                        sacc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[t][s], sacc[t][mt], 0, 0, 0);
+                    }
+                }
+            }
+            // keys that do not exist or are forced never become candidates: NaN fails every compare
+            if (kt * 64 + 64 > n_blk || fw != 0ull) {
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int b = mt * 32 + acc_row(lane, r);
+                        if (kt * 64 + b >= n_blk || ((fw >> b) & 1ull)) {
+#pragma unroll
+                            for (int t = 0; t < QT; ++t) sacc[t][mt][r] = __builtin_nanf("");
+                        }
+                    }
+            }
+#pragma unroll
+            for (int t = 0; t < QT; ++t) {
+                unsigned pass = 0u;  // register (mt, r) -> bit 31 - (16 mt + r): ascending key = descending bit
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) pass = (pass << 1) | (sacc[t][mt][r] >= thr_f[t] ? 1u : 0u);
+                while (pass != 0u) {
+                    const int b = __clz(pass);
+                    pass &= ~(0x80000000u >> b);
+                    const int key = static_cast<int>(kt) * 64 + 32 * (b >> 4) + acc_row(lane, b & 15);
+                    if (n_cand[t] < ft.cap) cand_row[t][n_cand[t]] = key;
+                    ++n_cand[t];
+                }
+            }
+        }
+        if (wave_active) {
+#pragma unroll
+            for (int t = 0; t < QT; ++t)
+                if (row_ok[t]) {
+                    ft.cand_count[row_id[t] * 2 + g] = n_cand[t];
+                    if (n_cand[t] > ft.cap) atomicOr(ft.overflow, 1);
+                }
+        }
+        return;
+    }
     const int64_t qtile = static_cast<int64_t>(bx) * CW + wave;
     const int64_t qrow = qtile * 32 + (lane & 31);
     const bool wave_active = qtile * 32 < n_blk;
@@ -162,18 +260,11 @@ __device__ __forceinline__ void compress_block(
 
     half2_t bmax[2][16];         // kThreshold: running maxima of the score registers (pairs, fp16 rounded
                                  // toward zero), even and odd steps apart
-    float thr_f = 0.f;           // kFilter: this query's bound (NaN for rows that do not exist: nothing passes)
-    int32_t *cand_row = nullptr; // kFilter: this lane's candidate list
-    int n_cand = 0;
     if constexpr (MODE == kThreshold) {
 #pragma unroll
         for (int par = 0; par < 2; ++par)
 #pragma unroll
             for (int i = 0; i < 16; ++i) bmax[par][i] = half2_t{-INFINITY, -INFINITY};
-    }
-    if constexpr (MODE == kFilter) {
-        thr_f = (qrow < n_blk) ? ft.thr[row_id] : __builtin_nanf("");
-        cand_row = ft.cand + (row_id * 2 + g) * ft.cap;
     }
 
     for (int64_t kt = 0; kt < n_kt; ++kt) {
@@ -220,32 +311,6 @@ __device__ __forceinline__ void compress_block(
                         }
                     }
             }
-        }
-        if constexpr (MODE == kFilter) {
-            // keys that do not exist or are forced never become candidates: NaN fails every compare
-            if (kt * 64 + 64 > n_blk || fw != 0ull) {
-                asm volatile("" ::: "memory");
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int b = mt * 32 + acc_row(lane, r);
-                        if (kt * 64 + b >= n_blk || ((fw >> b) & 1ull)) sacc[mt][r] = __builtin_nanf("");
-                    }
-            }
-            unsigned pass = 0u;  // register (mt, r) -> bit 31 - (16 mt + r): ascending key = descending bit
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) pass = (pass << 1) | (sacc[mt][r] >= thr_f ? 1u : 0u);
-            while (pass != 0u) {
-                const int b = __clz(pass);
-                pass &= ~(0x80000000u >> b);
-                const int key = static_cast<int>(kt) * 64 + 32 * (b >> 4) + acc_row(lane, b & 15);
-                if (n_cand < ft.cap) cand_row[n_cand] = key;
-                ++n_cand;
-            }
-            continue;
         }
         if (kt * 64 + 64 > n_blk) {           // pooled keys past the end of the sequence do not exist
             asm volatile("" ::: "memory");    // keep this rare path a real branch
@@ -332,13 +397,6 @@ __device__ __forceinline__ void compress_block(
         }
     }
 
-    if constexpr (MODE == kFilter) {
-        if (wave_active && qrow < n_blk) {
-            ft.cand_count[row_id * 2 + g] = n_cand;
-            if (n_cand > ft.cap) atomicOr(ft.overflow, 1);
-        }
-        return;
-    }
     if constexpr (MODE == kThreshold) {
         if (wave_active) {
             // k-th largest of the query's 128 bucket maxima (64 here, 64 in the lane 32 positions away),
@@ -422,7 +480,8 @@ static hipError_t run_compress(const void *qs_hi, const void *qs_lo, const void 
 {
     const int64_t tiles = pooled_tiles_padded(n_blk);
     const int64_t q_tiles = (n_blk + 31) / 32;
-    const unsigned gx = static_cast<unsigned>((q_tiles + CW - 1) / CW), gy = static_cast<unsigned>(heads);
+    constexpr int TPW = (MODE == kFilter) ? CW * kFilterQT : CW;  // query tiles per workgroup
+    const unsigned gx = static_cast<unsigned>((q_tiles + TPW - 1) / TPW), gy = static_cast<unsigned>(heads);
     dim3 grid(gx, gy);
     if (MODE == kStoreScores && ft.run_flag != nullptr) {
         const unsigned long long total = static_cast<unsigned long long>(gx) * gy;
