@@ -312,3 +312,69 @@ def gsa_layer(q, k, v, block: int, topk_blocks: int, tokens_per_view: int, speci
         out[img_rows[tok]] = vals
         res["out"] = out
     return res
+
+
+def window_blocks(views: int, tokens_per_view: int, special_per_view: int, grid_h: int, grid_w: int,
+                  window: int):
+    """Rows of each spatial pooling window (Sec. 3.2: non-overlapping s x s average pooling on
+    every image's patch grid).  A view is `special_per_view` special rows followed by the
+    grid_h x grid_w patch tokens in row-major order.  Windows tile the grid from the top left;
+    those on the right and bottom edges are cut where the grid ends (the paper leaves this
+    case open).  Returns a list over (view, window row, window column) of int64 arrays of
+    row numbers, each window's cells in row-major order."""
+    assert tokens_per_view == special_per_view + grid_h * grid_w
+    blocks = []
+    for view in range(views):
+        base = view * tokens_per_view + special_per_view
+        for y0 in range(0, grid_h, window):
+            for x0 in range(0, grid_w, window):
+                rows = [base + y * grid_w + x
+                        for y in range(y0, min(y0 + window, grid_h))
+                        for x in range(x0, min(x0 + window, grid_w))]
+                blocks.append(np.asarray(rows, dtype=np.int64))
+    return blocks
+
+
+def gsa_forward_blocks(q, k, v, blocks, topk_blocks: int, gate=None, scale=None, forced=None,
+                       idx_override=None) -> dict:
+    """The sparse two-branch path (eqs. 3-8) for pooling blocks given as explicit lists of rows
+    (any lengths >= 1), written out in numpy without any blocking: block means, S_guide,
+    softmax over the pooled keys, TopK (ties to the smaller index; `forced` blocks always taken
+    and out of the competition), per-row softmax over the tokens of the selected blocks, gated
+    merge.  Returns {"idx" [heads, n_blk, w], "o_comp" [heads, n_blk, d], "out", "o_sel"
+    [n_tok, heads, d] (rows outside every block are NaN), "s" [heads, n_blk, n_blk]}."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    n_tok, heads, d = q.shape
+    n_blk = len(blocks)
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(d)
+    qc = np.stack([q[b].mean(axis=0) for b in blocks], axis=1)          # [heads, n_blk, d]
+    kc = np.stack([k[b].mean(axis=0) for b in blocks], axis=1)
+    vc = np.stack([v[b].mean(axis=0) for b in blocks], axis=1)
+    s = np.einsum("hid,hjd->hij", qc, kc)                               # eq. 4
+    z = scale * s
+    p = np.exp(z - z.max(axis=2, keepdims=True))
+    o_comp = np.einsum("hij,hjd->hid", p / p.sum(axis=2, keepdims=True), vc)   # eq. 3
+    forced = np.asarray([] if forced is None else forced, dtype=np.int64)
+    k_dyn = min(int(topk_blocks), n_blk - forced.size)
+    idx = np.empty((heads, n_blk, forced.size + k_dyn), dtype=np.int32)
+    free = np.setdiff1d(np.arange(n_blk), forced)
+    for h in range(heads):
+        for i in range(n_blk):
+            order = sorted(free, key=lambda j: (-s[h, i, j], j))[:k_dyn]
+            idx[h, i] = np.sort(np.concatenate([forced, np.asarray(order, dtype=np.int64)]))
+    use = idx if idx_override is None else np.asarray(idx_override)
+    out = np.full((n_tok, heads, d), np.nan)
+    o_sel = np.full((n_tok, heads, d), np.nan)
+    for h in range(heads):
+        for i, rows in enumerate(blocks):
+            keys = np.concatenate([blocks[j] for j in use[h, i]])
+            logit = scale * (q[rows, h] @ k[keys, h].T)                  # eq. 6
+            w = np.exp(logit - logit.max(axis=1, keepdims=True))
+            o = (w / w.sum(axis=1, keepdims=True)) @ v[keys, h]
+            o_sel[rows, h] = o
+            g = 0.5 if gate is None else 1.0 / (1.0 + np.exp(-np.asarray(gate, dtype=np.float64)[rows, h]))
+            out[rows, h] = g * o_comp[h, i][None, :] + (1.0 - g) * o      # eqs. 5, 7, 8
+    return {"idx": idx, "o_comp": o_comp, "out": out, "o_sel": o_sel, "s": s}

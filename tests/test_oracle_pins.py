@@ -458,6 +458,49 @@ def test_layer_row_bookkeeping_closed_form(oracle):
         assert np.allclose(res["out"][t], want, atol=1e-12), t
 
 
+def test_window_blocks_tile_every_grid_cell_once(oracle):
+    blocks = oracle.window_blocks(3, 2 + 5 * 7, 2, 5, 7, 4)     # 5 x 7 grid, 4 x 4 windows: 2 x 2 windows per view
+    assert len(blocks) == 3 * 4
+    assert [len(b) for b in blocks[:4]] == [16, 12, 4, 3]        # full, right edge, bottom edge, corner
+    rows = np.concatenate(blocks)
+    want = [t for t in range(3 * 37) if t % 37 >= 2]
+    assert sorted(rows) == want and len(set(rows)) == len(rows)
+    # top-left window of view 1: rows 37 + 2 + y * 7 + x, y, x < 4
+    assert list(blocks[4]) == [39 + y * 7 + x for y in range(4) for x in range(4)]
+    # right-edge window keeps row-major order over its 3 columns
+    assert list(blocks[1][:4]) == [2 + 4, 2 + 5, 2 + 6, 2 + 7 + 4]
+    # a window that divides the grid gives equal blocks
+    assert {len(b) for b in oracle.window_blocks(2, 16, 0, 4, 4, 2)} == {4}
+
+
+def test_forward_blocks_agrees_with_the_blocked_route(oracle):
+    # The explicit-rows route (numpy, no blocking) and the C route on the same equal-length blocks.
+    n, h, d, b, kk = 70, 2, 8, 8, 3                               # ragged tail of 6
+    q, k, v = rnd((n, h, d), 60), rnd((n, h, d), 61), rnd((n, h, d), 62)
+    gate = rnd((n, h, d), 63)
+    blocks = [np.arange(j * b, min((j + 1) * b, n)) for j in range(9)]
+    for forced in (None, [0, 4]):
+        a = oracle.gsa_forward_blocks(q, k, v, blocks, kk, gate=gate, forced=forced)
+        c = oracle.gsa_forward(q, k, v, b, kk, gate=gate, forced=forced)
+        assert np.array_equal(a["idx"], c["idx"])
+        assert np.allclose(a["o_comp"], c["o_comp"], atol=1e-13)
+        assert np.allclose(a["out"], flat_tokens(oracle, c["out"], n, b), atol=1e-13)
+        assert np.allclose(a["o_sel"], flat_tokens(oracle, c["o_sel"], n, b), atol=1e-13)
+
+
+def test_forward_blocks_on_windows_closed_form(oracle):
+    # q = k = 0, v[t] = t: all softmaxes uniform, TopK takes the first blocks; on a 3 x 5 grid with
+    # 2 x 2 windows the first two windows of view 0 hold rows {0, 1, 5, 6} and {2, 3, 7, 8}.
+    blocks = oracle.window_blocks(2, 15, 0, 3, 5, 2)
+    z = np.zeros((30, 1, 4), dtype=np.float32)
+    v = np.tile(np.arange(30, dtype=np.float32)[:, None, None], (1, 1, 4))
+    res = oracle.gsa_forward_blocks(z, z, v, blocks, 2)
+    o_sel = np.mean([0, 1, 5, 6, 2, 3, 7, 8])
+    o_comp = np.mean([np.mean(b) for b in blocks])
+    assert np.allclose(res["out"], 0.5 * o_comp + 0.5 * o_sel, atol=1e-12)
+    assert np.array_equal(res["idx"][0], np.tile([0, 1], (len(blocks), 1)))
+
+
 def test_paper_sparse_ratios(oracle):
     """Table 2 prints 94 % (pi3 variant) and 84 % (VGGT variant, reference view always
     attended) at 10 views and top-32; counted on the selection stage both follow from
