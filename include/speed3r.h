@@ -85,6 +85,13 @@ typedef struct s3r_params {
      * tokens first is the paper's own [X_spec; X_img] arrangement. */
     int tokens_per_view;     /* 0, or a divisor of n_tok                                        */
     int special_per_view;    /* 0 <= special_per_view < tokens_per_view                         */
+    /* Spatial pooling windows (Sec. 3.2: non-overlapping s x s average pooling on each image's patch
+     * grid).  The tokens_per_view - special_per_view image rows of a view are a row-major grid_h x
+     * grid_w grid; blocks are its window x window windows (block must equal window * window), taken in
+     * row-major order over the grid, views one after another: n_blk = views * ceil(grid_h / window) *
+     * ceil(grid_w / window).  Windows on the right and bottom edges are cut where the grid ends and hold
+     * fewer tokens.  All 0: blocks are runs of `block` consecutive image rows. */
+    int grid_h, grid_w, window;
     int64_t n_tok;
     int heads, head_dim, block, topk;
     s3r_dtype dtype;
@@ -108,6 +115,10 @@ size_t speed3r_workspace_bytes(int64_t n_tok, int heads, int head_dim, int block
 /* The same from a filled-in parameter block (only its shape fields are read: n_tok, heads, head_dim,
  * block, topk, dtype, n_forced, tokens_per_view, special_per_view); needed with special tokens. */
 size_t speed3r_workspace_bytes_ex(const s3r_params *p);
+
+/* Number of blocks n_blk of the sequence the sparse path works on, for a filled-in parameter block
+ * (shape fields only); -1 on invalid arguments. */
+int64_t speed3r_num_blocks(const s3r_params *p);
 
 /* Key blocks each query block attends: n_forced + min(topk, n_blk - n_forced) (Sec. 3.3), or
  * min(topk, n_blk) without forced blocks; -1 on invalid arguments. */

@@ -342,7 +342,8 @@ def gsa_forward_blocks(q, k, v, blocks, topk_blocks: int, gate=None, scale=None,
     softmax over the pooled keys, TopK (ties to the smaller index; `forced` blocks always taken
     and out of the competition), per-row softmax over the tokens of the selected blocks, gated
     merge.  Returns {"idx" [heads, n_blk, w], "o_comp" [heads, n_blk, d], "out", "o_sel"
-    [n_tok, heads, d] (rows outside every block are NaN), "s" [heads, n_blk, n_blk]}."""
+    [n_tok, heads, d], "lse" [heads, n_tok] (rows outside every block are NaN),
+    "s" [heads, n_blk, n_blk]}."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
@@ -368,13 +369,16 @@ def gsa_forward_blocks(q, k, v, blocks, topk_blocks: int, gate=None, scale=None,
     use = idx if idx_override is None else np.asarray(idx_override)
     out = np.full((n_tok, heads, d), np.nan)
     o_sel = np.full((n_tok, heads, d), np.nan)
+    lse = np.full((heads, n_tok), np.nan)
     for h in range(heads):
         for i, rows in enumerate(blocks):
             keys = np.concatenate([blocks[j] for j in use[h, i]])
             logit = scale * (q[rows, h] @ k[keys, h].T)                  # eq. 6
-            w = np.exp(logit - logit.max(axis=1, keepdims=True))
+            mx = logit.max(axis=1, keepdims=True)
+            w = np.exp(logit - mx)
             o = (w / w.sum(axis=1, keepdims=True)) @ v[keys, h]
             o_sel[rows, h] = o
+            lse[h, rows] = mx[:, 0] + np.log(w.sum(axis=1))              # Alg. 2's L
             g = 0.5 if gate is None else 1.0 / (1.0 + np.exp(-np.asarray(gate, dtype=np.float64)[rows, h]))
             out[rows, h] = g * o_comp[h, i][None, :] + (1.0 - g) * o      # eqs. 5, 7, 8
-    return {"idx": idx, "o_comp": o_comp, "out": out, "o_sel": o_sel, "s": s}
+    return {"idx": idx, "o_comp": o_comp, "out": out, "o_sel": o_sel, "lse": lse, "s": s}

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ q, cons
     const int tid = threadIdx.x;
     const int c = tid & 7, r0 = tid >> 3;
     const int64_t t0 = j * B;
-    const int len = static_cast<int>((n_tok - t0 < B) ? (n_tok - t0) : B);
+    const int len = map.block_len(j, B, n_tok);
     const int64_t tile_base = (static_cast<int64_t>(h) * n_blk + j) * (B * 64);
 
     float acc[3][8];
@@ -126,6 +126,23 @@ static hipError_t run_pool(const void *q, const void *k, const void *v, float *q
                        stream, static_cast<const T *>(q), static_cast<const T *>(k),
                        static_cast<const T *>(v), qc, kc, vc, static_cast<bf16_t *>(kb),
                        static_cast<bf16_t *>(vb), n_tok, heads, n_blk, map);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void block_lens_kernel(TokenMap map, int block, int64_t n_tok, int64_t n_blk,
+                                                         int32_t *__restrict__ blk_len)
+{
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (j < n_blk) blk_len[j] = map.block_len(j, block, n_tok);
+}
+
+hipError_t launch_block_lens(TokenMap map, int block, int64_t n_tok, int64_t n_blk, int32_t *blk_len,
+                             hipStream_t stream)
+{
+    const int64_t grid = (n_blk + 255) / 256;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(block_lens_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0, stream, map, block, n_tok,
+                       n_blk, blk_len);
     return hipGetLastError();
 }
 

@@ -14,16 +14,51 @@ inline int64_t pooled_tiles_padded(int64_t n_blk) { return ((n_blk + 31) / 32 + 
 // in periods (views) of `period` rows; the sub-sequence takes the `count` consecutive rows that
 // start at row `first` of every period (image tokens: first = special tokens per view; special
 // tokens: first = 0).  period == 0 is the identity.  Sub-sequence indices must stay below 2^31.
+//
+// With win > 0 the `count` = grid_h * grid_w rows of a period are a row-major patch grid and the
+// sub-sequence is laid out in spatial windows of win x win cells (Sec. 3.2): block b of win * win
+// slots is window (b % nw) of view b / nw, windows in row-major order over the grid, the cells of
+// a window in row-major order; windows on the right and bottom edges are cut at the grid border
+// and fill only the first block_len slots of their block.
 struct TokenMap {
     int period = 0, first = 0, count = 0;
+    int win = 0, grid_h = 0, grid_w = 0, nwx = 0, nw = 0;
     __host__ __device__ int64_t row(int64_t t) const
     {
         if (period == 0) return t;
         const unsigned tt = static_cast<unsigned>(t);
-        const unsigned view = tt / static_cast<unsigned>(count);
-        return static_cast<int64_t>(view) * period + first + (tt - view * static_cast<unsigned>(count));
+        if (win == 0) {
+            const unsigned view = tt / static_cast<unsigned>(count);
+            return static_cast<int64_t>(view) * period + first + (tt - view * static_cast<unsigned>(count));
+        }
+        const unsigned slots = static_cast<unsigned>(win * win);
+        const unsigned blk = tt / slots, p = tt - blk * slots;
+        const unsigned view = blk / static_cast<unsigned>(nw), wid = blk - view * static_cast<unsigned>(nw);
+        const unsigned wy = wid / static_cast<unsigned>(nwx), wx = wid - wy * static_cast<unsigned>(nwx);
+        const unsigned left = static_cast<unsigned>(grid_w) - wx * win;
+        const unsigned cw = left < static_cast<unsigned>(win) ? left : static_cast<unsigned>(win);
+        const unsigned y = wy * win + p / cw, x = wx * win + p % cw;
+        return static_cast<int64_t>(view) * period + first + y * static_cast<unsigned>(grid_w) + x;
+    }
+    // Tokens of block `blk` of `block` slots in a sub-sequence of n_tok slots.
+    __host__ __device__ int block_len(int64_t blk, int block, int64_t n_tok) const
+    {
+        if (win == 0) {
+            const int64_t left = n_tok - blk * block;
+            return static_cast<int>(left < block ? left : block);
+        }
+        const unsigned wid = static_cast<unsigned>(blk) % static_cast<unsigned>(nw);
+        const unsigned wy = wid / static_cast<unsigned>(nwx), wx = wid - wy * static_cast<unsigned>(nwx);
+        const int ch = grid_h - static_cast<int>(wy) * win < win ? grid_h - static_cast<int>(wy) * win : win;
+        const int cw = grid_w - static_cast<int>(wx) * win < win ? grid_w - static_cast<int>(wx) * win : win;
+        return ch * cw;
     }
 };
+
+// blk_len[j] = map.block_len(j, block, n_tok) for every block (the table the attention kernels read
+// when blocks are spatial windows).
+hipError_t launch_block_lens(TokenMap map, int block, int64_t n_tok, int64_t n_blk, int32_t *blk_len,
+                             hipStream_t stream);
 
 // Block means of q, k, v (fp32 [heads][n_blk][64]; any of qc/kc/vc may be null together) and,
 // when kb/vb are given (bf16 input, block 64 or 128), the per-(head, block) K and V tiles in
@@ -101,6 +136,7 @@ struct SelectArgs {
     int64_t n_blk;             // key blocks = ceil(n_keys / block); also the query blocks when idx is given
     int64_t lse_stride;        // rows of the caller's tensors
     TokenMap qmap, kmap;
+    const int32_t *blk_len = nullptr;  // tokens per block of the kb/vb (or kmap) sequence; null: full blocks and a short last one
     int heads, block, kk;
     float scale;
     bool is_bf16;

@@ -18,7 +18,7 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
                                       T *__restrict__ out, T *__restrict__ o_sel, float *__restrict__ lse,
                                       int64_t n_tok, int64_t n_qblk, int64_t n_keys, int heads, int block,
                                       int kk, float scale_log2, TokenMap qmap, TokenMap kmap,
-                                      int64_t lse_stride)
+                                      int64_t lse_stride, const int32_t *__restrict__ blk_len)
 {
     __shared__ __attribute__((aligned(16))) float ks[kChunk][64];
     __shared__ __attribute__((aligned(16))) float vs[kChunk][64];
@@ -28,7 +28,9 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
     const int64_t i = bid / heads;
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int64_t t = i * block + tid;
-    const bool active = tid < block && t < n_tok;
+    // blk_len (spatial windows) describes the key blocks; it applies to the query blocks too when
+    // the queries are the same sequence (selection: idx given)
+    const bool active = tid < block && t < n_tok && (blk_len == nullptr || idx == nullptr || tid < blk_len[i]);
     const int64_t trow = qmap.row(active ? t : 0);  // the caller's row of this query
     const int64_t n_kblk = (n_keys + block - 1) / block;
 
@@ -46,7 +48,7 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
     for (int64_t a = 0; a < n_sel; ++a) {
         const int64_t j = (sel != nullptr) ? sel[a] : a;
         const int64_t u0 = j * block;
-        const int len = static_cast<int>((n_keys - u0 < block) ? (n_keys - u0) : block);
+        const int len = (blk_len != nullptr) ? blk_len[j] : static_cast<int>((n_keys - u0 < block) ? (n_keys - u0) : block);
         for (int c0 = 0; c0 < len; c0 += kChunk) {
             const int nk = (len - c0 < kChunk) ? (len - c0) : kChunk;
             __syncthreads();
@@ -134,14 +136,14 @@ hipError_t launch_select_generic(const SelectArgs &a, hipStream_t stream)
                            static_cast<const bf16_t *>(a.v), a.idx, a.o_comp,
                            static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
                            static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, n_qblk, a.n_keys, a.heads,
-                           a.block, a.kk, scale_log2, a.qmap, a.kmap, a.lse_stride);
+                           a.block, a.kk, scale_log2, a.qmap, a.kmap, a.lse_stride, a.blk_len);
     } else {
         hipLaunchKernelGGL(select_generic_kernel<float>, dim3(static_cast<unsigned>(grid)), dim3(threads),
                            0, stream, static_cast<const float *>(a.q), static_cast<const float *>(a.k),
                            static_cast<const float *>(a.v), a.idx, a.o_comp,
                            static_cast<const float *>(a.gate), static_cast<float *>(a.out),
                            static_cast<float *>(a.o_sel), a.lse, a.n_tok, n_qblk, a.n_keys, a.heads, a.block,
-                           a.kk, scale_log2, a.qmap, a.kmap, a.lse_stride);
+                           a.kk, scale_log2, a.qmap, a.kmap, a.lse_stride, a.blk_len);
     }
     return hipGetLastError();
 }

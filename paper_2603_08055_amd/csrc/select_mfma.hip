@@ -74,7 +74,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     bf16_t *__restrict__ out, bf16_t *__restrict__ o_sel, float *__restrict__ lse, int64_t n_tok,
     int64_t n_blk, int heads, int block, int kk, float scale_log2, int64_t set_offset, int64_t n_sets,
     int map_mode, TokenMap qmap, int64_t n_keys, int64_t lse_stride, const bf16_t *__restrict__ kb2,
-    const bf16_t *__restrict__ vb2, int64_t n_keys2)
+    const bf16_t *__restrict__ vb2, int64_t n_keys2, const int32_t *__restrict__ blk_len)
 {
     constexpr int NW = QW;             // waves per workgroup
     constexpr int CPW = 16 / NW;       // 1 KiB chunks of a unit (8 K + 8 V) issued by each wave
@@ -104,7 +104,8 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const int upb = block / kUnitKeys;  // units per key block (1 or 2)
     const int64_t qgroup = set;
     const int64_t t = qgroup * (32 * QW) + wave * 32 + (lane & 31);
-    const bool row_valid = t < n_tok;
+    bool row_valid = t < n_tok;
+    if (!DENSE && blk_len != nullptr) row_valid = wave * 32 + (lane & 31) < blk_len[qgroup];  // spatial windows
     const int64_t trow = qmap.row(row_valid ? t : 0);  // the caller's row of this query
     const int64_t n_units1 = (n_keys + kUnitKeys - 1) / kUnitKeys;     // units of the first key segment
     const int64_t n_units2 = (n_keys2 + kUnitKeys - 1) / kUnitKeys;    // dense only: second segment
@@ -173,7 +174,10 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         if (s + D < n_steps) issue(s + D);
 
         const int64_t w = unit_of(s);
-        const int64_t left = (DENSE && w >= n_units1) ? n_keys2 - (w - n_units1) * kUnitKeys : n_keys - w * kUnitKeys;
+        int64_t left;
+        if (DENSE && w >= n_units1) left = n_keys2 - (w - n_units1) * kUnitKeys;
+        else if (blk_len != nullptr) left = blk_len[w / upb] - (w % upb) * kUnitKeys;  // wave-uniform load
+        else left = n_keys - w * kUnitKeys;
         const int valid = static_cast<int>(left < kUnitKeys ? left : kUnitKeys);
         if (valid <= 0) continue;  // second half of a short last block
 
@@ -300,7 +304,8 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
                            a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
                            static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.block,
                            a.kk, a.scale * kLog2e, s0, ns, map_mode, a.qmap, a.n_keys, a.lse_stride,
-                           static_cast<const bf16_t *>(a.kb2), static_cast<const bf16_t *>(a.vb2), a.n_keys2);
+                           static_cast<const bf16_t *>(a.kb2), static_cast<const bf16_t *>(a.vb2), a.n_keys2,
+                           a.blk_len);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

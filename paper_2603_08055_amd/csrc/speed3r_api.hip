@@ -67,7 +67,7 @@ struct Layout {
     int width;   // blocks attended per row: kk + n_forced
     int head_chunk;
     size_t qc, kc, vc, oc, tile[6], idx, idx_merged, forced_clean, forced_words, s, kb, vb, kb_spec, vb_spec;
-    size_t thr, cand, cand_count, overflow, total;
+    size_t thr, cand, cand_count, overflow, blk_len, total;
 };
 
 // n_tok: tokens on the sparse path (the image tokens); n_spec: special tokens (dense rows).
@@ -111,6 +111,7 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, 
     L.cand = take(chunk_rows * 2 * kCandCap * sizeof(int32_t));
     L.cand_count = take(chunk_rows * 2 * sizeof(int));
     L.overflow = take(sizeof(int));
+    L.blk_len = take(static_cast<size_t>(L.n_blk) * sizeof(int32_t));
     L.total = off;
     return L;
 }
@@ -258,15 +259,30 @@ s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, 
 // Special / image token split of a sequence of `n_tok` rows in views of `period` rows whose first
 // `special` rows are special tokens (0, 0: no special tokens).
 struct Split {
-    int64_t n_img, n_spec;
+    int64_t n_img;   // slots of the sequence the sparse path works on (with windows: n_blk * block, edge
+                     // windows leaving slots empty)
+    int64_t n_spec;
+    bool windows;
     s3r::TokenMap img, spec;
 };
 
-s3r_status make_split(int64_t n_tok, int period, int special, Split *out)
+s3r_status make_split(int64_t n_tok, int period, int special, int grid_h, int grid_w, int window, int block,
+                      Split *out)
 {
     Split sp{};
     sp.n_img = n_tok;
     sp.n_spec = 0;
+    sp.windows = false;
+    if (window != 0 || grid_h != 0 || grid_w != 0) {
+        if (window <= 0 || grid_h <= 0 || grid_w <= 0)
+            return fail(S3R_ERR_INVALID_ARG, "window (%d), grid_h (%d) and grid_w (%d) must all be positive or all 0",
+                        window, grid_h, grid_w);
+        if (window * window != block)
+            return fail(S3R_ERR_INVALID_ARG, "block (%d) must equal window * window (%d)", block, window * window);
+        if (period <= 0 || special < 0 || period - special != grid_h * grid_w)
+            return fail(S3R_ERR_INVALID_ARG, "tokens_per_view (%d) must equal special_per_view (%d) + grid_h * grid_w (%d)",
+                        period, special, grid_h * grid_w);
+    }
     if (period == 0 && special == 0) { *out = sp; return S3R_OK; }
     if (period <= 0 || special < 0 || special >= period)
         return fail(S3R_ERR_INVALID_ARG, "special_per_view (%d) must lie in [0, tokens_per_view = %d)", special, period);
@@ -274,12 +290,20 @@ s3r_status make_split(int64_t n_tok, int period, int special, Split *out)
         return fail(S3R_ERR_INVALID_ARG, "n_tok (%lld) is not a multiple of tokens_per_view (%d)",
                     static_cast<long long>(n_tok), period);
     if (n_tok > 0x7fffffffLL) return fail(S3R_ERR_UNSUPPORTED, "n_tok exceeds 2^31 - 1 with special tokens");
-    if (special == 0) { *out = sp; return S3R_OK; }
+    if (special == 0 && window == 0) { *out = sp; return S3R_OK; }
     const int64_t views = n_tok / period;
     sp.n_spec = views * special;
     sp.n_img = n_tok - sp.n_spec;
     sp.img.period = period; sp.img.first = special; sp.img.count = period - special;
     sp.spec.period = period; sp.spec.first = 0; sp.spec.count = special;
+    if (window != 0) {
+        sp.windows = true;
+        sp.img.win = window; sp.img.grid_h = grid_h; sp.img.grid_w = grid_w;
+        sp.img.nwx = (grid_w + window - 1) / window;
+        sp.img.nw = sp.img.nwx * ((grid_h + window - 1) / window);
+        sp.n_img = views * sp.img.nw * block;
+        if (sp.n_img > 0x7fffffffLL) return fail(S3R_ERR_UNSUPPORTED, "windowed sequence exceeds 2^31 - 1 slots");
+    }
     *out = sp;
     return S3R_OK;
 }
@@ -354,12 +378,25 @@ size_t speed3r_workspace_bytes_ex(const s3r_params *p)
     if (!p) { fail(S3R_ERR_INVALID_ARG, "params is null"); return 0; }
     if (check_shape(p->n_tok, p->heads, p->head_dim, p->block, p->topk, p->dtype) != S3R_OK) return 0;
     Split sp{};
-    if (make_split(p->n_tok, p->tokens_per_view, p->special_per_view, &sp) != S3R_OK) return 0;
+    if (make_split(p->n_tok, p->tokens_per_view, p->special_per_view, p->grid_h, p->grid_w, p->window, p->block,
+                   &sp) != S3R_OK)
+        return 0;
     if (p->n_forced < 0 || p->n_forced > (sp.n_img + p->block - 1) / p->block) {
         fail(S3R_ERR_INVALID_ARG, "n_forced (%d) must lie in [0, n_blk]", p->n_forced);
         return 0;
     }
     return make_layout(sp.n_img, p->heads, p->block, p->topk, p->n_forced, p->dtype, sp.n_spec).total;
+}
+
+int64_t speed3r_num_blocks(const s3r_params *p)
+{
+    if (!p) { fail(S3R_ERR_INVALID_ARG, "params is null"); return -1; }
+    if (check_shape(p->n_tok, p->heads, p->head_dim, p->block, p->topk, p->dtype) != S3R_OK) return -1;
+    Split sp{};
+    if (make_split(p->n_tok, p->tokens_per_view, p->special_per_view, p->grid_h, p->grid_w, p->window, p->block,
+                   &sp) != S3R_OK)
+        return -1;
+    return (sp.n_img + p->block - 1) / p->block;
 }
 
 int speed3r_selected_per_row(int64_t n_tok, int block, int topk, int n_forced)
@@ -386,7 +423,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     if (p->n_forced < 0 || (p->n_forced > 0 && !p->forced_blocks) || (p->forced_blocks && p->n_forced == 0))
         return fail(S3R_ERR_INVALID_ARG, "forced_blocks and n_forced (%d) must be given together", p->n_forced);
     Split sp{};
-    st = make_split(p->n_tok, p->tokens_per_view, p->special_per_view, &sp);
+    st = make_split(p->n_tok, p->tokens_per_view, p->special_per_view, p->grid_h, p->grid_w, p->window, p->block, &sp);
     if (st != S3R_OK) return st;
     if (n_forced > (sp.n_img + p->block - 1) / p->block)
         return fail(S3R_ERR_INVALID_ARG, "n_forced (%d) exceeds the number of blocks", n_forced);
@@ -418,8 +455,13 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     void *kb = mfma ? at(ws, L.kb) : nullptr;
     void *vb = mfma ? at(ws, L.vb) : nullptr;
 
+    int32_t *blk_len = nullptr;
     {
         StageTimer tm(S3R_STAGE_POOL, stream);
+        if (sp.windows) {
+            blk_len = reinterpret_cast<int32_t *>(at(ws, L.blk_len));
+            S3R_HIP(s3r::launch_block_lens(sp.img, p->block, sp.n_img, L.n_blk, blk_len, stream), "block length kernel launch");
+        }
         S3R_HIP(s3r::launch_pool(p->q, p->k, p->v, qc, kc, vc, kb, vb, sp.n_img, p->heads, p->block, is_bf16,
                                  sp.img, stream),
                 "pool kernel launch");
@@ -448,7 +490,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     a.q = p->q; a.k = p->k; a.v = p->v; a.kb = kb; a.vb = vb; a.idx = idx_sel; a.o_comp = oc;
     a.gate = p->gate_logits; a.out = p->out; a.o_sel = p->o_sel; a.lse = p->lse_sel;
     a.n_tok = sp.n_img; a.n_keys = sp.n_img; a.n_blk = L.n_blk; a.lse_stride = p->n_tok;
-    a.qmap = sp.img; a.kmap = sp.img;
+    a.qmap = sp.img; a.kmap = sp.img; a.blk_len = blk_len;
     a.heads = p->heads; a.block = p->block; a.kk = L.width;
     a.scale = scale; a.is_bf16 = is_bf16;
     {
@@ -472,6 +514,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
                         "pool kernel launch (special tokens)");
             }
             d.kb = kb; d.vb = vb; d.n_keys = sp.n_img; d.n_blk = L.n_blk;      // image keys, then special keys
+            d.blk_len = blk_len;
             d.kb2 = kb_s; d.vb2 = vb_s; d.n_keys2 = sp.n_spec;
         } else {
             d.n_keys = p->n_tok; d.n_blk = (p->n_tok + p->block - 1) / p->block;  // every row, in place

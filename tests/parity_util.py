@@ -90,15 +90,15 @@ def to_host_f32(t: torch.Tensor) -> np.ndarray:
 
 
 def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "lse", "o_comp", "o_sel"),
-               forced=None, tokens_per_view=0, special_per_view=0):
+               forced=None, tokens_per_view=0, special_per_view=0, grid=None):
     """One call of the whole path through the C ABI; returns device tensors.  `forced`: ascending
     block indices (host array) every query block attends besides its TopK.  With special tokens
     the block-level outputs are sized for the image-only sequence."""
     n_tok, heads, d = q.shape
-    n_img = n_tok - (n_tok // tokens_per_view) * special_per_view if special_per_view else n_tok
-    n_blk = (n_img + block - 1) // block
     n_forced = 0 if forced is None else len(forced)
-    kk = s3r.speed3r_selected_per_row(n_img, block, topk, n_forced)
+    dt_code = s3r.S3R_BF16 if q.dtype == torch.bfloat16 else s3r.S3R_F32
+    n_blk = s3r.speed3r_num_blocks(n_tok, heads, d, block, topk, dt_code, tokens_per_view, special_per_view, grid)
+    kk = s3r.speed3r_selected_per_row(n_blk * block, block, topk, n_forced)
     dev = q.device
     out = torch.full_like(q, float("nan"))
     bufs = {}
@@ -113,7 +113,8 @@ def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "ls
     forced_t = None if n_forced == 0 else torch.from_numpy(np.asarray(forced, dtype=np.int32)).to(dev)
     s3r.speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, gate_logits=gate,
                                       softmax_scale=scale, forced_blocks=forced_t,
-                                      tokens_per_view=tokens_per_view, special_per_view=special_per_view, **bufs)
+                                      tokens_per_view=tokens_per_view, special_per_view=special_per_view,
+                                      grid=grid, **bufs)
     torch.cuda.synchronize()
     res = {"out": out}
     res.update({"idx": bufs.get("topk_idx"), "lse": bufs.get("lse_sel"),
@@ -210,4 +211,46 @@ def compare_layer_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, 
         ref = oracle.dense_attn(qf, kf, vf, 1.0 / math.sqrt(qf.shape[2]), q_tok=pick)
         got = to_host_f32(dev_res["out"].index_select(0, torch.from_numpy(pick).to(dev_res["out"].device)))
         stats["o_spec"] = assert_close(got, ref, TOL[dtype], f"{label} special rows")
+    return stats
+
+
+def compare_windows_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, topk, dtype, views, tokens_per_view,
+                                special_per_view, grid, forced=None, label=""):
+    """Blocks = spatial windows: everything against the oracle's explicit-rows route (all rows; sizes
+    are kept small), special rows against its dense attention."""
+    grid_h, grid_w, window = grid
+    tol = TOL[dtype]
+    blocks = oracle.window_blocks(views, tokens_per_view, special_per_view, grid_h, grid_w, window)
+    ref = oracle.gsa_forward_blocks(qf, kf, vf, blocks, topk, gate=gate_f, forced=forced)
+    gidx = dev_res["idx"].cpu().numpy()
+    n_blk = len(blocks)
+    stats = {}
+    if forced is None or len(forced) == 0:
+        stats["topk_exact"], stats["topk_tie_resolved"] = check_topk_sets(ref["s"], gidx, min(topk, n_blk))
+    else:
+        forced = np.asarray(forced, dtype=np.int64)
+        is_forced = np.isin(gidx, forced)
+        assert np.all(is_forced.sum(axis=2) == forced.size)
+        k_dyn = min(topk, n_blk - forced.size)
+        s_free = ref["s"].copy()
+        s_free[:, :, forced] = -np.inf
+        dyn = gidx[~is_forced].reshape(gidx.shape[0], gidx.shape[1], k_dyn)
+        stats["topk_exact"], stats["topk_tie_resolved"] = check_topk_sets(s_free, dyn, k_dyn)
+    if stats["topk_tie_resolved"]:
+        ref = oracle.gsa_forward_blocks(qf, kf, vf, blocks, topk, gate=gate_f, forced=forced, idx_override=gidx)
+    img_rows = np.concatenate(blocks)
+    stats["o_comp"] = assert_close(dev_res["o_comp"].cpu().numpy(), ref["o_comp"], tol, f"{label} o_comp")
+    take = torch.from_numpy(img_rows).to(dev_res["out"].device)
+    stats["o_sel"] = assert_close(to_host_f32(dev_res["o_sel"].index_select(0, take)), ref["o_sel"][img_rows], tol,
+                                  f"{label} o_sel")
+    stats["out"] = assert_close(to_host_f32(dev_res["out"].index_select(0, take)), ref["out"][img_rows], tol,
+                                f"{label} out")
+    err = float(np.max(np.abs(dev_res["lse"].index_select(1, take).cpu().numpy() - ref["lse"][:, img_rows])))
+    assert err <= tol, f"{label} lse abs err {err:.3e}"
+    stats["lse_abs"] = err
+    spec_rows, _ = oracle.token_partition(qf.shape[0], tokens_per_view, special_per_view)
+    if spec_rows.size:
+        dense = oracle.dense_attn(qf, kf, vf, 1.0 / math.sqrt(qf.shape[2]), q_tok=spec_rows)
+        got = to_host_f32(dev_res["out"].index_select(0, torch.from_numpy(spec_rows).to(dev_res["out"].device)))
+        stats["o_spec"] = assert_close(got, dense, tol, f"{label} special rows")
     return stats

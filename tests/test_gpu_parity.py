@@ -7,7 +7,8 @@ import pytest
 import torch
 
 from paper_2603_08055_amd import workloads
-from tests.parity_util import (TOL, assert_close, check_topk_sets, compare_layer_with_oracle, compare_with_oracle, log,
+from tests.parity_util import (TOL, assert_close, check_topk_sets, compare_layer_with_oracle, compare_windows_with_oracle,
+                               compare_with_oracle, log,
                                rel_errors, run_device, to_host_f32)
 
 pytestmark = pytest.mark.gpu
@@ -447,6 +448,51 @@ def test_special_tokens_untouched_outputs_and_zero_special(s3r):
     assert torch.isnan(res["o_sel"][spec].float()).all() and torch.isnan(res["lse"][:, spec]).all()
     assert torch.isfinite(res["out"].float()).all()
     assert torch.isfinite(res["o_sel"][~spec].float()).all() and torch.isfinite(res["lse"][:, ~spec]).all()
+
+
+# ------------------------------------------ spatial pooling windows on the patch grid (Sec. 3.2) --
+
+@pytest.mark.parametrize("dtype,views,special,grid_h,grid_w,window,topk,forced", [
+    ("bf16", 3, 5, 37, 37, 8, 6, None),        # the VGGT grid: 5 x 5 windows per view, edge windows of 5 columns / rows
+    ("bf16", 2, 0, 37, 37, 8, 4, None),        # the pi3 layout: no special tokens
+    ("bf16", 4, 1, 16, 24, 8, 3, None),        # windows divide the grid: every block full
+    ("bf16", 2, 5, 37, 37, 8, 5, [0, 4, 24]),  # forced windows incl. the corner one of view 0
+    ("f32", 2, 2, 9, 10, 4, 3, None),          # 4 x 4 windows (block 16): generic kernels
+    ("f32", 3, 0, 8, 8, 4, 2, [1]),
+    ("bf16", 2, 3, 11, 13, 4, 4, None),        # block 16 in bf16: generic kernels
+    ("bf16", 1, 0, 5, 5, 8, 1, None),          # a single cut window
+])
+def test_spatial_windows(s3r, oracle, dtype, views, special, grid_h, grid_w, window, topk, forced):
+    tpv = special + grid_h * grid_w
+    wl = workloads.Workload(f"windows_{dtype}_{views}x{grid_h}x{grid_w}_w{window}", views, tpv, 2, 64, dtype,
+                            window * window, topk, 96, "normal")
+    q, k, v = workloads.make_inputs(wl)
+    gate = workloads.make_gate_logits(wl)
+    grid = (grid_h, grid_w, window)
+    forced_a = None if forced is None else np.asarray(forced, dtype=np.int32)
+    res = run_device(s3r, q.cuda(), k.cuda(), v.cuda(), wl.block, topk, gate=gate.cuda(), forced=forced_a,
+                     tokens_per_view=tpv, special_per_view=special, grid=grid)
+    stats = compare_windows_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v),
+                                        to_host_f32(gate), topk, dtype, views, tpv, special, grid, forced=forced_a,
+                                        label=wl.name)
+    log(f"{wl.name}: {stats}")
+
+
+def test_spatial_windows_equal_plain_path_on_permuted_tokens(s3r, oracle):
+    """When the windows divide the grid, the windowed call on the original token order and the
+    plain blocked call on the tokens gathered into window-major order are the same computation:
+    bit-identical results, row for row."""
+    views, gh, gw, win = 3, 16, 24, 8
+    wl = workloads.Workload("windows_vs_permuted", views, gh * gw, 2, 64, "bf16", 64, 4, 97, "normal")
+    q, k, v = (t.cuda() for t in workloads.make_inputs(wl))
+    gate = workloads.make_gate_logits(wl).cuda()
+    perm = torch.from_numpy(np.concatenate(oracle.window_blocks(views, gh * gw, 0, gh, gw, win))).cuda()
+    a = run_device(s3r, q, k, v, 64, 4, gate=gate, tokens_per_view=gh * gw, special_per_view=0, grid=(gh, gw, win))
+    b = run_device(s3r, q[perm].contiguous(), k[perm].contiguous(), v[perm].contiguous(), 64, 4,
+                   gate=gate[perm].contiguous())
+    assert torch.equal(a["idx"], b["idx"]) and torch.equal(a["o_comp"], b["o_comp"])
+    assert torch.equal(a["out"][perm], b["out"]) and torch.equal(a["o_sel"][perm], b["o_sel"])
+    assert torch.equal(a["lse"][:, perm], b["lse"])
 
 
 @pytest.mark.parametrize("n_tok,block,topk,dtype", [(1, 64, 4, "bf16"), (63, 64, 1, "bf16"), (65, 64, 2, "bf16"),

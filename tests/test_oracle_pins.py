@@ -486,6 +486,7 @@ def test_forward_blocks_agrees_with_the_blocked_route(oracle):
         assert np.allclose(a["o_comp"], c["o_comp"], atol=1e-13)
         assert np.allclose(a["out"], flat_tokens(oracle, c["out"], n, b), atol=1e-13)
         assert np.allclose(a["o_sel"], flat_tokens(oracle, c["o_sel"], n, b), atol=1e-13)
+        assert np.allclose(a["lse"].T, flat_tokens(oracle, c["lse"].transpose(1, 2, 0), n, b), atol=1e-13)
 
 
 def test_forward_blocks_on_windows_closed_form(oracle):
