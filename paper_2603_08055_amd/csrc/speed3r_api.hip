@@ -43,7 +43,7 @@ int g_kernel_choice = 0;  // 0 auto, 1 generic attention kernels only, 2 TopK fr
 
 bool mfma_ok(s3r_dtype dtype, int block) { return g_kernel_choice != 1 && dtype == S3R_BF16 && (block == 64 || block == 128); }
 
-constexpr int kCandCap = 512;  // candidate slots per list of the TopK-in-the-sweep path (two lists per row)
+constexpr int kCandCap = 256;  // candidate slots per list of the TopK-in-the-sweep path (two lists per row)
 
 s3r_status check_shape(int64_t n_tok, int heads, int head_dim, int block, int topk, int dtype)
 {

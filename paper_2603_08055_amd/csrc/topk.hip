@@ -332,7 +332,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(const float *
 // does not depend on how the filter computed its own copy beyond which keys became candidates.
 // Ties go to the smaller index; output ascending.  Requires k <= 64 and at most 2 * cap <= 2048
 // candidates (lists that were cut are read up to cap: the caller redoes such launches).
-constexpr int kCandSlots = 32;  // candidates per lane
+constexpr int kCandSlots = 8;  // candidates per lane (at most 2 * cap = 512 per row)
 __global__ __launch_bounds__(64) void topk_candidates_kernel(const float *__restrict__ qc, const float *__restrict__ kc,
                                                             const int32_t *__restrict__ cand,
                                                             const int *__restrict__ cand_count, int cap,
