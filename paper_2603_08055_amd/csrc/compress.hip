@@ -104,7 +104,7 @@ __device__ __forceinline__ void compress_block(
     const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = by;
-    const int64_t n_kt = (n_blk + 63) / 64;
+    const int n_kt = static_cast<int>((n_blk + 63) / 64);  // 64-key steps (n_blk < 2^31)
     if constexpr (MODE == kThreshold) {
         if (bx == 0 && by == 0 && tid == 0) *ft.overflow = 0;  // the filter launch comes later in the stream
     }
@@ -118,22 +118,24 @@ __device__ __forceinline__ void compress_block(
         if constexpr (NARR >= 3) src[2] = vt_hi + head_tiles * kRowTileElems;
         if constexpr (NARR == 4) src[3] = vt_lo + head_tiles * kRowTileElems;
         const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
-        auto issue = [&](int64_t kt) {
-            const unsigned stage_byte = ring_base + static_cast<unsigned>(kt % NS) * (NARR * STAGE_ELEMS * 2);
+        auto issue = [&](int kt, int stage) {
+            const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (NARR * STAGE_ELEMS * 2);
 #pragma unroll
             for (int a = 0; a < NARR; ++a)
 #pragma unroll
                 for (int c = 0; c < 8; ++c)
-                    compress_lds_dma_16(src[a] + kt * STAGE_ELEMS + c * 512 + lane * 8,
+                    compress_lds_dma_16(src[a] + static_cast<int64_t>(kt) * STAGE_ELEMS + c * 512 + lane * 8,
                                         __builtin_amdgcn_readfirstlane(stage_byte + (a * 8 + c) * 1024));
         };
-        for (int64_t kt = 0; kt < D && kt < n_kt; ++kt) issue(kt);
-        for (int64_t kt = 0; kt < n_kt; ++kt) {
+        for (int kt = 0; kt < D && kt < n_kt; ++kt) issue(kt, kt);  // D < NS: stage = kt
+        int stage_ahead = D - 1;  // stage of step kt + D, stepped at the loop head
+        for (int kt = 0; kt < n_kt; ++kt) {
+            stage_ahead = (stage_ahead + 1 == NS) ? 0 : stage_ahead + 1;
             // step kt landed (loads return in order), tell everybody; the barrier also says the
             // compute waves are done with step kt - 1, whose stage the next request overwrites
             if (kt + D <= n_kt) compress_wait_vmcnt<CPS *(D - 1)>(); else compress_wait_vmcnt<0>();
             lds_barrier();
-            if (kt + D < n_kt) issue(kt + D);
+            if (kt + D < n_kt) issue(kt + D, stage_ahead);
         }
         return;
     }
@@ -170,11 +172,13 @@ __device__ __forceinline__ void compress_block(
                 }
             }
         }
-        for (int64_t kt = 0; kt < n_kt; ++kt) {
+        int stage = NS - 1;
+        for (int kt = 0; kt < n_kt; ++kt) {
+            stage = (stage + 1 == NS) ? 0 : stage + 1;
             lds_barrier();
             if (!wave_active) continue;
-            const bf16_t *k_hi = &ring[kt % NS][0][0];
-            const bf16_t *k_lo = &ring[kt % NS][1][0];
+            const bf16_t *k_hi = &ring[stage][0][0];
+            const bf16_t *k_lo = &ring[stage][1][0];
             const unsigned long long fw = (forced_words != nullptr) ? forced_words[kt] : 0ull;  // wave-uniform
             floatx16 sacc[QT][2];
 #pragma unroll
@@ -267,11 +271,13 @@ __device__ __forceinline__ void compress_block(
             for (int i = 0; i < 16; ++i) bmax[par][i] = half2_t{-INFINITY, -INFINITY};
     }
 
-    for (int64_t kt = 0; kt < n_kt; ++kt) {
+    int stage = NS - 1;
+    for (int kt = 0; kt < n_kt; ++kt) {
+        stage = (stage + 1 == NS) ? 0 : stage + 1;
         lds_barrier();
         if (!wave_active) continue;
-        const bf16_t *k_hi = &ring[kt % NS][0][0];
-        const bf16_t *k_lo = &ring[kt % NS][1][0];
+        const bf16_t *k_hi = &ring[stage][0][0];
+        const bf16_t *k_lo = &ring[stage][1][0];
 
         floatx16 sacc[2];
 #pragma unroll
@@ -343,8 +349,8 @@ __device__ __forceinline__ void compress_block(
             };
             if (kt & 1) raise(bmax[1]); else raise(bmax[0]);  // wave-uniform
         }
-        const bf16_t *v_hi = &ring[kt % NS][NARR >= 3 ? 2 : 0][0];
-        const bf16_t *v_lo = &ring[kt % NS][NARR - 1][0];
+        const bf16_t *v_hi = &ring[stage][NARR >= 3 ? 2 : 0][0];
+        const bf16_t *v_lo = &ring[stage][NARR - 1][0];
         // online softmax (eq. 3), base-2 exponent with the scale folded in
         float mx = sacc[0][0];
 #pragma unroll

@@ -101,7 +101,8 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         }
         set += set_offset;
     }
-    const int upb = block / kUnitKeys;  // units per key block (1 or 2)
+    const int upb_shift = block / kUnitKeys - 1;  // units per key block: 1 or 2, as a shift
+    const int upb_mask = (1 << upb_shift) - 1;
     const int64_t qgroup = set;
     const int64_t t = qgroup * (32 * QW) + wave * 32 + (lane & 31);
     bool row_valid = t < n_tok;
@@ -122,13 +123,13 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     }
 
     // ---- the list of key blocks this workgroup visits ---------------------------------------
-    int64_t n_steps;  // units to process
+    int n_steps;  // units to process (host side keeps this below 2^31)
     const int32_t *sel = nullptr;
     if constexpr (DENSE) {
-        n_steps = n_units1 + n_units2;
+        n_steps = static_cast<int>(n_units1 + n_units2);
     } else {
         sel = idx + (static_cast<int64_t>(h) * n_blk + qgroup) * kk;
-        n_steps = static_cast<int64_t>(kk) * upb;
+        n_steps = kk << upb_shift;
     }
 
     const bf16_t *kb_h = kb + static_cast<int64_t>(h) * n_blk * block * 64;
@@ -137,14 +138,14 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const bf16_t *vb2_h = DENSE ? vb2 + static_cast<int64_t>(h) * n_units2 * kUnitElems : nullptr;
     const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0]));
 
-    // step s -> key unit (global unit index)
-    auto unit_of = [&](int64_t s) -> int64_t {
+    // step s -> key unit (global unit index); 32-bit arithmetic: these run once per step on the scalar unit
+    auto unit_of = [&](int s) -> int {
         if constexpr (DENSE) return s;
-        else return static_cast<int64_t>(sel[s / upb]) * upb + s % upb;
+        else return (sel[s >> upb_shift] << upb_shift) + (s & upb_mask);
     };
-    auto issue = [&](int64_t s) {  // this wave's share of unit s -> stage s % NS
+    auto issue = [&](int s, int stage) {  // this wave's share of unit s -> LDS stage `stage`
         const int64_t w = unit_of(s);
-        const unsigned stage_byte = ring_base + static_cast<unsigned>(s % NS) * (2 * kUnitElems * 2);
+        const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (2 * kUnitElems * 2);
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
             const int chunk = wave * CPW + c;  // 0..7: K, 8..15: V
@@ -164,25 +165,28 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
     float m_run = -1e30f, l_run = 0.f;
 
-    for (int64_t s = 0; s < D && s < n_steps; ++s) issue(s);
+    for (int s = 0; s < D && s < n_steps; ++s) issue(s, s);  // D < NS: stage = s
 
-    for (int64_t s = 0; s < n_steps; ++s) {
+    int stage = NS - 1, stage_ahead = D - 1;  // stages of unit s and of unit s + D, stepped at the loop head
+    for (int s = 0; s < n_steps; ++s) {
+        stage = (stage + 1 == NS) ? 0 : stage + 1;
+        stage_ahead = (stage_ahead + 1 == NS) ? 0 : stage_ahead + 1;
         // unit s: this wave's loads done, then everybody's (barrier); the barrier also says every wave
         // has finished unit s - 1, whose stage the next request overwrites
         if (s + D <= n_steps) wait_vmcnt<CPW *(D - 1)>(); else wait_vmcnt<0>();
         lds_barrier();
-        if (s + D < n_steps) issue(s + D);
+        if (s + D < n_steps) issue(s + D, stage_ahead);
 
         const int64_t w = unit_of(s);
         int64_t left;
         if (DENSE && w >= n_units1) left = n_keys2 - (w - n_units1) * kUnitKeys;
-        else if (blk_len != nullptr) left = blk_len[w / upb] - (w % upb) * kUnitKeys;  // wave-uniform load
+        else if (blk_len != nullptr) left = blk_len[w >> upb_shift] - (static_cast<int>(w) & upb_mask) * kUnitKeys;  // wave-uniform load
         else left = n_keys - w * kUnitKeys;
         const int valid = static_cast<int>(left < kUnitKeys ? left : kUnitKeys);
         if (valid <= 0) continue;  // second half of a short last block
 
-        const bf16_t *ks = &ring[s % NS][0];
-        const bf16_t *vs = &ring[s % NS][kUnitElems];
+        const bf16_t *ks = &ring[stage][0];
+        const bf16_t *vs = &ring[stage][kUnitElems];
         floatx16 sacc[2];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
