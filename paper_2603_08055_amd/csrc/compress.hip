@@ -34,6 +34,8 @@
 #include "s3r_device.h"
 #include "s3r_kernels.h"
 
+#include <type_traits>
+
 namespace s3r {
 
 constexpr float kCompressRescaleSlack = 8.0f;  // see select_mfma.hip: lazy raise of the running maximum
@@ -71,7 +73,7 @@ __device__ __forceinline__ half2_t pack_rtz(float a, float b)
     return __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(a, b));
 }
 
-enum CompressMode { kStoreScores = 0, kThreshold = 1, kFilter = 2 };
+enum CompressMode { kStoreScores = 0, kThreshold = 1, kFilter = 2, kThresholdPipe = 3 };
 constexpr int kFilterQT = 1;  // query tiles (of 32 pooled queries) per wave of the filter sweep
 
 // What the TopK-in-the-sweep modes read and write besides the operands.
@@ -105,7 +107,7 @@ __device__ __forceinline__ void compress_block(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = by;
     const int n_kt = static_cast<int>((n_blk + 63) / 64);  // 64-key steps (n_blk < 2^31)
-    if constexpr (MODE == kThreshold) {
+    if constexpr (MODE == kThreshold || MODE == kThresholdPipe) {
         if (bx == 0 && by == 0 && tid == 0) *ft.overflow = 0;  // the filter launch comes later in the stream
     }
     const int64_t head_tiles = static_cast<int64_t>(h) * tiles_padded;
@@ -118,6 +120,38 @@ __device__ __forceinline__ void compress_block(
         if constexpr (NARR >= 3) src[2] = vt_hi + head_tiles * kRowTileElems;
         if constexpr (NARR == 4) src[3] = vt_lo + head_tiles * kRowTileElems;
         const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
+        if constexpr (MODE == kThresholdPipe) {
+            // Software-pipelined sweep: the compute waves read the keys of step t one barrier before
+            // its values, so request group t = {keys of step t -> stage t % 3, values of step t - 1 ->
+            // stage (t - 1) % 3}; t = 0 .. n_kt, out-of-range steps clamped (loaded but never used), so
+            // that every group has the same number of loads.  Two groups in flight.
+            static_assert(NS == 3 && NARR == 3, "pipelined sweep: three stages, bf16 values");
+            auto issue_group = [&](int t, int kstage, int vstage) {
+                const int tk = t < n_kt ? t : n_kt - 1, tv = t >= 1 ? t - 1 : 0;
+#pragma unroll
+                for (int a = 0; a < 3; ++a) {
+                    const int step = a < 2 ? tk : tv, stage = a < 2 ? kstage : vstage;
+                    const unsigned base = ring_base + static_cast<unsigned>(stage) * (NARR * STAGE_ELEMS * 2);
+#pragma unroll
+                    for (int c = 0; c < 8; ++c)
+                        compress_lds_dma_16(src[a] + static_cast<int64_t>(step) * STAGE_ELEMS + c * 512 + lane * 8,
+                                            __builtin_amdgcn_readfirstlane(base + (a * 8 + c) * 1024));
+                }
+            };
+            issue_group(0, 0, 2);
+            if (n_kt >= 1) issue_group(1, 1, 0);
+            int kstage = 1, vstage = 0;  // of the group issued last
+            for (int j = 0; j <= n_kt; ++j) {
+                if (j + 1 <= n_kt) compress_wait_vmcnt<CPS>(); else compress_wait_vmcnt<0>();
+                lds_barrier();  // group j has landed; the stages group j + 2 goes to are free
+                if (j + 2 <= n_kt) {
+                    kstage = (kstage + 1 == 3) ? 0 : kstage + 1;
+                    vstage = (vstage + 1 == 3) ? 0 : vstage + 1;
+                    issue_group(j + 2, kstage, vstage);
+                }
+            }
+            return;
+        }
         auto issue = [&](int kt, int stage) {
             const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (NARR * STAGE_ELEMS * 2);
 #pragma unroll
@@ -141,6 +175,228 @@ __device__ __forceinline__ void compress_block(
     }
 
     // ---- compute waves ---------------------------------------------------------------------------
+    if constexpr (MODE == kThresholdPipe) {
+        // The threshold sweep, software-pipelined in half steps of 32 keys inside each wave: while the
+        // matrix pipe computes the scores of the next half step and the P.V product of the previous
+        // one, the vector ALU runs the softmax of the current one.  (Without this every wave runs
+        // MFMA and VALU phases one after the other, and the waves of a CU fall into step.)
+        const int64_t qtile = static_cast<int64_t>(bx) * CW + wave;
+        const int64_t qrow = qtile * 32 + (lane & 31);
+        const bool wave_active = qtile * 32 < n_blk;
+        const int64_t row_id = static_cast<int64_t>(h) * n_blk + (qrow < n_blk ? qrow : 0);
+        if (!wave_active) {
+            for (int j = 0; j <= n_kt; ++j) lds_barrier();
+            return;
+        }
+        bf16x8 qhi[4], qlo[4];
+        {
+            const int64_t qb = (head_tiles + qtile) * kRowTileElems;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                qhi[s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
+                qlo[s] = *reinterpret_cast<const bf16x8 *>(qs_lo + qb + (s * 64 + lane) * 8);
+            }
+        }
+        floatx16 oacc[2];
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+        float m_run = -1e30f, l_run = 0.f;
+        half2_t bmax[2][16];  // [step parity][mt * 8 + register pair]
+#pragma unroll
+        for (int par = 0; par < 2; ++par)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) bmax[par][i] = half2_t{-INFINITY, -INFINITY};
+
+        // scores of half step mt of the keys in `stage` (only used before the loop)
+        auto scores = [&](int stage, int mt, floatx16 &acc) {
+            const bf16_t *k_hi = &ring[stage][0][0], *k_lo = &ring[stage][1][0];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int off = mt * kRowTileElems + (s * 64 + lane) * 8;
+                const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + off);
+                const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(k_lo + off);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, qhi[s], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qlo[s], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[s], acc, 0, 0, 0);
+            }
+        };
+        // O^T += Vc^T P^T for half step mt of the values in `stage` (only used after the loop)
+        auto pv = [&](int stage, int mt, const bf16x8 (&p)[2]) {
+            const bf16_t *v_hi = &ring[stage][2][0];
+#pragma unroll
+            for (int w = 0; w < 2; ++w)
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    const bf16x8 b = *reinterpret_cast<const bf16x8 *>(v_hi + mt * kRowTileElems + ((w * 2 + dt) * 64 + lane) * 8);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, p[w], oacc[dt], 0, 0, 0);
+                }
+        };
+        // before the overlapped region: keys that do not exist, the running maximum (rarely raised)
+        auto soft_pre = [&](int kt, int mt, floatx16 &acc) {
+            if (kt * 64 + mt * 32 + 32 > n_blk) {
+                asm volatile("" ::: "memory");  // keep this rare path a real branch
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (kt * 64 + mt * 32 + acc_row(lane, r) >= n_blk) acc[r] = -INFINITY;
+            }
+            float mx = acc[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+            const float m_tile = compress_max_halves(mx) * scale_log2;
+            const bool grow = m_tile > m_run + kCompressRescaleSlack;
+            if (__any(grow)) {
+                const float m_new = grow ? m_tile : m_run;
+                const float alpha = fast_exp2(m_run - m_new);
+                m_run = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+            }
+        };
+        // One half step, written out as 16 slots of {one MFMA, one LDS operand read for the MFMA three
+        // slots later, the vector work on one score register}, with a scheduling fence after every
+        // slot so that the order stays as written.  The MFMAs: P.V of the half step before (values in
+        // stage pv_stage, half pv_mt, operands p_in), then the scores of the half step after (keys in
+        // stage k_stage, half k_mt, into acc_next).  The vector work: the softmax of this half step
+        // (scores acc, half mt): bucket maxima, probabilities, their sum, bf16 operands p_out.
+        auto half_step = [&](auto forced_tag, unsigned long long fw, int mt, floatx16 &acc, half2_t (&bm)[16],
+                             bf16x8 (&p_out)[2], int pv_stage, int pv_mt, const bf16x8 (&p_in)[2], int k_stage,
+                             int k_mt, floatx16 &acc_next) {
+            constexpr bool FORCED = decltype(forced_tag)::value;
+            const bf16_t *v_src = &ring[pv_stage][2][0] + pv_mt * kRowTileElems + lane * 8;
+            const bf16_t *khi_src = &ring[k_stage][0][0] + k_mt * kRowTileElems + lane * 8;
+            const bf16_t *klo_src = &ring[k_stage][1][0] + k_mt * kRowTileElems + lane * 8;
+            bf16x8 rd[12];  // reads in order of need: V chunks 0..3, then (k_lo, k_hi) of channel steps 0..3
+            auto read = [&](int i) {
+                if (i < 4) rd[i] = *reinterpret_cast<const bf16x8 *>(v_src + i * 512);
+                else if ((i & 1) == 0) rd[i] = *reinterpret_cast<const bf16x8 *>(klo_src + ((i - 4) >> 1) * 512);
+                else rd[i] = *reinterpret_cast<const bf16x8 *>(khi_src + ((i - 4) >> 1) * 512);
+            };
+            read(0); read(1); read(2);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_next[r] = 0.f;
+            float lsum[4] = {0.f, 0.f, 0.f, 0.f};
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                // ---- matrix pipe
+                if (j < 4) {
+                    oacc[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd[j], p_in[j >> 1], oacc[j & 1], 0, 0, 0);
+                } else {
+                    const int t = j - 4, cs = t / 3, which = t % 3;  // channel step, term of the hi/lo sum
+                    const bf16x8 &a = rd[4 + 2 * cs + (which == 0 ? 0 : 1)];
+                    acc_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, which == 1 ? qlo[cs] : qhi[cs], acc_next, 0, 0, 0);
+                }
+                if (j + 3 < 12) read(j + 3);
+                // ---- vector ALU, score register j
+                if ((j & 1) == 0) {
+                    float a0 = acc[j], a1 = acc[j + 1];
+                    if constexpr (FORCED) {  // forced blocks do not compete (Sec. 3.3)
+                        const unsigned two = static_cast<unsigned>(fw >> (mt * 32 + acc_row(lane, j))) & 3u;
+                        a0 = (two & 1u) ? -INFINITY : a0;
+                        a1 = (two & 2u) ? -INFINITY : a1;
+                    }
+                    bm[mt * 8 + (j >> 1)] = __builtin_elementwise_max(bm[mt * 8 + (j >> 1)], pack_rtz(a0, a1));
+                }
+                acc[j] = fast_exp2(acc[j] * scale_log2 - m_run);
+                lsum[j & 3] += acc[j];
+                if (j & 1) {
+                    p_out[j >> 3][(j & 7) - 1] = static_cast<bf16_t>(acc[j - 1]);
+                    p_out[j >> 3][j & 7] = static_cast<bf16_t>(acc[j]);
+                }
+                // nothing needs these values before the next barrier: tie them to this slot, or the
+                // compiler moves the vector work away from the MFMAs it is meant to overlap with
+                asm volatile("" : "+v"(lsum[j & 3]));
+                if ((j & 1) == 0) asm volatile("" : "+v"(bm[mt * 8 + (j >> 1)]));
+                if ((j & 7) == 7) asm volatile("" : "+v"(p_out[j >> 3]));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            l_run += (lsum[0] + lsum[1]) + (lsum[2] + lsum[3]);
+        };
+
+        floatx16 sacc0, sacc1;
+        bf16x8 p0[2], p1[2];
+#pragma unroll
+        for (int w = 0; w < 2; ++w)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p1[w][i] = static_cast<bf16_t>(0.f);  // first P.V of the loop adds nothing
+        lds_barrier();  // group 0: keys of step 0 (and a copy of the values of step 0 in stage 2)
+        scores(0, 0, sacc0);
+        int kst = 0, vprev = 2;  // stage of the keys of step kt; stage of the values of step kt - 1
+        // one 64-key step; PAR = step parity (which bucket set), as a compile-time choice
+        auto step = [&](auto forced_tag, auto par_tag, int kt) {
+            constexpr int PAR = decltype(par_tag)::value;
+            const unsigned long long fw = decltype(forced_tag)::value ? forced_words[kt] : 0ull;  // wave-uniform
+            const int knext = (kst + 1 == 3) ? 0 : kst + 1;
+            // half step 0: softmax here; P.V of the previous half step and scores of half step 1 on the matrix pipe
+            soft_pre(kt, 0, sacc0);
+            half_step(forced_tag, fw, 0, sacc0, bmax[PAR], p0, vprev, 1, p1, kst, 1, sacc1);
+            lds_barrier();  // group kt + 1: keys of step kt + 1, values of step kt
+            // half step 1: softmax here; P.V of half step 0 and the first scores of the next step on the matrix pipe
+            // (after the last step: a copy of its keys, result unused)
+            soft_pre(kt, 1, sacc1);
+            half_step(forced_tag, fw, 1, sacc1, bmax[PAR], p1, kst, 0, p0, knext, 0, sacc0);
+            vprev = kst;
+            kst = knext;
+        };
+        auto sweep = [&](auto forced_tag) {
+            int kt = 0;
+            for (; kt + 1 < n_kt; kt += 2) {
+                step(forced_tag, std::integral_constant<int, 0>{}, kt);
+                step(forced_tag, std::integral_constant<int, 1>{}, kt + 1);
+            }
+            if (kt < n_kt) step(forced_tag, std::integral_constant<int, 0>{}, kt);
+        };
+        if (forced_words != nullptr) sweep(std::true_type{}); else sweep(std::false_type{});
+        pv(vprev, 1, p1);
+
+        {
+            float bm[64];
+#pragma unroll
+            for (int par = 0; par < 2; ++par)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        unsigned short bits = __builtin_bit_cast(unsigned short, static_cast<_Float16>(bmax[par][i][e]));
+                        if ((bits & 0x8000u) && bits != 0xfc00u) bits += 1;  // rounded toward zero: step negatives down
+                        bm[par * 32 + i * 2 + e] = static_cast<float>(__builtin_bit_cast(_Float16, bits));
+                    }
+            uint32_t T = 0u;
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t trial = T | (1u << bit);
+                const float trial_f = key_to_float(trial);
+                int c = 0;
+                if (trial_f == trial_f) {
+#pragma unroll
+                    for (int i = 0; i < 64; ++i) c += bm[i] >= trial_f ? 1 : 0;
+                }
+                const auto sw = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(c), static_cast<unsigned>(c), false, false);
+                if (static_cast<int>(sw[0] + sw[1]) >= ft.k) T = trial;
+            }
+            if (qrow < n_blk && g == 0) ft.thr[row_id] = T < 0x007fffffu ? -INFINITY : key_to_float(T);
+        }
+        if (qrow < n_blk) {
+            const float inv = 1.f / compress_sum_halves(l_run);
+            float *orow = o_comp + (static_cast<int64_t>(h) * n_blk + qrow) * 64;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    floatx4 o;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[i] = oacc[dt][4 * r4 + i] * inv;
+                    *reinterpret_cast<floatx4 *>(orow + 32 * dt + 8 * r4 + 4 * g) = o;
+                }
+        }
+        return;
+    }
     if constexpr (MODE == kFilter) {
         // Scores only, kFilterQT query tiles per wave.  (Two tiles per wave, which halves the LDS reads
         // per MFMA, measured no faster on MI355X: the sweep is bound by neither.)
@@ -528,7 +784,7 @@ hipError_t launch_compress_threshold(const void *qs_hi, const void *qs_lo, const
     ft.thr = thr; ft.overflow = overflow; ft.k = k;
     if (vt_lo != nullptr)
         return run_compress<true, 2, 3, kThreshold>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
-    return run_compress<false, 3, 3, kThreshold>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
+    return run_compress<false, 3, 3, kThresholdPipe>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
 }
 
 hipError_t launch_compress_filter(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,

@@ -105,8 +105,8 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, 
     const size_t spec_tiles = mfma_ok(dtype, block) ? static_cast<size_t>(heads) * ((n_spec + 63) / 64) * 64 * 64 * 2 : 0;
     L.kb_spec = take(spec_tiles);
     L.vb_spec = take(spec_tiles);
-    // TopK-in-the-sweep buffers, per head chunk like S
-    const size_t chunk_rows = static_cast<size_t>(L.head_chunk) * L.n_blk;
+    // TopK-in-the-sweep buffers, for all heads at once (the sweeps are not chunked)
+    const size_t chunk_rows = static_cast<size_t>(heads) * L.n_blk;
     L.thr = take(chunk_rows * sizeof(float));
     L.cand = take(chunk_rows * 2 * kCandCap * sizeof(int32_t));
     L.cand_count = take(chunk_rows * 2 * sizeof(int));
@@ -210,32 +210,25 @@ s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, 
                 "split kernel launch");
     }
     const size_t tile_head = static_cast<size_t>(tiles) * 32 * 64 * 2;  // bytes per head per array
+    if (fused) {
+        // all heads in one launch each: nothing here is as large as S
+        {
+            StageTimer tm(S3R_STAGE_COMPRESS, stream);
+            S3R_HIP(s3r::launch_compress_threshold(tile[0], tile[1], tile[2], tile[3], tile[4],
+                                                   accurate_pv ? tile[5] : nullptr, o_comp, n_blk, heads, scale,
+                                                   forced_words, kk, fb.thr, fb.overflow, stream),
+                    "compress (threshold) kernel launch");
+        }
+        StageTimer tm(S3R_STAGE_TOPK, stream);
+        S3R_HIP(s3r::launch_compress_filter(tile[0], tile[1], tile[2], tile[3], n_blk, heads, forced_words, fb.thr,
+                                            fb.cand, fb.cand_count, kCandCap, fb.overflow, stream),
+                "compress (filter) kernel launch");
+        S3R_HIP(s3r::launch_topk_candidates(qc, kc, fb.cand, fb.cand_count, kCandCap, idx, n_blk, heads, kk, stream),
+                "candidate topk kernel launch");
+    }
+    const int *run_flag = fused ? fb.overflow : nullptr;
     for (int h0 = 0; h0 < heads; h0 += head_chunk) {
         const int hc = (heads - h0 < head_chunk) ? heads - h0 : head_chunk;
-        if (fused) {
-            {
-                StageTimer tm(S3R_STAGE_COMPRESS, stream);
-                S3R_HIP(s3r::launch_compress_threshold(at(tile[0], h0 * tile_head), at(tile[1], h0 * tile_head),
-                                                       at(tile[2], h0 * tile_head), at(tile[3], h0 * tile_head),
-                                                       at(tile[4], h0 * tile_head),
-                                                       accurate_pv ? at(tile[5], h0 * tile_head) : nullptr,
-                                                       o_comp + static_cast<size_t>(h0) * n_blk * 64, n_blk, hc, scale,
-                                                       forced_words, kk, fb.thr, fb.overflow, stream),
-                        "compress (threshold) kernel launch");
-            }
-            StageTimer tm(S3R_STAGE_TOPK, stream);
-            S3R_HIP(s3r::launch_compress_filter(at(tile[0], h0 * tile_head), at(tile[1], h0 * tile_head),
-                                                at(tile[2], h0 * tile_head), at(tile[3], h0 * tile_head), n_blk, hc,
-                                                forced_words, fb.thr, fb.cand, fb.cand_count, kCandCap, fb.overflow,
-                                                stream),
-                    "compress (filter) kernel launch");
-            S3R_HIP(s3r::launch_topk_candidates(qc + static_cast<size_t>(h0) * n_blk * 64,
-                                                kc + static_cast<size_t>(h0) * n_blk * 64, fb.cand, fb.cand_count,
-                                                kCandCap, idx + static_cast<size_t>(h0) * n_blk * kk, n_blk, hc, kk,
-                                                stream),
-                    "candidate topk kernel launch");
-        }
-        const int *run_flag = fused ? fb.overflow : nullptr;
         {
             StageTimer tm(S3R_STAGE_COMPRESS, stream);
             S3R_HIP(s3r::launch_compress(at(tile[0], h0 * tile_head), at(tile[1], h0 * tile_head),

@@ -415,6 +415,8 @@ __global__ __launch_bounds__(64) void topk_candidates_kernel(const float *__rest
         int place = 0;
         for (int o = 0; o < kk; ++o) place += win[o] < v ? 1 : 0;
         idx[row * k + place] = v;
+    } else if (lane < k) {
+        idx[row * k + lane] = 0;  // fewer candidates than k (only after a cut list): keep the row in range
     }
 }
 

@@ -301,7 +301,7 @@ def test_topk_in_sweep_candidate_overflow_falls_back(s3r, oracle):
 
 def test_topk_in_sweep_is_deterministic_and_agrees_with_stored_scores(s3r):
     """Two runs agree bit for bit; the stored-score route picks the same sets except where the two
-    roundings of a score resolve a near-tie differently (rare), and Oc' is the same either way."""
+    roundings of a score resolve a near-tie differently (rare), and Oc' agrees within the bf16 tolerance."""
     wl = workloads.Workload("two_routes", 1, 700 * 64, 2, 64, "bf16", 64, 12, 95, "normal")
     q, kx, v = workloads.make_inputs(wl, device="cuda")
     a = run_device(s3r, q, kx, v, wl.block, wl.topk)
@@ -314,7 +314,9 @@ def test_topk_in_sweep_is_deterministic_and_agrees_with_stored_scores(s3r):
         s3r.speed3r_set_kernel_choice(0)
     same_rows = (a["idx"] == c["idx"]).all(dim=2).float().mean().item()
     assert same_rows > 0.99, same_rows
-    assert torch.equal(a["o_comp"], c["o_comp"])
+    # the two routes run the online softmax at different granularity (different running maxima, hence
+    # differently rounded bf16 probabilities): same values within the bf16 tolerance
+    assert_close(a["o_comp"].cpu().numpy(), c["o_comp"].cpu().numpy(), TOL["bf16"], "o_comp of the two routes")
 
 
 # ------------------------------------------------- forced global-context blocks (Sec. 3.3) --
