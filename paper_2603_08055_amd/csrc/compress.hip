@@ -74,7 +74,6 @@ __device__ __forceinline__ half2_t pack_rtz(float a, float b)
 }
 
 enum CompressMode { kStoreScores = 0, kThreshold = 1, kFilter = 2, kThresholdPipe = 3 };
-constexpr int kFilterQT = 1;  // query tiles (of 32 pooled queries) per wave of the filter sweep
 
 // What the TopK-in-the-sweep modes read and write besides the operands.
 struct FusedTopkArgs {
@@ -120,38 +119,6 @@ __device__ __forceinline__ void compress_block(
         if constexpr (NARR >= 3) src[2] = vt_hi + head_tiles * kRowTileElems;
         if constexpr (NARR == 4) src[3] = vt_lo + head_tiles * kRowTileElems;
         const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
-        if constexpr (MODE == kThresholdPipe) {
-            // Software-pipelined sweep: the compute waves read the keys of step t one barrier before
-            // its values, so request group t = {keys of step t -> stage t % 3, values of step t - 1 ->
-            // stage (t - 1) % 3}; t = 0 .. n_kt, out-of-range steps clamped (loaded but never used), so
-            // that every group has the same number of loads.  Two groups in flight.
-            static_assert(NS == 3 && NARR == 3, "pipelined sweep: three stages, bf16 values");
-            auto issue_group = [&](int t, int kstage, int vstage) {
-                const int tk = t < n_kt ? t : n_kt - 1, tv = t >= 1 ? t - 1 : 0;
-#pragma unroll
-                for (int a = 0; a < 3; ++a) {
-                    const int step = a < 2 ? tk : tv, stage = a < 2 ? kstage : vstage;
-                    const unsigned base = ring_base + static_cast<unsigned>(stage) * (NARR * STAGE_ELEMS * 2);
-#pragma unroll
-                    for (int c = 0; c < 8; ++c)
-                        compress_lds_dma_16(src[a] + static_cast<int64_t>(step) * STAGE_ELEMS + c * 512 + lane * 8,
-                                            __builtin_amdgcn_readfirstlane(base + (a * 8 + c) * 1024));
-                }
-            };
-            issue_group(0, 0, 2);
-            if (n_kt >= 1) issue_group(1, 1, 0);
-            int kstage = 1, vstage = 0;  // of the group issued last
-            for (int j = 0; j <= n_kt; ++j) {
-                if (j + 1 <= n_kt) compress_wait_vmcnt<CPS>(); else compress_wait_vmcnt<0>();
-                lds_barrier();  // group j has landed; the stages group j + 2 goes to are free
-                if (j + 2 <= n_kt) {
-                    kstage = (kstage + 1 == 3) ? 0 : kstage + 1;
-                    vstage = (vstage + 1 == 3) ? 0 : vstage + 1;
-                    issue_group(j + 2, kstage, vstage);
-                }
-            }
-            return;
-        }
         auto issue = [&](int kt, int stage) {
             const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (NARR * STAGE_ELEMS * 2);
 #pragma unroll
@@ -184,13 +151,47 @@ __device__ __forceinline__ void compress_block(
         const int64_t qrow = qtile * 32 + (lane & 31);
         const bool wave_active = qtile * 32 < n_blk;
         const int64_t row_id = static_cast<int64_t>(h) * n_blk + (qrow < n_blk ? qrow : 0);
-        if (!wave_active) {
-            for (int j = 0; j <= n_kt; ++j) lds_barrier();
-            return;
-        }
+        // Loads.  The keys of step t are read one barrier before its values, so request group t =
+        // {keys of step t -> stage t % 3, values of step t - 1 -> stage (t - 1) % 3}, t = 0 .. n_kt,
+        // out-of-range steps clamped (loaded, never used) so that every group has the same 24 chunks of
+        // 1 KiB; each wave issues CPW of them.  Group t + 2 is requested right after the barrier that
+        // publishes group t; before a barrier a wave waits until only its newest request is in flight.
+        static_assert(NS == 3 && NARR == 3 && 24 % CW == 0, "pipelined sweep: three stages, bf16 values");
+        constexpr int CPW = 24 / CW;
+        const bf16_t *src_k_hi = ks_hi + head_tiles * kRowTileElems, *src_k_lo = ks_lo + head_tiles * kRowTileElems;
+        const bf16_t *src_v = vt_hi + head_tiles * kRowTileElems;
+        const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
+        auto issue_group = [&](int t, int kstage, int vstage) __attribute__((always_inline)) {
+            const int tk = t < n_kt ? t : n_kt - 1, tv = t >= 1 ? t - 1 : 0;
+#pragma unroll
+            for (int i = 0; i < CPW; ++i) {
+                static_assert(CW == 4, "chunk i * CW + wave: the array (i / 2) is then known at compile time");
+                const int a = i >> 1, c = (i & 1) * 4 + wave;  // chunk i * 4 + wave of 0..7 k_hi, 8..15 k_lo, 16..23 v
+                const bf16_t *src = (a == 0 ? src_k_hi : a == 1 ? src_k_lo : src_v) +
+                                    static_cast<int64_t>(a < 2 ? tk : tv) * STAGE_ELEMS + c * 512 + lane * 8;
+                const unsigned dst = ring_base + static_cast<unsigned>(a < 2 ? kstage : vstage) * (NARR * STAGE_ELEMS * 2) +
+                                     (a * 8 + c) * 1024;
+                compress_lds_dma_16(src, __builtin_amdgcn_readfirstlane(dst));
+            }
+        };
+        issue_group(0, 0, 2);
+        if (n_kt >= 1) issue_group(1, 1, 0);
+        int g_kstage = 1, g_vstage = 0;  // stages of the group requested last
+        auto publish = [&](int j) __attribute__((always_inline)) {  // barrier j: group j has landed everywhere; then request group j + 2
+            if (j + 1 <= n_kt) compress_wait_vmcnt<CPW>(); else compress_wait_vmcnt<0>();
+            lds_barrier();
+            if (j + 2 <= n_kt) {
+                g_kstage = (g_kstage + 1 == 3) ? 0 : g_kstage + 1;
+                g_vstage = (g_vstage + 1 == 3) ? 0 : g_vstage + 1;
+                issue_group(j + 2, g_kstage, g_vstage);
+            }
+        };
         bf16x8 qhi[4], qlo[4];
         {
-            const int64_t qb = (head_tiles + qtile) * kRowTileElems;
+            // query tiles past the end of the head's range (inactive waves) still take part in the loads
+            // and barriers; they compute on the last tile and write nothing
+            const int64_t qt = wave_active ? qtile : (n_blk - 1) / 32;
+            const int64_t qb = (head_tiles + qt) * kRowTileElems;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 qhi[s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
@@ -210,7 +211,7 @@ __device__ __forceinline__ void compress_block(
             for (int i = 0; i < 16; ++i) bmax[par][i] = half2_t{-INFINITY, -INFINITY};
 
         // scores of half step mt of the keys in `stage` (only used before the loop)
-        auto scores = [&](int stage, int mt, floatx16 &acc) {
+        auto scores = [&](int stage, int mt, floatx16 &acc) __attribute__((always_inline)) {
             const bf16_t *k_hi = &ring[stage][0][0], *k_lo = &ring[stage][1][0];
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -225,7 +226,7 @@ __device__ __forceinline__ void compress_block(
             }
         };
         // O^T += Vc^T P^T for half step mt of the values in `stage` (only used after the loop)
-        auto pv = [&](int stage, int mt, const bf16x8 (&p)[2]) {
+        auto pv = [&](int stage, int mt, const bf16x8 (&p)[2]) __attribute__((always_inline)) {
             const bf16_t *v_hi = &ring[stage][2][0];
 #pragma unroll
             for (int w = 0; w < 2; ++w)
@@ -236,7 +237,7 @@ __device__ __forceinline__ void compress_block(
                 }
         };
         // before the overlapped region: keys that do not exist, the running maximum (rarely raised)
-        auto soft_pre = [&](int kt, int mt, floatx16 &acc) {
+        auto soft_pre = [&](int kt, int mt, floatx16 &acc) __attribute__((always_inline)) {
             if (kt * 64 + mt * 32 + 32 > n_blk) {
                 asm volatile("" ::: "memory");  // keep this rare path a real branch
 #pragma unroll
@@ -267,13 +268,13 @@ __device__ __forceinline__ void compress_block(
         // (scores acc, half mt): bucket maxima, probabilities, their sum, bf16 operands p_out.
         auto half_step = [&](auto forced_tag, unsigned long long fw, int mt, floatx16 &acc, half2_t (&bm)[16],
                              bf16x8 (&p_out)[2], int pv_stage, int pv_mt, const bf16x8 (&p_in)[2], int k_stage,
-                             int k_mt, floatx16 &acc_next) {
+                             int k_mt, floatx16 &acc_next) __attribute__((always_inline)) {
             constexpr bool FORCED = decltype(forced_tag)::value;
             const bf16_t *v_src = &ring[pv_stage][2][0] + pv_mt * kRowTileElems + lane * 8;
             const bf16_t *khi_src = &ring[k_stage][0][0] + k_mt * kRowTileElems + lane * 8;
             const bf16_t *klo_src = &ring[k_stage][1][0] + k_mt * kRowTileElems + lane * 8;
             bf16x8 rd[12];  // reads in order of need: V chunks 0..3, then (k_lo, k_hi) of channel steps 0..3
-            auto read = [&](int i) {
+            auto read = [&](int i) __attribute__((always_inline)) {
                 if (i < 4) rd[i] = *reinterpret_cast<const bf16x8 *>(v_src + i * 512);
                 else if ((i & 1) == 0) rd[i] = *reinterpret_cast<const bf16x8 *>(klo_src + ((i - 4) >> 1) * 512);
                 else rd[i] = *reinterpret_cast<const bf16x8 *>(khi_src + ((i - 4) >> 1) * 512);
@@ -326,18 +327,18 @@ __device__ __forceinline__ void compress_block(
         for (int w = 0; w < 2; ++w)
 #pragma unroll
             for (int i = 0; i < 8; ++i) p1[w][i] = static_cast<bf16_t>(0.f);  // first P.V of the loop adds nothing
-        lds_barrier();  // group 0: keys of step 0 (and a copy of the values of step 0 in stage 2)
+        publish(0);  // group 0: keys of step 0 (and a copy of the values of step 0 in stage 2)
         scores(0, 0, sacc0);
         int kst = 0, vprev = 2;  // stage of the keys of step kt; stage of the values of step kt - 1
         // one 64-key step; PAR = step parity (which bucket set), as a compile-time choice
-        auto step = [&](auto forced_tag, auto par_tag, int kt) {
+        auto step = [&](auto forced_tag, auto par_tag, int kt) __attribute__((always_inline)) {
             constexpr int PAR = decltype(par_tag)::value;
             const unsigned long long fw = decltype(forced_tag)::value ? forced_words[kt] : 0ull;  // wave-uniform
             const int knext = (kst + 1 == 3) ? 0 : kst + 1;
             // half step 0: softmax here; P.V of the previous half step and scores of half step 1 on the matrix pipe
             soft_pre(kt, 0, sacc0);
             half_step(forced_tag, fw, 0, sacc0, bmax[PAR], p0, vprev, 1, p1, kst, 1, sacc1);
-            lds_barrier();  // group kt + 1: keys of step kt + 1, values of step kt
+            publish(kt + 1);  // group kt + 1: keys of step kt + 1, values of step kt
             // half step 1: softmax here; P.V of half step 0 and the first scores of the next step on the matrix pipe
             // (after the last step: a copy of its keys, result unused)
             soft_pre(kt, 1, sacc1);
@@ -345,7 +346,7 @@ __device__ __forceinline__ void compress_block(
             vprev = kst;
             kst = knext;
         };
-        auto sweep = [&](auto forced_tag) {
+        auto sweep = [&](auto forced_tag) __attribute__((always_inline)) {
             int kt = 0;
             for (; kt + 1 < n_kt; kt += 2) {
                 step(forced_tag, std::integral_constant<int, 0>{}, kt);
@@ -398,101 +399,131 @@ __device__ __forceinline__ void compress_block(
         return;
     }
     if constexpr (MODE == kFilter) {
-        // Scores only, kFilterQT query tiles per wave.  (Two tiles per wave, which halves the LDS reads
-        // per MFMA, measured no faster on MI355X: the sweep is bound by neither.)
-        constexpr int QT = kFilterQT;
-        const int64_t qtile0 = (static_cast<int64_t>(bx) * CW + wave) * QT;
-        const bool wave_active = qtile0 * 32 < n_blk;
-        bf16x8 qhi[QT][4], qlo[QT][4];
-        float thr_f[QT];           // NaN for rows that do not exist: nothing passes
-        int32_t *cand_row[QT];
-        int n_cand[QT];
-        int64_t row_id[QT];
-        bool row_ok[QT];
+        // Scores only, software-pipelined in half steps of 32 keys like the threshold sweep: while the
+        // matrix pipe computes the scores of the next half step, the vector ALU compares the current
+        // ones with the query's bound; the (few) keys that pass are then appended to the lane's list.
+        // (Two query tiles per wave, which halves the LDS reads per MFMA, measured no faster.)
+        const int64_t qtile = static_cast<int64_t>(bx) * CW + wave;
+        const int64_t qrow = qtile * 32 + (lane & 31);
+        const bool wave_active = qtile * 32 < n_blk;
+        const bool row_ok = qrow < n_blk;
+        const int64_t row_id = static_cast<int64_t>(h) * n_blk + (row_ok ? qrow : 0);
+        // Loads: no loader wave; each wave issues CPW of the 16 one-KiB chunks of a step (keys hi and
+        // lo), D steps ahead, right after the barrier that publishes a step, and before a barrier
+        // waits until only its requests for later steps are in flight.  (The candidate stores share
+        // the counter; they only make the wait stricter.)
+        static_assert(NARR == 2 && 16 % CW == 0, "filter sweep: keys only");
+        constexpr int CPW = 16 / CW;
+        static_assert(CPW * (D - 1) < 64, "vmcnt budget");
+        const bf16_t *src_k_hi = ks_hi + head_tiles * kRowTileElems, *src_k_lo = ks_lo + head_tiles * kRowTileElems;
+        const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
+        auto issue_step = [&](int t, int stage) __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < QT; ++t) {
-            const int64_t qrow = (qtile0 + t) * 32 + (lane & 31);
-            row_ok[t] = qrow < n_blk;
-            row_id[t] = static_cast<int64_t>(h) * n_blk + (row_ok[t] ? qrow : 0);
-            thr_f[t] = row_ok[t] ? ft.thr[row_id[t]] : __builtin_nanf("");
-            cand_row[t] = ft.cand + (row_id[t] * 2 + g) * ft.cap;
-            n_cand[t] = 0;
-            if (wave_active) {
-                // tiles past the end of the head's padded range are never read: clamp to the last one
-                const int64_t qt = (qtile0 + t < tiles_padded) ? qtile0 + t : tiles_padded - 1;
-                const int64_t qb = (head_tiles + qt) * kRowTileElems;
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    qhi[t][s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
-                    qlo[t][s] = *reinterpret_cast<const bf16x8 *>(qs_lo + qb + (s * 64 + lane) * 8);
-                }
+            for (int i = 0; i < CPW; ++i) {
+                static_assert(CW == 4, "chunk i * CW + wave: the array (i / 2) is then known at compile time");
+                const int chunk = i * 4 + wave;  // 0..7 k_hi, 8..15 k_lo
+                const bf16_t *src = ((i >> 1) == 0 ? src_k_hi : src_k_lo) + static_cast<int64_t>(t) * STAGE_ELEMS +
+                                    (chunk & 7) * 512 + lane * 8;
+                compress_lds_dma_16(src, __builtin_amdgcn_readfirstlane(
+                                             ring_base + static_cast<unsigned>(stage) * (NARR * STAGE_ELEMS * 2) + chunk * 1024));
             }
-        }
-        int stage = NS - 1;
-        for (int kt = 0; kt < n_kt; ++kt) {
-            stage = (stage + 1 == NS) ? 0 : stage + 1;
+        };
+        for (int t = 0; t < D && t < n_kt; ++t) issue_step(t, t);  // D < NS: stage = t
+        int stage_ahead = D - 1;
+        auto publish = [&](int j) __attribute__((always_inline)) {  // barrier j: step j has landed everywhere (j = n_kt: nothing new); then request step j + D
+            if (j + D <= n_kt) compress_wait_vmcnt<CPW *(D - 1)>(); else compress_wait_vmcnt<0>();
             lds_barrier();
-            if (!wave_active) continue;
-            const bf16_t *k_hi = &ring[stage][0][0];
-            const bf16_t *k_lo = &ring[stage][1][0];
-            const unsigned long long fw = (forced_words != nullptr) ? forced_words[kt] : 0ull;  // wave-uniform
-            floatx16 sacc[QT][2];
+            stage_ahead = (stage_ahead + 1 == NS) ? 0 : stage_ahead + 1;
+            if (j + D < n_kt) issue_step(j + D, stage_ahead);
+        };
+        const float thr_f = (wave_active && row_ok) ? ft.thr[row_id] : __builtin_nanf("");  // NaN: nothing passes
+        int32_t *cand_row = ft.cand + (row_id * 2 + g) * ft.cap;
+        int n_cand = 0;
+        bf16x8 qhi[4], qlo[4];
+        {
+            // waves past the end of the head's range still take part in loads and barriers
+            const int64_t qt = wave_active ? qtile : (n_blk - 1) / 32;
+            const int64_t qb = (head_tiles + qt) * kRowTileElems;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-                for (int t = 0; t < QT; ++t)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sacc[t][mt][r] = 0.f;
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const int off = mt * kRowTileElems + (s * 64 + lane) * 8;
-                    const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + off);
-                    const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(k_lo + off);
-#pragma unroll
-                    for (int t = 0; t < QT; ++t) {  // same MFMA order as the threshold sweep: same bits
-                        sacc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, qhi[t][s], sacc[t][mt], 0, 0, 0);
-                        sacc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qlo[t][s], sacc[t][mt], 0, 0, 0);
-                        sacc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[t][s], sacc[t][mt], 0, 0, 0);
-                    }
-                }
-            }
-            // keys that do not exist or are forced never become candidates: NaN fails every compare
-            if (kt * 64 + 64 > n_blk || fw != 0ull) {
-                asm volatile("" ::: "memory");
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int b = mt * 32 + acc_row(lane, r);
-                        if (kt * 64 + b >= n_blk || ((fw >> b) & 1ull)) {
-#pragma unroll
-                            for (int t = 0; t < QT; ++t) sacc[t][mt][r] = __builtin_nanf("");
-                        }
-                    }
-            }
-#pragma unroll
-            for (int t = 0; t < QT; ++t) {
-                unsigned pass = 0u;  // register (mt, r) -> bit 31 - (16 mt + r): ascending key = descending bit
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) pass = (pass << 1) | (sacc[t][mt][r] >= thr_f[t] ? 1u : 0u);
-                while (pass != 0u) {
-                    const int b = __clz(pass);
-                    pass &= ~(0x80000000u >> b);
-                    const int key = static_cast<int>(kt) * 64 + 32 * (b >> 4) + acc_row(lane, b & 15);
-                    if (n_cand[t] < ft.cap) cand_row[t][n_cand[t]] = key;
-                    ++n_cand[t];
-                }
+            for (int s = 0; s < 4; ++s) {
+                qhi[s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
+                qlo[s] = *reinterpret_cast<const bf16x8 *>(qs_lo + qb + (s * 64 + lane) * 8);
             }
         }
-        if (wave_active) {
+        // One half step as 12 slots of {one MFMA of the next half step's scores (same order as the
+        // threshold sweep: same bits), one LDS operand read, compares of the current scores}, order
+        // fixed by scheduling fences; then the emission of the keys that passed.
+        auto half_step = [&](int kt, int mt, floatx16 &acc, int k_stage, int k_mt, floatx16 &acc_next,
+                             unsigned long long fw) __attribute__((always_inline)) {
+            // keys that do not exist or are forced never become candidates: NaN fails every compare
+            if (kt * 64 + mt * 32 + 32 > n_blk || fw != 0ull) {
+                asm volatile("" ::: "memory");  // keep this rare path a real branch
 #pragma unroll
-            for (int t = 0; t < QT; ++t)
-                if (row_ok[t]) {
-                    ft.cand_count[row_id[t] * 2 + g] = n_cand[t];
-                    if (n_cand[t] > ft.cap) atomicOr(ft.overflow, 1);
+                for (int r = 0; r < 16; ++r) {
+                    const int b = mt * 32 + acc_row(lane, r);
+                    if (kt * 64 + b >= n_blk || ((fw >> b) & 1ull)) acc[r] = __builtin_nanf("");
                 }
+            }
+            const bf16_t *khi_src = &ring[k_stage][0][0] + k_mt * kRowTileElems + lane * 8;
+            const bf16_t *klo_src = &ring[k_stage][1][0] + k_mt * kRowTileElems + lane * 8;
+            bf16x8 rd[8];  // (k_lo, k_hi) of channel steps 0..3
+            auto read = [&](int i) __attribute__((always_inline)) {
+                rd[i] = *reinterpret_cast<const bf16x8 *>(((i & 1) ? khi_src : klo_src) + (i >> 1) * 512);
+            };
+            read(0); read(1); read(2);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_next[r] = 0.f;
+            unsigned pass = 0u;  // register r -> bit 15 - r: ascending key = descending bit
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 12; ++j) {
+                const int cs = j / 3, which = j % 3;
+                const bf16x8 &a = rd[2 * cs + (which == 0 ? 0 : 1)];
+                acc_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, which == 1 ? qlo[cs] : qhi[cs], acc_next, 0, 0, 0);
+                if (j + 3 < 8) read(j + 3);
+                pass = (pass << 1) | (acc[j] >= thr_f ? 1u : 0u);
+                if (j >= 8) pass = (pass << 1) | (acc[j + 4] >= thr_f ? 1u : 0u);  // registers 12..15 ride along
+                asm volatile("" : "+v"(pass));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // bits now in the order r = 0..7, 8, 12, 9, 13, 10, 14, 11, 15 (high to low)
+            while (pass != 0u) {
+                const int b = __clz(pass) - 16;
+                pass &= ~(0x8000u >> b);
+                const int r = b < 8 ? b : 8 + ((b - 8) >> 1) + 4 * ((b - 8) & 1);
+                const int key = kt * 64 + 32 * mt + acc_row(lane, r);
+                if (n_cand < ft.cap) cand_row[n_cand] = key;
+                ++n_cand;
+            }
+        };
+        floatx16 sacc0, sacc1;
+        publish(0);  // keys of step 0
+        {
+            const bf16_t *k_hi = &ring[0][0][0], *k_lo = &ring[0][1][0];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc0[r] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + (s * 64 + lane) * 8);
+                const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(k_lo + (s * 64 + lane) * 8);
+                sacc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, qhi[s], sacc0, 0, 0, 0);
+                sacc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qlo[s], sacc0, 0, 0, 0);
+                sacc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[s], sacc0, 0, 0, 0);
+            }
+        }
+        int kst = 0;
+        for (int kt = 0; kt < n_kt; ++kt) {
+            const unsigned long long fw = (forced_words != nullptr) ? forced_words[kt] : 0ull;  // wave-uniform
+            const int knext = (kst + 1 == NS) ? 0 : kst + 1;
+            half_step(kt, 0, sacc0, kst, 1, sacc1, fw);
+            publish(kt + 1);  // keys of step kt + 1 (after the last step: nothing new; the scores computed
+                              // from that stage are never looked at)
+            half_step(kt, 1, sacc1, knext, 0, sacc0, fw);
+            kst = knext;
+        }
+        if (wave_active && row_ok) {
+            ft.cand_count[row_id * 2 + g] = n_cand;
+            if (n_cand > ft.cap) atomicOr(ft.overflow, 1);
         }
         return;
     }
@@ -712,8 +743,11 @@ __device__ __forceinline__ void compress_block(
 // grid: (ceil(tiles / CW), heads); CW compute waves (32 pooled queries each) + 1 loader wave.  With a
 // run flag (kStoreScores only): a small 1-D grid that does nothing when the device word is 0 and
 // walks over the (gx, gy) shares otherwise.
+// The pipelined sweeps have no loader wave: all CW waves compute and each issues its share of the loads.
+template <int CW, int MODE> constexpr int compress_threads() { return (MODE == kThresholdPipe || MODE == kFilter) ? CW * 64 : (CW + 1) * 64; }
+
 template <bool SPLIT_PV, int NS, int CW, int MODE>
-__global__ __launch_bounds__((CW + 1) * 64, 2) void compress_kernel(
+__global__ __launch_bounds__((compress_threads<CW, MODE>()), 2) void compress_kernel(
     const bf16_t *__restrict__ qs_hi, const bf16_t *__restrict__ qs_lo,
     const bf16_t *__restrict__ ks_hi, const bf16_t *__restrict__ ks_lo,
     const bf16_t *__restrict__ vt_hi, const bf16_t *__restrict__ vt_lo, float *__restrict__ s_guide,
@@ -742,15 +776,14 @@ static hipError_t run_compress(const void *qs_hi, const void *qs_lo, const void 
 {
     const int64_t tiles = pooled_tiles_padded(n_blk);
     const int64_t q_tiles = (n_blk + 31) / 32;
-    constexpr int TPW = (MODE == kFilter) ? CW * kFilterQT : CW;  // query tiles per workgroup
-    const unsigned gx = static_cast<unsigned>((q_tiles + TPW - 1) / TPW), gy = static_cast<unsigned>(heads);
+    const unsigned gx = static_cast<unsigned>((q_tiles + CW - 1) / CW), gy = static_cast<unsigned>(heads);
     dim3 grid(gx, gy);
     if (MODE == kStoreScores && ft.run_flag != nullptr) {
         const unsigned long long total = static_cast<unsigned long long>(gx) * gy;
         if (total > 0xffffffffull) return hipErrorInvalidValue;
         grid = dim3(total > kFlaggedGrid ? kFlaggedGrid : static_cast<unsigned>(total), 1);
     }
-    hipLaunchKernelGGL((compress_kernel<SPLIT_PV, NS, CW, MODE>), grid, dim3((CW + 1) * 64), 0, stream,
+    hipLaunchKernelGGL((compress_kernel<SPLIT_PV, NS, CW, MODE>), grid, dim3(compress_threads<CW, MODE>()), 0, stream,
                        static_cast<const bf16_t *>(qs_hi), static_cast<const bf16_t *>(qs_lo),
                        static_cast<const bf16_t *>(ks_hi), static_cast<const bf16_t *>(ks_lo),
                        static_cast<const bf16_t *>(vt_hi), static_cast<const bf16_t *>(vt_lo), s_guide, ld_s,
@@ -784,7 +817,7 @@ hipError_t launch_compress_threshold(const void *qs_hi, const void *qs_lo, const
     ft.thr = thr; ft.overflow = overflow; ft.k = k;
     if (vt_lo != nullptr)
         return run_compress<true, 2, 3, kThreshold>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
-    return run_compress<false, 3, 3, kThresholdPipe>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
+    return run_compress<false, 3, 4, kThresholdPipe>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
 }
 
 hipError_t launch_compress_filter(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
@@ -794,7 +827,7 @@ hipError_t launch_compress_filter(const void *qs_hi, const void *qs_lo, const vo
 {
     FusedTopkArgs ft{};
     ft.thr = const_cast<float *>(thr); ft.cand = cand; ft.cand_count = cand_count; ft.cap = cap; ft.overflow = overflow;
-    return run_compress<false, 4, 3, kFilter>(qs_hi, qs_lo, ks_hi, ks_lo, nullptr, nullptr, nullptr, 0, nullptr, n_blk, heads, 0.f, forced_words, ft, stream);
+    return run_compress<false, 4, 4, kFilter>(qs_hi, qs_lo, ks_hi, ks_lo, nullptr, nullptr, nullptr, 0, nullptr, n_blk, heads, 0.f, forced_words, ft, stream);
 }
 
 }  // namespace s3r
