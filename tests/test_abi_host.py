@@ -74,6 +74,29 @@ def test_workspace_bytes_and_shape_validation(s3r):
     assert s3r.speed3r_selected_per_row(1000, 64, 16, 5) == 16          # 5 fixed + the 11 others
     assert s3r.speed3r_selected_per_row(1000, 64, 4, 16) == 16          # nothing left to pick
     assert lib.speed3r_selected_per_row(1000, 64, 4, 17) == -1
+    # special tokens and spatial windows: sizes follow from the parameter block
+    n_vggt = 10 * 1374
+    assert s3r.speed3r_num_blocks(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16) == 215                      # runs of 64 rows
+    assert s3r.speed3r_num_blocks(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16, 1374, 5) == 214            # 13690 image rows
+    assert s3r.speed3r_num_blocks(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16, 1374, 5, (37, 37, 8)) == 250   # 5 x 5 windows per view
+    assert s3r.speed3r_num_blocks(n_vggt, 16, 64, 16, 16, s3r.S3R_BF16, 1374, 5, (37, 37, 4)) == 1000  # 10 x 10 windows per view
+    w_plain = s3r.speed3r_workspace_bytes_ex(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16)
+    assert w_plain == s3r.speed3r_workspace_bytes(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16)
+    assert s3r.speed3r_workspace_bytes_ex(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16, 0, 1374, 5, (37, 37, 8)) > w_plain
+    bad = [dict(tokens_per_view=1000, special_per_view=5),                     # 13740 is not a multiple of 1000
+           dict(tokens_per_view=1374, special_per_view=1374),                  # nothing left for the sparse path
+           dict(tokens_per_view=1374, special_per_view=5, grid=(37, 37, 4)),   # block 64 is not 4 x 4
+           dict(tokens_per_view=1374, special_per_view=5, grid=(37, 36, 8)),   # 1369 rows are not a 37 x 36 grid
+           dict(grid=(37, 37, 8)),                                             # windows need the view length
+           dict(tokens_per_view=1374, special_per_view=5, grid=(37, 37, 0))]
+    for kw in bad:
+        assert s3r.speed3r_workspace_bytes_ex(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16, 0, kw.get("tokens_per_view", 0),
+                                              kw.get("special_per_view", 0), kw.get("grid")) == 0, kw
+        with pytest.raises(s3r.Speed3rError):
+            s3r.speed3r_num_blocks(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16, kw.get("tokens_per_view", 0),
+                                   kw.get("special_per_view", 0), kw.get("grid"))
+    assert lib.speed3r_set_kernel_choice(2) == s3r.S3R_OK and lib.speed3r_set_kernel_choice(3) == s3r.S3R_ERR_INVALID_ARG
+    assert lib.speed3r_set_kernel_choice(0) == s3r.S3R_OK
     # null / bad arguments are rejected before any device work
     assert lib.speed3r_sparse_global_attn_ex(None) == s3r.S3R_ERR_INVALID_ARG
     assert "null" in s3r.speed3r_last_error()
