@@ -161,6 +161,19 @@ s3r_status speed3r_compress_attn_scores(const float *qc, const float *kc, const 
                                         int heads, int head_dim, float softmax_scale,
                                         int accurate_pv, void *stream);
 
+/* Steps 2-4 in one go, without S_guide in memory (Sec. 3.2 "Efficient Kernel Implementation",
+ * supplementary Sec. 1): compressed attention and, for every query block, the ascending indices of the
+ * k = min(topk, n_blk) pooled keys with the largest scores; equal scores go to the smaller index.
+ *   qc, kc, vc : in  fp32 [heads][n_blk][head_dim]
+ *   o_comp     : out fp32 [heads][n_blk][head_dim]
+ *   idx        : out int32 [heads][n_blk][k]
+ * Requires k <= 64 (S3R_ERR_UNSUPPORTED otherwise: use the two entry points around this one).
+ * Should the scores of a row tie so massively that its candidate lists run over, the call falls back,
+ * on the device, to scores written to library scratch; the result is the same.  Library-held scratch. */
+s3r_status speed3r_compress_attn_topk(const float *qc, const float *kc, const float *vc, float *o_comp,
+                                      int32_t *idx, int64_t n_blk, int heads, int head_dim, int topk,
+                                      float softmax_scale, int accurate_pv, void *stream);
+
 /* Step 4 (TopKSelect): idx[h][i][0..k) = ascending indices of the k = min(topk, n_blk) largest
  * entries of s_guide[h][i][0..n_blk); equal scores go to the smaller index.  Deterministic.
  * s_guide must hold no NaN. */

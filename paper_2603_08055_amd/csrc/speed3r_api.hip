@@ -569,6 +569,52 @@ s3r_status speed3r_compress_attn_scores(const float *qc, const float *kc, const 
                              static_cast<hipStream_t>(stream));
 }
 
+s3r_status speed3r_compress_attn_topk(const float *qc, const float *kc, const float *vc, float *o_comp, int32_t *idx,
+                                      int64_t n_blk, int heads, int head_dim, int topk, float softmax_scale,
+                                      int accurate_pv, void *stream)
+{
+    if (n_blk <= 0 || heads <= 0 || heads > 65535 || topk <= 0)
+        return fail(S3R_ERR_INVALID_ARG, "n_blk, heads and topk must be positive");
+    if (head_dim != 64) return fail(S3R_ERR_UNSUPPORTED, "head_dim %d unsupported (must be 64)", head_dim);
+    if (!qc || !kc || !vc || !o_comp || !idx) return fail(S3R_ERR_INVALID_ARG, "all five tensors must be non-null");
+    if (!aligned16(qc) || !aligned16(kc) || !aligned16(o_comp))
+        return fail(S3R_ERR_INVALID_ARG, "qc, kc and o_comp must be 16-byte aligned");
+    if (n_blk * heads > 0x7fffffffLL) return fail(S3R_ERR_UNSUPPORTED, "n_blk * heads exceeds 2^31 - 1");
+    const int kk = static_cast<int>(topk < n_blk ? topk : n_blk);
+    if (kk > s3r::kFusedTopkMaxK) return fail(S3R_ERR_UNSUPPORTED, "k = %d exceeds %d", kk, s3r::kFusedTopkMaxK);
+    if (g_kernel_choice == 2) return fail(S3R_ERR_UNSUPPORTED, "TopK inside the sweep is switched off (kernel choice 2)");
+    // scratch: six operand tile arrays, bounds, candidate lists and counts, overflow word, and S for the
+    // fallback in head chunks
+    const int64_t tiles = s3r::pooled_tiles_padded(n_blk);
+    const size_t arr = align_up(static_cast<size_t>(heads) * tiles * 32 * 64 * 2);
+    const size_t rows = static_cast<size_t>(heads) * n_blk;
+    const int64_t ld_s = (n_blk + 63) / 64 * 64;
+    const size_t per_head_s = static_cast<size_t>(n_blk) * ld_s * sizeof(float);
+    int64_t hc = static_cast<int64_t>(kScoreBytesCap / per_head_s);
+    if (hc < 1) hc = 1;
+    if (hc > heads) hc = heads;
+    size_t off = 6 * arr;
+    auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
+    const size_t o_thr = take(rows * sizeof(float));
+    const size_t o_cand = take(rows * 2 * kCandCap * sizeof(int32_t));
+    const size_t o_cnt = take(rows * 2 * sizeof(int));
+    const size_t o_ovf = take(sizeof(int));
+    const size_t o_s = take(per_head_s * hc);
+    void *ws = nullptr;
+    s3r_status st = scratch_get(off, &ws);
+    if (st != S3R_OK) return st;
+    void *tile[6];
+    for (int a = 0; a < 6; ++a) tile[a] = at(ws, a * arr);
+    FusedBufs fb;
+    fb.thr = reinterpret_cast<float *>(at(ws, o_thr));
+    fb.cand = reinterpret_cast<int32_t *>(at(ws, o_cand));
+    fb.cand_count = reinterpret_cast<int *>(at(ws, o_cnt));
+    fb.overflow = reinterpret_cast<int *>(at(ws, o_ovf));
+    return run_compress_topk(qc, kc, vc, tile, reinterpret_cast<float *>(at(ws, o_s)), ld_s, static_cast<int>(hc), o_comp,
+                             idx, n_blk, tiles, heads, kk, resolve_scale(softmax_scale, head_dim), accurate_pv != 0, true,
+                             nullptr, fb, static_cast<hipStream_t>(stream));
+}
+
 s3r_status speed3r_topk_blocks(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t n_blk, int heads,
                                int topk, void *stream)
 {

@@ -45,6 +45,7 @@ EXPORTS = {
     "speed3r_pool_blocks": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _int, _int, _vp]),
     "speed3r_compress_attn_scores": (_int, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _int, _int, _flt,
                                             _int, _vp]),
+    "speed3r_compress_attn_topk": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _int, _flt, _int, _vp]),
     "speed3r_topk_blocks": (_int, [_vp, _i64, _vp, _i64, _int, _int, _vp]),
     "speed3r_select_attn": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _int, _int,
                                    _int, _int, _int, _flt, _vp]),
@@ -228,6 +229,15 @@ def speed3r_compress_attn_scores(qc, kc, vc, s_guide, o_comp, softmax_scale=0.0,
                                                s_guide.shape[2], _dev(o_comp, "o_comp", f32), n_blk,
                                                heads, head_dim, float(softmax_scale),
                                                int(bool(accurate_pv)), _stream(stream)))
+
+
+def speed3r_compress_attn_topk(qc, kc, vc, o_comp, idx, topk, softmax_scale=0.0, accurate_pv=False, stream=None):
+    heads, n_blk, head_dim = qc.shape
+    f32 = torch.float32
+    _check(load().speed3r_compress_attn_topk(_dev(qc, "qc", f32), _dev(kc, "kc", f32), _dev(vc, "vc", f32),
+                                             _dev(o_comp, "o_comp", f32), _dev(idx, "idx", torch.int32), n_blk,
+                                             heads, head_dim, int(topk), float(softmax_scale),
+                                             int(bool(accurate_pv)), _stream(stream)))
 
 
 def speed3r_topk_blocks(s_guide, idx, n_blk, topk, stream=None):

@@ -263,6 +263,57 @@ def test_config5_pi3_block128_small(s3r, oracle, topk):
     end_to_end(s3r, oracle, wl, rows=rows, with_gate=(topk == 16))
 
 
+# ---------------------------------------- compressed attention + TopK without S_guide in memory --
+
+def compress_topk_case(s3r, qc, kc, vc, k, accurate):
+    heads, n_blk, _ = qc.shape
+    kk = min(k, n_blk)
+    o_comp = torch.full((heads, n_blk, 64), float("nan"), device="cuda")
+    idx = torch.full((heads, n_blk, kk), -1, dtype=torch.int32, device="cuda")
+    s3r.speed3r_compress_attn_topk(torch.from_numpy(qc).cuda(), torch.from_numpy(kc).cuda(), torch.from_numpy(vc).cuda(),
+                                   o_comp, idx, k, accurate_pv=accurate)
+    torch.cuda.synchronize()
+    return o_comp.cpu().numpy(), idx.cpu().numpy()
+
+
+@pytest.mark.parametrize("n_blk,k,span", [(5, 3, 2), (63, 7, 2), (64, 64, 3), (65, 1, 2), (200, 16, 8), (1000, 64, 8),
+                                          (2100, 32, 8), (2100, 64, 1), (50, 1000, 4)])
+def test_compress_attn_topk_exact_on_integer_scores(s3r, oracle, n_blk, k, span):
+    """Pooled tensors of small integers: every product and sum is exact in bf16 pairs, fp32 and
+    fp64 alike, so the TopK sets must equal the oracle's bit for bit, ties (there are many) going to
+    the smaller index; with span 1 the ties are so massive that the candidate lists run over and the
+    call takes its fallback, which must give the same sets."""
+    rng = np.random.default_rng(n_blk * 7 + k)
+    heads = 2
+    qc = rng.integers(-span, span + 1, (heads, n_blk, 64)).astype(np.float32)
+    kc = rng.integers(-span, span + 1, (heads, n_blk, 64)).astype(np.float32)
+    vc = rng.standard_normal((heads, n_blk, 64)).astype(np.float32)
+    _, idx = compress_topk_case(s3r, qc, kc, vc, k, False)
+    ref = oracle.topk(oracle.scores(qc.astype(np.float64), kc.astype(np.float64)), min(k, n_blk))
+    assert np.array_equal(idx, ref)
+
+
+@pytest.mark.parametrize("n_blk,heads,k,accurate", [(16, 2, 4, True), (172, 4, 16, False), (172, 4, 16, True),
+                                                    (1000, 2, 64, False), (2147, 3, 32, False), (33, 1, 5, False)])
+def test_compress_attn_topk_random(s3r, oracle, n_blk, heads, k, accurate):
+    rng = np.random.default_rng(n_blk + 13 * k)
+    qc, kc, vc = (rng.standard_normal((heads, n_blk, 64)).astype(np.float32) for _ in range(3))
+    o_comp, idx = compress_topk_case(s3r, qc, kc, vc, k, accurate)
+    s64 = oracle.scores(qc.astype(np.float64), kc.astype(np.float64))
+    n_exact, n_tie = check_topk_sets(s64, idx, min(k, n_blk))
+    assert n_tie <= max(1, (heads * n_blk) // 100)            # fp32-grade scores: near-ties are rare
+    ref = oracle.compressed_attn(s64, vc.astype(np.float64), 0.125)
+    assert_close(o_comp, ref, TOL["f32"] if accurate else TOL["bf16"], "o_comp")
+
+
+def test_compress_attn_topk_rejects_large_k(s3r):
+    z = torch.zeros((1, 128, 64), device="cuda")
+    idx = torch.zeros((1, 128, 65), dtype=torch.int32, device="cuda")
+    with pytest.raises(s3r.Speed3rError) as e:
+        s3r.speed3r_compress_attn_topk(z, z, z, torch.empty_like(z), idx, 65)
+    assert e.value.status == s3r.S3R_ERR_UNSUPPORTED
+
+
 # ------------------------------------ TopK inside the compression sweep vs from stored scores --
 
 @pytest.mark.parametrize("cfg,over", [(2, {}), (3, {"views": 20}), (5, {"views": 12, "topk": 64}),
