@@ -73,6 +73,16 @@ __device__ __forceinline__ half2_t pack_rtz(float a, float b)
     return __builtin_bit_cast(half2_t, __builtin_amdgcn_cvt_pkrtz(a, b));
 }
 
+// max of packed fp16 pairs without the canonicalising copy the generic builtin adds (no NaNs here)
+__device__ __forceinline__ half2_t pk_max(half2_t a, half2_t b)
+{
+    half2_t r;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
 enum CompressMode { kStoreScores = 0, kThreshold = 1, kFilter = 2, kThresholdPipe = 3 };
 
 // What the TopK-in-the-sweep modes read and write besides the operands.
@@ -303,17 +313,22 @@ __device__ __forceinline__ void compress_block(
                         a0 = (two & 1u) ? -INFINITY : a0;
                         a1 = (two & 2u) ? -INFINITY : a1;
                     }
-                    bm[mt * 8 + (j >> 1)] = __builtin_elementwise_max(bm[mt * 8 + (j >> 1)], pack_rtz(a0, a1));
+                    bm[mt * 8 + (j >> 1)] = pk_max(bm[mt * 8 + (j >> 1)], pack_rtz(a0, a1));
                 }
                 acc[j] = fast_exp2(acc[j] * scale_log2 - m_run);
-                lsum[j & 3] += acc[j];
                 if (j & 1) {
-                    p_out[j >> 3][(j & 7) - 1] = static_cast<bf16_t>(acc[j - 1]);
-                    p_out[j >> 3][j & 7] = static_cast<bf16_t>(acc[j]);
+                    // the pair as bf16 operands of P.V; the row sum adds the same rounded values (one
+                    // dot-product instruction per pair)
+                    const bf16x2 pr = {static_cast<bf16_t>(acc[j - 1]), static_cast<bf16_t>(acc[j])};
+                    p_out[j >> 3][(j & 7) - 1] = pr[0];
+                    p_out[j >> 3][j & 7] = pr[1];
+                    lsum[(j >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(pr, bf16x2{static_cast<bf16_t>(1.f), static_cast<bf16_t>(1.f)},
+                                                                         lsum[(j >> 1) & 3], false);
                 }
                 // nothing needs these values before the next barrier: tie them to this slot, or the
                 // compiler moves the vector work away from the MFMAs it is meant to overlap with
-                asm volatile("" : "+v"(lsum[j & 3]));
+                if (j & 1) asm volatile("" : "+v"(lsum[(j >> 1) & 3]));
+                else asm volatile("" : "+v"(acc[j]));
                 if ((j & 1) == 0) asm volatile("" : "+v"(bm[mt * 8 + (j >> 1)]));
                 if ((j & 7) == 7) asm volatile("" : "+v"(p_out[j >> 3]));
                 __builtin_amdgcn_sched_barrier(0);
