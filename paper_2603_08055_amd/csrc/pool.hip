@@ -73,7 +73,10 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ q, cons
             if (!valid)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) raw[i] = static_cast<bf16_t>(0.f);
-            bf16_t *dst = kb + tile_base + (r >> 5) * kRowTileElems + row_tile_chunk_offset(r & 31, c);
+            // 32-row tiles in operand order; a block of 16 rows is stored as the 16-row half of such a
+            // tile, column chunk by column chunk, so that two of them interleave into one tile
+            bf16_t *dst = (B >= 32) ? kb + tile_base + (r >> 5) * kRowTileElems + row_tile_chunk_offset(r & 31, c)
+                                    : kb + tile_base + (c * 16 + r) * 8;
             *reinterpret_cast<bf16x8 *>(dst) = raw;
         }
         if (valid) {
@@ -154,13 +157,13 @@ hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, f
     if (n_blk * heads > 0x7fffffffLL) return hipErrorInvalidValue;
     if (map.period != 0 && n_tok > 0x7fffffffLL) return hipErrorInvalidValue;
     const bool repack = kb != nullptr;
-    if (repack && !(is_bf16 && (block == 64 || block == 128))) return hipErrorInvalidValue;
+    if (repack && !is_bf16) return hipErrorInvalidValue;
 #define S3R_POOL_CASE(TT, BB, RR) \
     return run_pool<TT, BB, RR>(q, k, v, qc, kc, vc, kb, vb, n_tok, heads, n_blk, map, stream)
     if (is_bf16) {
         switch (block) {
-        case 16: S3R_POOL_CASE(bf16_t, 16, false);
-        case 32: S3R_POOL_CASE(bf16_t, 32, false);
+        case 16: if (repack) S3R_POOL_CASE(bf16_t, 16, true); else S3R_POOL_CASE(bf16_t, 16, false);
+        case 32: if (repack) S3R_POOL_CASE(bf16_t, 32, true); else S3R_POOL_CASE(bf16_t, 32, false);
         case 64: if (repack) S3R_POOL_CASE(bf16_t, 64, true); else S3R_POOL_CASE(bf16_t, 64, false);
         case 128: if (repack) S3R_POOL_CASE(bf16_t, 128, true); else S3R_POOL_CASE(bf16_t, 128, false);
         }

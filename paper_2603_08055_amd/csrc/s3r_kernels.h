@@ -61,8 +61,8 @@ hipError_t launch_block_lens(TokenMap map, int block, int64_t n_tok, int64_t n_b
                              hipStream_t stream);
 
 // Block means of q, k, v (fp32 [heads][n_blk][64]; any of qc/kc/vc may be null together) and,
-// when kb/vb are given (bf16 input, block 64 or 128), the per-(head, block) K and V tiles in
-// MFMA operand order: kb, vb are bf16 [heads][n_blk][block * 64].  n_tok counts the tokens of the
+// when kb/vb are given (bf16 input), the per-(head, block) K and V tiles in MFMA operand order:
+// kb, vb are bf16 [heads][n_blk][block * 64] (blocks of 16 rows: half tiles, see pool.hip).  n_tok counts the tokens of the
 // sub-sequence `map` picks out of q, k, v; blocks are runs of that sub-sequence.
 hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, float *kc, float *vc,
                        void *kb, void *vb, int64_t n_tok, int heads, int block, bool is_bf16,
@@ -145,7 +145,7 @@ struct SelectArgs {
 // One thread per query row, fp32 FMA; any dtype, any supported block size.
 hipError_t launch_select_generic(const SelectArgs &a, hipStream_t stream);
 
-// bf16 MFMA kernels (block 64 or 128).
+// bf16 MFMA kernels (any supported block size).
 hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream);
 
 }  // namespace s3r

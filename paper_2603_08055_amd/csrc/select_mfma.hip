@@ -67,7 +67,13 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 // QW    : waves per workgroup = query rows / 32 (block / 32 for selection: one query block)
 // DENSE : every key unit instead of an index list
 // NS    : LDS stages of the unit ring
-template <int QW, bool DENSE, int NS>
+// SMALL : key blocks of 16 or 32 tokens (4 x 4 spatial windows and the like): a 64-key unit is put
+//         together from 4 or 2 blocks, each lane of an LDS-direct load fetching its 16 bytes from the
+//         block its unit row belongs to (the pooling kernel stores such blocks as small tiles in the
+//         same operand order), and a query block fills only the first `block` of a wave's 32 query
+//         columns.  At 16 FLOP per byte of K/V such blocks are bound by the gather alone, so the
+//         empty MFMA columns cost nothing.
+template <int QW, bool DENSE, int NS, bool SMALL>
 __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ kb, const bf16_t *__restrict__ vb,
     const int32_t *__restrict__ idx, const float *__restrict__ o_comp, const bf16_t *__restrict__ gate,
@@ -101,14 +107,20 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         }
         set += set_offset;
     }
-    const int upb_shift = block / kUnitKeys - 1;  // units per key block: 1 or 2, as a shift
+    const int upb_shift = SMALL ? 0 : block / kUnitKeys - 1;  // units per key block: 1 or 2, as a shift
     const int upb_mask = (1 << upb_shift) - 1;
+    const int bpu_shift = SMALL ? (block == 16 ? 2 : 1) : 0;  // SMALL: blocks per unit: 4 or 2, as a shift
     const int64_t qgroup = set;
-    const int64_t t = qgroup * (32 * QW) + wave * 32 + (lane & 31);
+    int64_t t = qgroup * (32 * QW) + wave * 32 + (lane & 31);
     bool row_valid = t < n_tok;
+    if constexpr (SMALL && !DENSE) {  // one query block of `block` rows per wave
+        t = qgroup * block + (lane & 31);
+        row_valid = (lane & 31) < block && t < n_tok;
+    }
     if (!DENSE && blk_len != nullptr) row_valid = wave * 32 + (lane & 31) < blk_len[qgroup];  // spatial windows
     const int64_t trow = qmap.row(row_valid ? t : 0);  // the caller's row of this query
-    const int64_t n_units1 = (n_keys + kUnitKeys - 1) / kUnitKeys;     // units of the first key segment
+    const int64_t n_units1 = SMALL ? (n_blk + (1 << bpu_shift) - 1) >> bpu_shift
+                                   : (n_keys + kUnitKeys - 1) / kUnitKeys;  // units of the first key segment
     const int64_t n_units2 = (n_keys2 + kUnitKeys - 1) / kUnitKeys;    // dense only: second segment
 
     bf16x8 qb[4];
@@ -129,8 +141,19 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         n_steps = static_cast<int>(n_units1 + n_units2);
     } else {
         sel = idx + (static_cast<int64_t>(h) * n_blk + qgroup) * kk;
-        n_steps = kk << upb_shift;
+        n_steps = SMALL ? (kk + (1 << bpu_shift) - 1) >> bpu_shift : kk << upb_shift;
     }
+    // SMALL: the c-th key block of unit s, or -1 past the end of the list
+    auto block_at = [&](int s, int c) -> int {
+        const int pos = (s << bpu_shift) + c;
+        if constexpr (DENSE) return pos < n_blk ? pos : -1;
+        else return pos < kk ? sel[pos] : -1;
+    };
+    auto block_tokens = [&](int j) -> int {  // tokens of key block j (j >= 0)
+        if (blk_len != nullptr) return blk_len[j];
+        const int64_t left = n_keys - static_cast<int64_t>(j) * block;
+        return static_cast<int>(left < block ? left : block);
+    };
 
     const bf16_t *kb_h = kb + static_cast<int64_t>(h) * n_blk * block * 64;
     const bf16_t *vb_h = vb + static_cast<int64_t>(h) * n_blk * block * 64;
@@ -144,8 +167,40 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         else return (sel[s >> upb_shift] << upb_shift) + (s & upb_mask);
     };
     auto issue = [&](int s, int stage) {  // this wave's share of unit s -> LDS stage `stage`
-        const int64_t w = unit_of(s);
         const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (2 * kUnitElems * 2);
+        if constexpr (SMALL) {
+            if (!(DENSE && s >= n_units1)) {
+                // blocks of this unit; missing ones (short last unit) point at the first, and are masked
+                int b[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int j = (c < (1 << bpu_shift)) ? block_at(s, c) : -1;
+                    b[c] = j >= 0 ? j : block_at(s, 0);
+                }
+                const int64_t tile = static_cast<int64_t>(block) * 64;  // elements of a block's K (or V) tile
+#pragma unroll
+                for (int c = 0; c < CPW; ++c) {
+                    const int chunk = wave * CPW + c;   // 0..7: K chunk (mt, channel step), 8..15: V chunk (v, dt)
+                    const bf16_t *src;
+                    if (chunk < 8) {
+                        const int mt = (chunk & 7) >> 2, cs = chunk & 3;
+                        if (bpu_shift == 1) {  // block 32: the 32-row tile of block mt
+                            src = kb_h + b[mt] * tile + cs * 512 + lane * 8;
+                        } else {               // block 16: rows 0..15 of the tile from block 2 mt, rows 16..31 from 2 mt + 1
+                            const int blk = ((lane >> 4) & 1) ? b[2 * mt + 1] : b[2 * mt];
+                            src = kb_h + blk * tile + ((cs * 2 + (lane >> 5)) * 16 + (lane & 15)) * 8;
+                        }
+                    } else {
+                        const int v = (chunk & 7) >> 1, dt = chunk & 1, mt = v >> 1, hw = v & 1;
+                        if (bpu_shift == 1) src = vb_h + b[mt] * tile + ((hw * 2 + dt) * 64 + lane) * 8;
+                        else src = vb_h + b[2 * mt + hw] * tile + (dt * 64 + lane) * 8;
+                    }
+                    lds_dma_16(src, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
+                }
+                return;
+            }
+        }
+        const int64_t w = unit_of(s);
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
             const int chunk = wave * CPW + c;  // 0..7: K, 8..15: V
@@ -177,13 +232,26 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         lds_barrier();
         if (s + D < n_steps) issue(s + D, stage_ahead);
 
-        const int64_t w = unit_of(s);
-        int64_t left;
-        if (DENSE && w >= n_units1) left = n_keys2 - (w - n_units1) * kUnitKeys;
-        else if (blk_len != nullptr) left = blk_len[w >> upb_shift] - (static_cast<int>(w) & upb_mask) * kUnitKeys;  // wave-uniform load
-        else left = n_keys - w * kUnitKeys;
-        const int valid = static_cast<int>(left < kUnitKeys ? left : kUnitKeys);
-        if (valid <= 0) continue;  // second half of a short last block
+        // which of the unit's 64 keys exist (wave-uniform)
+        unsigned long long vmask;
+        if (SMALL && !(DENSE && s >= n_units1)) {
+            vmask = 0ull;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (c < (1 << bpu_shift)) {
+                    const int j = block_at(s, c);
+                    const int len = j >= 0 ? block_tokens(j) : 0;
+                    vmask |= ((1ull << len) - 1ull) << (c * block);
+                }
+        } else {
+            const int64_t w = unit_of(s);
+            int64_t left;
+            if (DENSE && w >= n_units1) left = n_keys2 - (w - n_units1) * kUnitKeys;
+            else if (blk_len != nullptr) left = blk_len[w >> upb_shift] - (static_cast<int>(w) & upb_mask) * kUnitKeys;  // wave-uniform load
+            else left = n_keys - w * kUnitKeys;
+            vmask = left >= kUnitKeys ? ~0ull : left <= 0 ? 0ull : (1ull << left) - 1ull;
+        }
+        if (vmask == 0ull) continue;  // second half of a short last block
 
         const bf16_t *ks = &ring[stage][0];
         const bf16_t *vs = &ring[stage][kUnitElems];
@@ -198,13 +266,13 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
                 sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[c], sacc[mt], 0, 0, 0);
             }
         }
-        if (valid < kUnitKeys) {              // keys past the end of the sequence do not exist
+        if (vmask != ~0ull) {                 // keys past the end of a block or of the sequence do not exist
             asm volatile("" ::: "memory");    // keep this rare path a real branch
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (mt * 32 + acc_row(lane, r) >= valid) sacc[mt][r] = -INFINITY;
+                    if (!((vmask >> (mt * 32 + acc_row(lane, r))) & 1ull)) sacc[mt][r] = -INFINITY;
         }
         float mx = sacc[0][0];
 #pragma unroll
@@ -283,7 +351,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         }
 }
 
-template <int QW, bool DENSE, int NS>
+template <int QW, bool DENSE, int NS, bool SMALL = false>
 static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
 {
     const int64_t rows_per_group = 32 * QW;
@@ -302,7 +370,7 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
     for (int64_t s0 = 0; s0 < sets; s0 += per_launch) {
         const int64_t ns = (sets - s0 < per_launch) ? sets - s0 : per_launch;
         const int64_t grid = (map_mode == 2) ? (ns + 7) / 8 * 8 * a.heads : ns * a.heads;
-        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS>), dim3(static_cast<unsigned>(grid)),
+        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL>), dim3(static_cast<unsigned>(grid)),
                            dim3(QW * 64), 0, stream, static_cast<const bf16_t *>(a.q),
                            static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
                            a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
@@ -323,13 +391,15 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
     // queueing once the memory fabric is saturated).
     if (a.qmap.period != 0 && a.n_tok > 0x7fffffffLL) return hipErrorInvalidValue;
     if (a.idx == nullptr) {
-        if (a.block != 64 && a.block != 128) return hipErrorInvalidValue;
         if (a.n_keys2 > 0 && (a.kb2 == nullptr || a.vb2 == nullptr)) return hipErrorInvalidValue;
-        return run_select<4, true, 3>(a, stream);
+        if (a.block == 64 || a.block == 128) return run_select<4, true, 3>(a, stream);
+        if (a.block == 16 || a.block == 32) return run_select<4, true, 3, true>(a, stream);
+        return hipErrorInvalidValue;
     }
     if (a.n_keys != a.n_tok || a.n_keys2 != 0) return hipErrorInvalidValue;  // selection: keys = the query sequence
     if (a.block == 64) return run_select<2, false, 2>(a, stream);
     if (a.block == 128) return run_select<4, false, 2>(a, stream);
+    if (a.block == 16 || a.block == 32) return run_select<1, false, 2, true>(a, stream);
     return hipErrorInvalidValue;
 }
 

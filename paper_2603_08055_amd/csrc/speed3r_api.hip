@@ -41,7 +41,7 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int g_kernel_choice = 0;  // 0 auto, 1 generic attention kernels only, 2 TopK from scores written to memory
 
-bool mfma_ok(s3r_dtype dtype, int block) { return g_kernel_choice != 1 && dtype == S3R_BF16 && (block == 64 || block == 128); }
+bool mfma_ok(s3r_dtype dtype, int block) { return g_kernel_choice != 1 && dtype == S3R_BF16; }  // any supported block
 
 constexpr int kCandCap = 256;  // candidate slots per list of the TopK-in-the-sweep path (two lists per row)
 

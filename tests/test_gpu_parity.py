@@ -160,7 +160,10 @@ def select_case(s3r, oracle, dtype, n_tok, heads, block, kk, choice, with_gate, 
 
 
 @pytest.mark.parametrize("block,n_tok,kk", [(64, 1024, 4), (64, 1000, 5), (128, 1100, 3), (64, 64, 1),
-                                            (128, 2000, 16), (64, 2500, 40)])
+                                            (128, 2000, 16), (64, 2500, 40),
+                                            # blocks of 16 / 32 tokens: units put together from 4 / 2 blocks
+                                            (16, 1024, 8), (16, 1000, 7), (16, 200, 5), (16, 16, 1), (16, 37, 3),
+                                            (32, 1024, 6), (32, 333, 4), (32, 1000, 3), (32, 40, 2), (16, 3000, 32)])
 @pytest.mark.parametrize("with_gate", [False, True])
 def test_select_attn_mfma_bf16(s3r, oracle, block, n_tok, kk, with_gate):
     select_case(s3r, oracle, "bf16", n_tok, 3, block, kk, 0, with_gate, 1000 + n_tok)
@@ -555,6 +558,16 @@ def test_spatial_windows_equal_plain_path_on_permuted_tokens(s3r, oracle):
 def test_edge_shapes(s3r, oracle, n_tok, block, topk, dtype):
     wl = workloads.Workload(f"edge_{n_tok}_{block}_{topk}", 1, n_tok, 2, 64, dtype, block, topk, 77, "normal")
     end_to_end(s3r, oracle, wl, with_gate=True)
+
+
+@pytest.mark.parametrize("block,views,topk", [(16, 6, 32), (32, 6, 16)])
+def test_small_blocks_end_to_end(s3r, oracle, block, views, topk):
+    """The paper's default pooling size (4 x 4 = 16 tokens, top-32) and 32-token blocks on the MFMA
+    path, on 1374-token views (ragged last block), sampled query blocks."""
+    wl = workloads.config(2, views=views, block=block, topk=topk)
+    rng = np.random.default_rng(18)
+    rows = np.unique(np.concatenate([[0, 1, wl.n_blk - 2, wl.n_blk - 1], rng.choice(wl.n_blk, 40, replace=False)]))
+    end_to_end(s3r, oracle, wl, rows=rows, with_gate=True, label=f"config2/{views}views/block{block}")
 
 
 def test_full_topk_equals_dense_kernel(s3r, oracle):
