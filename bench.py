@@ -105,6 +105,7 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload (1..5); the metric is quoted on 4")
     ap.add_argument("--views", type=int, default=None, help="override the number of views")
     ap.add_argument("--topk", type=int, default=None)
+    ap.add_argument("--block", type=int, default=None, help="override the pooling block (16, 32, 64, 128)")
     ap.add_argument("--special", type=int, default=0,
                     help="treat the first N tokens of every view as special tokens (dense rows); not the headline metric")
     ap.add_argument("--forced-vggt", action="store_true",
@@ -127,6 +128,8 @@ def main():
         over["views"] = args.views
     if args.topk is not None:
         over["topk"] = args.topk
+    if args.block is not None:
+        over["block"] = args.block
     wl = workloads.config(args.config, **over)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
