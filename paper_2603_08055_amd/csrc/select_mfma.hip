@@ -171,29 +171,37 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         if constexpr (SMALL) {
             if (!(DENSE && s >= n_units1)) {
                 // blocks of this unit; missing ones (short last unit) point at the first, and are masked
-                int b[4];
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const int j = (c < (1 << bpu_shift)) ? block_at(s, c) : -1;
-                    b[c] = j >= 0 ? j : block_at(s, 0);
-                }
+                const int f0 = block_at(s, 0);
+                int b0 = f0, b1 = block_at(s, 1), b2 = -1, b3 = -1;
+                if (bpu_shift == 2) { b2 = block_at(s, 2); b3 = block_at(s, 3); }
+                b1 = b1 >= 0 ? b1 : f0;
+                b2 = b2 >= 0 ? b2 : f0;
+                b3 = b3 >= 0 ? b3 : f0;
                 const int64_t tile = static_cast<int64_t>(block) * 64;  // elements of a block's K (or V) tile
+                // Chunk c * QW + wave for c = 0 .. CPW - 1: the tile half mt a chunk belongs to is then a
+                // compile-time constant (chunks 0..7 = K (mt, channel step), 8..15 = V (v = 2 mt + hw, dt)),
+                // which keeps the block numbers in registers.
+                static_assert(QW == 1 || QW == 2 || QW == 4, "chunk distribution");
 #pragma unroll
                 for (int c = 0; c < CPW; ++c) {
-                    const int chunk = wave * CPW + c;   // 0..7: K chunk (mt, channel step), 8..15: V chunk (v, dt)
+                    const int base = c * QW;                 // compile time
+                    const int chunk = base + wave;           // base .. base + QW - 1, all in the same mt
+                    const int mt = (base & 7) >> 2;          // compile time
+                    const int lo = mt == 0 ? b0 : (bpu_shift == 2 ? b2 : b1);   // first block of tile half mt
+                    const int hi = mt == 0 ? b1 : b3;                            // block 16 only: its second block
                     const bf16_t *src;
-                    if (chunk < 8) {
-                        const int mt = (chunk & 7) >> 2, cs = chunk & 3;
+                    if (base < 8) {
+                        const int cs = chunk & 3;
                         if (bpu_shift == 1) {  // block 32: the 32-row tile of block mt
-                            src = kb_h + b[mt] * tile + cs * 512 + lane * 8;
-                        } else {               // block 16: rows 0..15 of the tile from block 2 mt, rows 16..31 from 2 mt + 1
-                            const int blk = ((lane >> 4) & 1) ? b[2 * mt + 1] : b[2 * mt];
+                            src = kb_h + lo * tile + cs * 512 + lane * 8;
+                        } else {               // block 16: rows 0..15 of the tile from its first block, rows 16..31 from its second
+                            const int blk = ((lane >> 4) & 1) ? hi : lo;
                             src = kb_h + blk * tile + ((cs * 2 + (lane >> 5)) * 16 + (lane & 15)) * 8;
                         }
                     } else {
-                        const int v = (chunk & 7) >> 1, dt = chunk & 1, mt = v >> 1, hw = v & 1;
-                        if (bpu_shift == 1) src = vb_h + b[mt] * tile + ((hw * 2 + dt) * 64 + lane) * 8;
-                        else src = vb_h + b[2 * mt + hw] * tile + (dt * 64 + lane) * 8;
+                        const int hw = ((chunk & 7) >> 1) & 1, dt = chunk & 1;
+                        if (bpu_shift == 1) src = vb_h + lo * tile + ((hw * 2 + dt) * 64 + lane) * 8;
+                        else src = vb_h + (hw ? hi : lo) * tile + (dt * 64 + lane) * 8;
                     }
                     lds_dma_16(src, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
                 }
