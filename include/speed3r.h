@@ -4,9 +4,10 @@
  * (batch omitted as in the paper), one GPU.
  *
  * The path (Sec. 3.2, eqs. 3-8; supplementary Alg. 1 and Alg. 2):
- *   1. pool      Q, K, V are mean-pooled over blocks of `block` consecutive
- *                tokens (the paper's s x s window read as a 1-D token run; the
- *                last block may be short and is averaged over its valid tokens).
+ *   1. pool      Q, K, V are mean-pooled over blocks of `block` tokens: runs of
+ *                consecutive tokens (the last block may be short and is averaged
+ *                over its valid tokens) or, on request, the paper's s x s spatial
+ *                windows of every view's patch grid.
  *   2. scores    S_guide[h,i,j] = Qc[h,i] . Kc[h,j]                  (eq. 4)
  *   3. compress  Oc'[h,i] = softmax_j(scale * S_guide[h,i,:]) Vc[h]  (eq. 3)
  *   4. topk      per (h,i): the k = min(topk, n_blk) key blocks with the
@@ -17,6 +18,9 @@
  *   6. merge     out = g * Oc'[h, t / block] + (1 - g) * O_sel,
  *                g = sigmoid(gate_logits) or 1/2                   (eqs. 5, 7, 8)
  * and, as the comparison point, plain dense softmax attention (eq. 2 form).
+ * Optional parts of the layer (fields of s3r_params): special tokens, which get
+ * dense attention over all tokens (eqs. 1-2), a fixed set of key blocks every
+ * query block attends besides its TopK (Sec. 3.3), spatial pooling windows.
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer unless stated otherwise; the
