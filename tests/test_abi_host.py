@@ -160,3 +160,19 @@ def test_workloads_are_seeded_and_shaped():
     o = workloads.make_inputs(workloads.config(5, views=1))[1].float()
     hot = (o[:, 0].norm(dim=-1) > 20).float().mean()
     assert 0.02 < float(hot) < 0.09
+
+
+def test_vggt_forced_blocks_helper():
+    """Fixed global context of the VGGT variant (Sec. 3.3): every block holding a token of the
+    reference view or of a view at the stride, ascending and distinct."""
+    import numpy as np
+    from paper_2603_08055_amd import workloads
+    wl = workloads.config(4)                                   # 1000 views of 1374 tokens, block 64
+    f = workloads.vggt_forced_blocks(wl)
+    assert f.dtype == np.int32 and np.all(np.diff(f) > 0)
+    per_view = [set(range(v * 1374 // 64, ((v + 1) * 1374 - 1) // 64 + 1)) for v in range(0, 1000, 100)]
+    assert set(f.tolist()) == set().union(*per_view) and len(f) == 224
+    assert f[0] == 0 and f[21] == 21 and f[22] == 100 * 1374 // 64
+    assert list(workloads.vggt_forced_blocks(workloads.config(2))) == list(range(22))          # 8 views: reference view only
+    two = workloads.vggt_forced_blocks(workloads.config(3), view_stride=50)                     # views 0 and 50
+    assert list(two) == list(range(22)) + list(range(50 * 1374 // 64, (51 * 1374 - 1) // 64 + 1))
