@@ -33,6 +33,8 @@
 
 namespace s3r {
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
 constexpr float kRescaleSlack = 8.0f;
 constexpr int kUnitKeys = 64;
 constexpr int kUnitElems = kUnitKeys * 64;  // bf16 elements of one K (or V) unit: 8 KiB
@@ -119,10 +121,6 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     }
     if (!DENSE && blk_len != nullptr) row_valid = wave * 32 + (lane & 31) < blk_len[qgroup];  // spatial windows
     const int64_t trow = qmap.row(row_valid ? t : 0);  // the caller's row of this query
-    const int64_t n_units1 = SMALL ? (n_blk + (1 << bpu_shift) - 1) >> bpu_shift
-                                   : (n_keys + kUnitKeys - 1) / kUnitKeys;  // units of the first key segment
-    const int64_t n_units2 = (n_keys2 + kUnitKeys - 1) / kUnitKeys;    // dense only: second segment
-
     bf16x8 qb[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -133,6 +131,9 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
             for (int i = 0; i < 8; ++i) qb[s][i] = static_cast<bf16_t>(0.f);
         }
     }
+    const int64_t n_units1 = SMALL ? (n_blk + (1 << bpu_shift) - 1) >> bpu_shift
+                                   : (n_keys + kUnitKeys - 1) / kUnitKeys;  // units of the first key segment
+    const int64_t n_units2 = (n_keys2 + kUnitKeys - 1) / kUnitKeys;    // dense only: second segment
 
     // ---- the list of key blocks this workgroup visits ---------------------------------------
     int n_steps;  // units to process (host side keeps this below 2^31)
@@ -160,37 +161,46 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const bf16_t *kb2_h = DENSE ? kb2 + static_cast<int64_t>(h) * n_units2 * kUnitElems : nullptr;
     const bf16_t *vb2_h = DENSE ? vb2 + static_cast<int64_t>(h) * n_units2 * kUnitElems : nullptr;
     const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0]));
+    const bool wave_k = wave * CPW < 8;              // plain units: this wave copies K chunks (else V chunks)
+    const bf16_t *seg1 = wave_k ? kb_h : vb_h;       // ... of the first key segment
+    const bf16_t *seg2 = wave_k ? kb2_h : vb2_h;     // ... of the second (dense only)
 
     // step s -> key unit (global unit index); 32-bit arithmetic: these run once per step on the scalar unit
     auto unit_of = [&](int s) -> int {
         if constexpr (DENSE) return s;
         else return (sel[s >> upb_shift] << upb_shift) + (s & upb_mask);
     };
+    // SMALL: the blocks a 64-key unit is put together from; missing ones (short last unit) point at the
+    // first, and are masked
+    struct UnitBlocks { int b0, b1, b2, b3; };
+    auto blocks_of = [&](int s) -> UnitBlocks {
+        const int f0 = block_at(s, 0);
+        int b1 = block_at(s, 1), b2 = -1, b3 = -1;
+        if (bpu_shift == 2) { b2 = block_at(s, 2); b3 = block_at(s, 3); }
+        return UnitBlocks{f0, b1 >= 0 ? b1 : f0, b2 >= 0 ? b2 : f0, b3 >= 0 ? b3 : f0};
+    };
     auto issue = [&](int s, int stage) {  // this wave's share of unit s -> LDS stage `stage`
         const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (2 * kUnitElems * 2);
         if constexpr (SMALL) {
-            if (!(DENSE && s >= n_units1)) {
-                // blocks of this unit; missing ones (short last unit) point at the first, and are masked
-                const int f0 = block_at(s, 0);
-                int b0 = f0, b1 = block_at(s, 1), b2 = -1, b3 = -1;
-                if (bpu_shift == 2) { b2 = block_at(s, 2); b3 = block_at(s, 3); }
-                b1 = b1 >= 0 ? b1 : f0;
-                b2 = b2 >= 0 ? b2 : f0;
-                b3 = b3 >= 0 ? b3 : f0;
-                const int64_t tile = static_cast<int64_t>(block) * 64;  // elements of a block's K (or V) tile
-                // Chunk c * QW + wave for c = 0 .. CPW - 1: the tile half mt a chunk belongs to is then a
-                // compile-time constant (chunks 0..7 = K (mt, channel step), 8..15 = V (v = 2 mt + hw, dt)),
-                // which keeps the block numbers in registers.
-                static_assert(QW == 1 || QW == 2 || QW == 4, "chunk distribution");
+            // (dense: the second key segment is stored as plain 64-key units)
+            const bool small = !(DENSE && s >= n_units1);
+            const UnitBlocks b = blocks_of(small ? s : 0);
+            const int64_t tile = static_cast<int64_t>(block) * 64;  // elements of a block's K (or V) tile
+            // Chunk c * QW + wave for c = 0 .. CPW - 1: the tile half mt a chunk belongs to is then a
+            // compile-time constant (chunks 0..7 = K (mt, channel step), 8..15 = V (v = 2 mt + hw, dt)),
+            // which keeps the block numbers in registers.
+            static_assert(QW == 1 || QW == 2 || QW == 4, "chunk distribution");
 #pragma unroll
-                for (int c = 0; c < CPW; ++c) {
-                    const int base = c * QW;                 // compile time
-                    const int chunk = base + wave;           // base .. base + QW - 1, all in the same mt
-                    const int mt = (base & 7) >> 2;          // compile time
-                    const int lo = mt == 0 ? b0 : (bpu_shift == 2 ? b2 : b1);   // first block of tile half mt
-                    const int hi = mt == 0 ? b1 : b3;                            // block 16 only: its second block
-                    const bf16_t *src;
-                    if (base < 8) {
+            for (int c = 0; c < CPW; ++c) {
+                const int base = c * QW;                 // compile time
+                const int chunk = base + wave;           // base .. base + QW - 1, all in the same mt
+                const int mt = (base & 7) >> 2;          // compile time
+                const bool is_k = base < 8;              // compile time
+                const bf16_t *src;
+                if (small) {
+                    const int lo = mt == 0 ? b.b0 : (bpu_shift == 2 ? b.b2 : b.b1);   // first block of tile half mt
+                    const int hi = mt == 0 ? b.b1 : b.b3;                              // block 16 only: its second block
+                    if (is_k) {
                         const int cs = chunk & 3;
                         if (bpu_shift == 1) {  // block 32: the 32-row tile of block mt
                             src = kb_h + lo * tile + cs * 512 + lane * 8;
@@ -203,21 +213,22 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
                         if (bpu_shift == 1) src = vb_h + lo * tile + ((hw * 2 + dt) * 64 + lane) * 8;
                         else src = vb_h + (hw ? hi : lo) * tile + (dt * 64 + lane) * 8;
                     }
-                    lds_dma_16(src, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
+                } else {
+                    const int64_t w2 = s - n_units1;
+                    src = (is_k ? kb2_h : vb2_h) + w2 * kUnitElems + (chunk & 7) * 512 + lane * 8;
                 }
-                return;
+                lds_dma_16(src, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
             }
+            return;
         }
+        // all chunks of a wave are of one kind (K or V) here
+        static_assert(SMALL || CPW <= 8, "a wave's chunks must be all K or all V");
         const int64_t w = unit_of(s);
+        const bf16_t *unit = (DENSE && w >= n_units1) ? seg2 + (w - n_units1) * kUnitElems : seg1 + w * kUnitElems;
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
             const int chunk = wave * CPW + c;  // 0..7: K, 8..15: V
-            const bf16_t *src;
-            if (DENSE && w >= n_units1)
-                src = (chunk < 8 ? kb2_h : vb2_h) + (w - n_units1) * kUnitElems + (chunk & 7) * 512 + lane * 8;
-            else
-                src = (chunk < 8 ? kb_h : vb_h) + w * kUnitElems + (chunk & 7) * 512 + lane * 8;
-            lds_dma_16(src, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
+            lds_dma_16(unit + (chunk & 7) * 512 + lane * 8, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
         }
     };
 
@@ -228,65 +239,52 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
     float m_run = -1e30f, l_run = 0.f;
 
-    for (int s = 0; s < D && s < n_steps; ++s) issue(s, s);  // D < NS: stage = s
-
-    int stage = NS - 1, stage_ahead = D - 1;  // stages of unit s and of unit s + D, stepped at the loop head
-    for (int s = 0; s < n_steps; ++s) {
-        stage = (stage + 1 == NS) ? 0 : stage + 1;
-        stage_ahead = (stage_ahead + 1 == NS) ? 0 : stage_ahead + 1;
-        // unit s: this wave's loads done, then everybody's (barrier); the barrier also says every wave
-        // has finished unit s - 1, whose stage the next request overwrites
-        if (s + D <= n_steps) wait_vmcnt<CPW *(D - 1)>(); else wait_vmcnt<0>();
-        lds_barrier();
-        if (s + D < n_steps) issue(s + D, stage_ahead);
-
-        // which of the unit's 64 keys exist (wave-uniform)
-        unsigned long long vmask;
+    // which of unit s's 64 keys exist (wave-uniform)
+    auto unit_mask = [&](int s) -> unsigned long long {
         if (SMALL && !(DENSE && s >= n_units1)) {
-            vmask = 0ull;
+            unsigned long long vm = 0ull;
 #pragma unroll
             for (int c = 0; c < 4; ++c)
                 if (c < (1 << bpu_shift)) {
                     const int j = block_at(s, c);
                     const int len = j >= 0 ? block_tokens(j) : 0;
-                    vmask |= ((1ull << len) - 1ull) << (c * block);
+                    vm |= ((1ull << len) - 1ull) << (c * block);
                 }
-        } else {
-            const int64_t w = unit_of(s);
-            int64_t left;
-            if (DENSE && w >= n_units1) left = n_keys2 - (w - n_units1) * kUnitKeys;
-            else if (blk_len != nullptr) left = blk_len[w >> upb_shift] - (static_cast<int>(w) & upb_mask) * kUnitKeys;  // wave-uniform load
-            else left = n_keys - w * kUnitKeys;
-            vmask = left >= kUnitKeys ? ~0ull : left <= 0 ? 0ull : (1ull << left) - 1ull;
+            return vm;
         }
-        if (vmask == 0ull) continue;  // second half of a short last block
+        const int64_t w = unit_of(s);
+        int64_t left;
+        if (DENSE && w >= n_units1) left = n_keys2 - (w - n_units1) * kUnitKeys;
+        else if (blk_len != nullptr) left = blk_len[w >> upb_shift] - (static_cast<int>(w) & upb_mask) * kUnitKeys;  // wave-uniform load
+        else left = n_keys - w * kUnitKeys;
+        return left >= kUnitKeys ? ~0ull : left <= 0 ? 0ull : (1ull << left) - 1ull;
+    };
 
-        const bf16_t *ks = &ring[stage][0];
-        const bf16_t *vs = &ring[stage][kUnitElems];
-        floatx16 sacc[2];
+    floatx16 sacc[2];
+    bf16x8 pb[4];  // probabilities of one unit as MFMA operands
+    const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // S^T = K Q^T of the unit whose K sits in `ks`
+    auto scores = [&](const bf16_t *ks) __attribute__((always_inline)) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[mt][r] = 0.f;
-#pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(ks + ((mt * 4 + c) * 64 + lane) * 8);
-                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[c], sacc[mt], 0, 0, 0);
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[c], c == 0 ? zero16 : sacc[mt], 0, 0, 0);
             }
         }
-        if (vmask != ~0ull) {                 // keys past the end of a block or of the sequence do not exist
-            asm volatile("" ::: "memory");    // keep this rare path a real branch
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (!((vmask >> (mt * 32 + acc_row(lane, r))) & 1ull)) sacc[mt][r] = -INFINITY;
-        }
-        float mx = sacc[0][0];
+    };
+    // keys past the end of a block or of the sequence do not exist
+    auto mask_scores = [&](unsigned long long vmask) __attribute__((always_inline)) {
+        asm volatile("" ::: "memory");    // keep this rare path a real branch
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mt][r]);
+            for (int r = 0; r < 16; ++r)
+                if (!((vmask >> (mt * 32 + acc_row(lane, r))) & 1ull)) sacc[mt][r] = -INFINITY;
+    };
+    // the running maximum after a unit whose largest score (per lane) is mx
+    auto raise_max = [&](float mx) __attribute__((always_inline)) {
         const float m_tile = max_with_other_half(mx) * scale_log2;
         const bool grow = m_tile > m_run + kRescaleSlack;
         if (__any(grow)) {  // rare after the first unit: raise the maximum, rescale the accumulators
@@ -299,33 +297,68 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
         }
-        float lsum[4] = {0.f, 0.f, 0.f, 0.f};
+    };
+    // online softmax of sacc[X] -> pb[X]
+    auto softmax = [&](unsigned long long vmask) __attribute__((always_inline)) {
+        if (vmask != ~0ull) mask_scores(vmask);
+        float mx = sacc[0][0];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                sacc[mt][r] = fast_exp2(sacc[mt][r] * scale_log2 - m_run);
-                lsum[r & 3] += sacc[mt][r];
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mt][r]);
+        raise_max(mx);
+        // The row sum adds the probabilities as the MFMA will see them (rounded to bf16), two per
+        // v_dot2_f32_bf16 with a vector of ones: half the instructions of fp32 adds, and numerator and
+        // denominator of the softmax then carry the same rounding.
+        const bf16x2 ones = {static_cast<bf16_t>(1.f), static_cast<bf16_t>(1.f)};
+        float lsum[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+            for (int i = 0; i < 8; i += 2) {
+                const int mt = v >> 1, r = 8 * (v & 1) + i;
+                const bf16x2 pr = {static_cast<bf16_t>(fast_exp2(sacc[mt][r] * scale_log2 - m_run)),
+                                   static_cast<bf16_t>(fast_exp2(sacc[mt][r + 1] * scale_log2 - m_run))};
+                lsum[(i >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum[(i >> 1) & 3], false);
+                pb[v][i] = pr[0];
+                pb[v][i + 1] = pr[1];
             }
         l_run += (lsum[0] + lsum[1]) + (lsum[2] + lsum[3]);
+    };
+    // O^T += V^T P^T for the unit whose V sits in `vs`
+    auto accumulate = [&](const bf16_t *vs) __attribute__((always_inline)) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int mt = v >> 1, hw = v & 1;
-            bf16x8 pb;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) pb[i] = static_cast<bf16_t>(sacc[mt][8 * hw + i]);
+        for (int v = 0; v < 4; ++v)
 #pragma unroll
             for (int dt = 0; dt < 2; ++dt) {
                 const bf16x8 va = *reinterpret_cast<const bf16x8 *>(vs + ((v * 2 + dt) * 64 + lane) * 8);
-                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, oacc[dt], 0, 0, 0);
+                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[v], oacc[dt], 0, 0, 0);
             }
-        }
+    };
+
+    for (int s = 0; s < D && s < n_steps; ++s) issue(s, s);  // D < NS: stage = s
+
+    int stage = NS - 1, stage_ahead = D - 1;  // stages of unit s and of unit s + D, stepped at the loop head
+    for (int s = 0; s < n_steps; ++s) {
+        stage = (stage + 1 == NS) ? 0 : stage + 1;
+        stage_ahead = (stage_ahead + 1 == NS) ? 0 : stage_ahead + 1;
+        // unit s: this wave's loads done, then everybody's (barrier); the barrier also says every wave
+        // has finished unit s - 1, whose stage the next request overwrites
+        if (s + D <= n_steps) wait_vmcnt<CPW *(D - 1)>(); else wait_vmcnt<0>();
+        lds_barrier();
+        if (s + D < n_steps) issue(s + D, stage_ahead);
+        const unsigned long long vmask = unit_mask(s);
+        if (vmask == 0ull) continue;  // second half of a short last block
+        scores(&ring[stage][0]);
+        softmax(vmask);
+        accumulate(&ring[stage][kUnitElems]);
     }
 
     if (!row_valid) return;
     const float l_tot = sum_with_other_half(l_run);
     const float inv = 1.f / l_tot;
-    if (lse != nullptr && g == 0) lse[static_cast<int64_t>(h) * lse_stride + trow] = (m_run + __builtin_log2f(l_tot)) * kLn2;
+    if (lse != nullptr && g == 0)
+        lse[static_cast<int64_t>(h) * lse_stride + trow] = (m_run + __builtin_log2f(l_tot)) * kLn2;
     const int64_t o = (trow * heads + h) * 64;
     const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_blk + t / block) * 64 : nullptr;
 #pragma unroll
