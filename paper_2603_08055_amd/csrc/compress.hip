@@ -27,10 +27,18 @@
 //     a value below a bucket's true maximum is still a valid bound.  The k-th largest of the 128 bucket maxima is a lower bound of the
 //     query's k-th largest score (k <= 64: that many distinct keys reach it); it is written out per
 //     query.
-//   FILTER mode: the scores are recomputed (same MFMA sequence, so the same bits) and the index of
-//     every score at or above the query's bound is appended to that lane's private candidate list
-//     (a few hundred per query instead of N_b).  No softmax, no Vc, no atomics, deterministic.
-// The exact TopK among the candidates is a small kernel of its own (topk.hip).
+//   FILTER mode: the scores are recomputed and the index of every score at or above the query's
+//     bound is appended to that lane's private candidate list (about a hundred per query instead of
+//     N_b).  No softmax, no Vc, no atomics, deterministic.
+// The exact TopK among the candidates is a small kernel of its own (topk.hip), which recomputes their
+// scores as fp32 dot products.  Because of that the filter needs no fp32-grade scores, only a
+// rigorous error bound, and uses the hi parts alone (one MFMA instead of three, half the LDS reads).
+// With 2^-9 the rounding unit of bf16, a hi-only score s~ and the fp32 score s of the same pair differ
+// by at most eps = 2^-8 (1 + small) |q| |k| (two operand roundings plus fp32 accumulation).  Every key
+// of the exact TopK has s >= T, the threshold sweep's bound, hence s~ >= T - eps: the threshold sweep
+// writes T - eps, with eps from the query's own norm and the largest key norm of the head, and the
+// filter keeps every s~ at or above that.  (The threshold sweep itself keeps the three-MFMA scores:
+// they also feed the softmax of the compressed attention, whose logits need the accuracy.)
 #include "s3r_device.h"
 #include "s3r_kernels.h"
 
@@ -83,11 +91,35 @@ __device__ __forceinline__ half2_t pk_max(half2_t a, half2_t b)
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+// eps for the query whose hi operands this lane and the lane 32 positions away hold: the largest
+// possible distance between a score computed from the hi parts alone and the fp32-grade score of the
+// same (query, key) pair.  |q| <= |q_hi| (1 + 2^-9); the factor 1.03 covers that, the fp32
+// accumulations, the 2^-16 |q||k| of the three-MFMA scores and the roundings of this computation.
+__device__ __forceinline__ float topk_margin(const bf16x8 (&qhi)[4], const float *__restrict__ kmax2_head, int lane)
+{
+    static_assert(kKeyNormSlots == 64, "one partial maximum per lane");
+    float kmax2 = kmax2_head[lane];
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) kmax2 = fmaxf(kmax2, __shfl_xor(kmax2, d, 64));
+    float ss = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float f = static_cast<float>(qhi[s][i]);
+            ss = fmaf(f, f, ss);
+        }
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(ss), __float_as_uint(ss), false, false);
+    ss = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    return (1.03f / 256.f) * __builtin_sqrtf(ss * kmax2);
+}
+
 enum CompressMode { kStoreScores = 0, kThreshold = 1, kFilter = 2, kThresholdPipe = 3 };
 
 // What the TopK-in-the-sweep modes read and write besides the operands.
 struct FusedTopkArgs {
-    float *thr;            // [heads][n_blk]: lower bound of each query's k-th largest score
+    const float *kmax2;    // [heads][kKeyNormSlots]: partial maxima of the squared L2 norms of the pooled keys (threshold modes)
+    float *thr;            // [heads][n_blk]: what a key's hi-only score must reach to be a candidate
     int32_t *cand;         // [heads][n_blk][2][cap] candidate key indices, one list per lane of a query
     int *cand_count;       // [heads][n_blk][2] entries asked for (may exceed cap: the list is then cut)
     int *overflow;         // set to 1 when any list was cut (the caller then redoes TopK the plain way)
@@ -105,7 +137,8 @@ __device__ __forceinline__ void compress_block(
     int64_t ld_s, float *__restrict__ o_comp, int64_t n_blk, int64_t tiles_padded, float scale_log2,
     const unsigned long long *__restrict__ forced_words, const FusedTopkArgs &ft, unsigned bx, unsigned by)
 {
-    constexpr int NARR = (MODE == kFilter) ? 2 : (SPLIT_PV ? 4 : 3);  // ks_hi, ks_lo [, vt_hi [, vt_lo]]
+    // operand arrays staged per step: ks_hi, ks_lo [, vt_hi [, vt_lo]]; the filter sweep: ks_hi alone
+    constexpr int NARR = (MODE == kFilter) ? 1 : (SPLIT_PV ? 4 : 3);
     constexpr int STAGE_ELEMS = 2 * kRowTileElems;   // 64 keys x 64 channels per array: 8 KiB
     constexpr int CPS = NARR * 8;                    // 1 KiB chunks per step, all issued by the loader wave
     constexpr int D = NS - 1;                        // steps in flight
@@ -121,34 +154,36 @@ __device__ __forceinline__ void compress_block(
     }
     const int64_t head_tiles = static_cast<int64_t>(h) * tiles_padded;
 
-    if (wave == CW) {
-        // ---- loader wave ---------------------------------------------------------------------
-        const bf16_t *src[NARR];
-        src[0] = ks_hi + head_tiles * kRowTileElems;
-        src[1] = ks_lo + head_tiles * kRowTileElems;
-        if constexpr (NARR >= 3) src[2] = vt_hi + head_tiles * kRowTileElems;
-        if constexpr (NARR == 4) src[3] = vt_lo + head_tiles * kRowTileElems;
-        const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
-        auto issue = [&](int kt, int stage) {
-            const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (NARR * STAGE_ELEMS * 2);
+    if constexpr (MODE == kStoreScores || MODE == kThreshold) {  // (the pipelined sweeps have no loader wave)
+        if (wave == CW) {
+            // ---- loader wave ---------------------------------------------------------------------
+            const bf16_t *src[NARR];
+            src[0] = ks_hi + head_tiles * kRowTileElems;
+            src[1] = ks_lo + head_tiles * kRowTileElems;
+            if constexpr (NARR >= 3) src[2] = vt_hi + head_tiles * kRowTileElems;
+            if constexpr (NARR == 4) src[3] = vt_lo + head_tiles * kRowTileElems;
+            const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
+            auto issue = [&](int kt, int stage) {
+                const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (NARR * STAGE_ELEMS * 2);
 #pragma unroll
-            for (int a = 0; a < NARR; ++a)
+                for (int a = 0; a < NARR; ++a)
 #pragma unroll
-                for (int c = 0; c < 8; ++c)
-                    compress_lds_dma_16(src[a] + static_cast<int64_t>(kt) * STAGE_ELEMS + c * 512 + lane * 8,
-                                        __builtin_amdgcn_readfirstlane(stage_byte + (a * 8 + c) * 1024));
-        };
-        for (int kt = 0; kt < D && kt < n_kt; ++kt) issue(kt, kt);  // D < NS: stage = kt
-        int stage_ahead = D - 1;  // stage of step kt + D, stepped at the loop head
-        for (int kt = 0; kt < n_kt; ++kt) {
-            stage_ahead = (stage_ahead + 1 == NS) ? 0 : stage_ahead + 1;
-            // step kt landed (loads return in order), tell everybody; the barrier also says the
-            // compute waves are done with step kt - 1, whose stage the next request overwrites
-            if (kt + D <= n_kt) compress_wait_vmcnt<CPS *(D - 1)>(); else compress_wait_vmcnt<0>();
-            lds_barrier();
-            if (kt + D < n_kt) issue(kt + D, stage_ahead);
+                    for (int c = 0; c < 8; ++c)
+                        compress_lds_dma_16(src[a] + static_cast<int64_t>(kt) * STAGE_ELEMS + c * 512 + lane * 8,
+                                            __builtin_amdgcn_readfirstlane(stage_byte + (a * 8 + c) * 1024));
+            };
+            for (int kt = 0; kt < D && kt < n_kt; ++kt) issue(kt, kt);  // D < NS: stage = kt
+            int stage_ahead = D - 1;  // stage of step kt + D, stepped at the loop head
+            for (int kt = 0; kt < n_kt; ++kt) {
+                stage_ahead = (stage_ahead + 1 == NS) ? 0 : stage_ahead + 1;
+                // step kt landed (loads return in order), tell everybody; the barrier also says the
+                // compute waves are done with step kt - 1, whose stage the next request overwrites
+                if (kt + D <= n_kt) compress_wait_vmcnt<CPS *(D - 1)>(); else compress_wait_vmcnt<0>();
+                lds_barrier();
+                if (kt + D < n_kt) issue(kt + D, stage_ahead);
+            }
+            return;
         }
-        return;
     }
 
     // ---- compute waves ---------------------------------------------------------------------------
@@ -396,7 +431,8 @@ __device__ __forceinline__ void compress_block(
                 const auto sw = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(c), static_cast<unsigned>(c), false, false);
                 if (static_cast<int>(sw[0] + sw[1]) >= ft.k) T = trial;
             }
-            if (qrow < n_blk && g == 0) ft.thr[row_id] = T < 0x007fffffu ? -INFINITY : key_to_float(T);
+            const float margin = topk_margin(qhi, ft.kmax2 + h * kKeyNormSlots, lane);  // the filter compares hi-only scores
+            if (qrow < n_blk && g == 0) ft.thr[row_id] = T < 0x007fffffu ? -INFINITY : key_to_float(T) - margin;
         }
         if (qrow < n_blk) {
             const float inv = 1.f / compress_sum_halves(l_run);
@@ -414,33 +450,32 @@ __device__ __forceinline__ void compress_block(
         return;
     }
     if constexpr (MODE == kFilter) {
-        // Scores only, software-pipelined in half steps of 32 keys like the threshold sweep: while the
-        // matrix pipe computes the scores of the next half step, the vector ALU compares the current
-        // ones with the query's bound; the (few) keys that pass are then appended to the lane's list.
-        // (Two query tiles per wave, which halves the LDS reads per MFMA, measured no faster.)
+        // Scores only (hi parts), software-pipelined in half steps of 32 keys like the threshold sweep:
+        // while the matrix pipe computes the scores of the next half step, the vector ALU compares the
+        // current ones with the query's bound; the (few) keys that pass are then appended to the lane's
+        // list.  (Two query tiles per wave, which halves the LDS reads per MFMA, measured no faster.)
         const int64_t qtile = static_cast<int64_t>(bx) * CW + wave;
         const int64_t qrow = qtile * 32 + (lane & 31);
         const bool wave_active = qtile * 32 < n_blk;
         const bool row_ok = qrow < n_blk;
         const int64_t row_id = static_cast<int64_t>(h) * n_blk + (row_ok ? qrow : 0);
-        // Loads: no loader wave; each wave issues CPW of the 16 one-KiB chunks of a step (keys hi and
-        // lo), D steps ahead, right after the barrier that publishes a step, and before a barrier
-        // waits until only its requests for later steps are in flight.  (The candidate stores share
-        // the counter; they only make the wait stricter.)
-        static_assert(NARR == 2 && 16 % CW == 0, "filter sweep: keys only");
-        constexpr int CPW = 16 / CW;
+        // Loads: no loader wave; each wave issues CPW of the 8 one-KiB chunks of a step, D steps ahead,
+        // right after the barrier that publishes a step, and before a barrier waits until only its
+        // requests for later steps are in flight.  (The candidate stores share the counter; they only
+        // make the wait stricter.  Collecting the candidates in LDS and writing them out in batches
+        // was measured: slower.)
+        static_assert(NARR == 1 && 8 % CW == 0, "filter sweep: hi parts of the keys only");
+        constexpr int CPW = 8 / CW;
         static_assert(CPW * (D - 1) < 64, "vmcnt budget");
-        const bf16_t *src_k_hi = ks_hi + head_tiles * kRowTileElems, *src_k_lo = ks_lo + head_tiles * kRowTileElems;
+        const bf16_t *src_k_hi = ks_hi + head_tiles * kRowTileElems;
         const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
         auto issue_step = [&](int t, int stage) __attribute__((always_inline)) {
 #pragma unroll
             for (int i = 0; i < CPW; ++i) {
-                static_assert(CW == 4, "chunk i * CW + wave: the array (i / 2) is then known at compile time");
-                const int chunk = i * 4 + wave;  // 0..7 k_hi, 8..15 k_lo
-                const bf16_t *src = ((i >> 1) == 0 ? src_k_hi : src_k_lo) + static_cast<int64_t>(t) * STAGE_ELEMS +
-                                    (chunk & 7) * 512 + lane * 8;
-                compress_lds_dma_16(src, __builtin_amdgcn_readfirstlane(
-                                             ring_base + static_cast<unsigned>(stage) * (NARR * STAGE_ELEMS * 2) + chunk * 1024));
+                const int chunk = i * CW + wave;
+                compress_lds_dma_16(src_k_hi + static_cast<int64_t>(t) * STAGE_ELEMS + chunk * 512 + lane * 8,
+                                    __builtin_amdgcn_readfirstlane(
+                                        ring_base + static_cast<unsigned>(stage) * (NARR * STAGE_ELEMS * 2) + chunk * 1024));
             }
         };
         for (int t = 0; t < D && t < n_kt; ++t) issue_step(t, t);  // D < NS: stage = t
@@ -451,61 +486,65 @@ __device__ __forceinline__ void compress_block(
             stage_ahead = (stage_ahead + 1 == NS) ? 0 : stage_ahead + 1;
             if (j + D < n_kt) issue_step(j + D, stage_ahead);
         };
-        const float thr_f = (wave_active && row_ok) ? ft.thr[row_id] : __builtin_nanf("");  // NaN: nothing passes
+        // A score passes when score - bound is not negative.  Scores are finite; the bound is kept finite
+        // or +inf so that the difference is never NaN: -inf (fewer than k keys compete: every real key
+        // passes) becomes the lowest finite float, rows that do not exist get +inf (nothing passes).
+        float thr_f = INFINITY;
+        if (wave_active && row_ok) thr_f = fmaxf(ft.thr[row_id], -3.4028234664e38f);
+        floatx16 neg_thr;  // where the MFMA chains start
+#pragma unroll
+        for (int r = 0; r < 16; ++r) neg_thr[r] = -thr_f;
         int32_t *cand_row = ft.cand + (row_id * 2 + g) * ft.cap;
         int n_cand = 0;
-        bf16x8 qhi[4], qlo[4];
+        bf16x8 qhi[4];
         {
             // waves past the end of the head's range still take part in loads and barriers
             const int64_t qt = wave_active ? qtile : (n_blk - 1) / 32;
             const int64_t qb = (head_tiles + qt) * kRowTileElems;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                qhi[s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
-                qlo[s] = *reinterpret_cast<const bf16x8 *>(qs_lo + qb + (s * 64 + lane) * 8);
-            }
+            for (int s = 0; s < 4; ++s) qhi[s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
         }
-        // One half step as 12 slots of {one MFMA of the next half step's scores (same order as the
-        // threshold sweep: same bits), one LDS operand read, compares of the current scores}, order
-        // fixed by scheduling fences; then the emission of the keys that passed.
+        // One half step as 4 slots of {one MFMA of the next half step's scores, its LDS operand read two
+        // slots ahead, the vector work on four of the current scores}, order fixed by scheduling fences;
+        // then the emission of the keys that passed.  The MFMA chain starts from minus the bound instead
+        // of zero, so a register holds score - bound, and the vector work per score is a single funnel
+        // shift that appends its sign bit to the lane's mask (compare, select and shift-or would be three
+        // instructions, and this sweep is bound by the vector ALU).  Adding the bound inside the chain
+        // moves the result by a few fp32 roundings of |bound| + |score|, far inside the margin the bound
+        // already carries.
         auto half_step = [&](int kt, int mt, floatx16 &acc, int k_stage, int k_mt, floatx16 &acc_next,
                              unsigned long long fw) __attribute__((always_inline)) {
-            // keys that do not exist or are forced never become candidates: NaN fails every compare
+            // keys that do not exist or are forced never become candidates: -inf is below every bound
             if (kt * 64 + mt * 32 + 32 > n_blk || fw != 0ull) {
                 asm volatile("" ::: "memory");  // keep this rare path a real branch
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int b = mt * 32 + acc_row(lane, r);
-                    if (kt * 64 + b >= n_blk || ((fw >> b) & 1ull)) acc[r] = __builtin_nanf("");
+                    if (kt * 64 + b >= n_blk || ((fw >> b) & 1ull)) acc[r] = -INFINITY;
                 }
             }
             const bf16_t *khi_src = &ring[k_stage][0][0] + k_mt * kRowTileElems + lane * 8;
-            const bf16_t *klo_src = &ring[k_stage][1][0] + k_mt * kRowTileElems + lane * 8;
-            bf16x8 rd[8];  // (k_lo, k_hi) of channel steps 0..3
+            bf16x8 rd[4];  // keys of channel steps 0..3
             auto read = [&](int i) __attribute__((always_inline)) {
-                rd[i] = *reinterpret_cast<const bf16x8 *>(((i & 1) ? khi_src : klo_src) + (i >> 1) * 512);
+                rd[i] = *reinterpret_cast<const bf16x8 *>(khi_src + i * 512);
             };
-            read(0); read(1); read(2);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc_next[r] = 0.f;
-            unsigned pass = 0u;  // register r -> bit 15 - r: ascending key = descending bit
+            read(0); read(1);
+            unsigned fail = 0u;  // register r -> bit 15 - r, set when the score is below the bound
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < 12; ++j) {
-                const int cs = j / 3, which = j % 3;
-                const bf16x8 &a = rd[2 * cs + (which == 0 ? 0 : 1)];
-                acc_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, which == 1 ? qlo[cs] : qhi[cs], acc_next, 0, 0, 0);
-                if (j + 3 < 8) read(j + 3);
-                pass = (pass << 1) | (acc[j] >= thr_f ? 1u : 0u);
-                if (j >= 8) pass = (pass << 1) | (acc[j + 4] >= thr_f ? 1u : 0u);  // registers 12..15 ride along
-                asm volatile("" : "+v"(pass));
+            for (int j = 0; j < 4; ++j) {
+                acc_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd[j], qhi[j], j == 0 ? neg_thr : acc_next, 0, 0, 0);
+                if (j + 2 < 4) read(j + 2);
+#pragma unroll
+                for (int r = 4 * j; r < 4 * j + 4; ++r)
+                    fail = __builtin_amdgcn_alignbit(fail, __float_as_uint(acc[r]), 31);  // (fail << 1) | sign
+                asm volatile("" : "+v"(fail));
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // bits now in the order r = 0..7, 8, 12, 9, 13, 10, 14, 11, 15 (high to low)
+            unsigned pass = ~fail & 0xffffu;
             while (pass != 0u) {
-                const int b = __clz(pass) - 16;
-                pass &= ~(0x8000u >> b);
-                const int r = b < 8 ? b : 8 + ((b - 8) >> 1) + 4 * ((b - 8) & 1);
+                const int r = __clz(pass) - 16;
+                pass &= ~(0x8000u >> r);
                 const int key = kt * 64 + 32 * mt + acc_row(lane, r);
                 if (n_cand < ft.cap) cand_row[n_cand] = key;
                 ++n_cand;
@@ -514,15 +553,11 @@ __device__ __forceinline__ void compress_block(
         floatx16 sacc0, sacc1;
         publish(0);  // keys of step 0
         {
-            const bf16_t *k_hi = &ring[0][0][0], *k_lo = &ring[0][1][0];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc0[r] = 0.f;
+            const bf16_t *k_hi = &ring[0][0][0];
+            sacc0 = neg_thr;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + (s * 64 + lane) * 8);
-                const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(k_lo + (s * 64 + lane) * 8);
-                sacc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, qhi[s], sacc0, 0, 0, 0);
-                sacc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qlo[s], sacc0, 0, 0, 0);
                 sacc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[s], sacc0, 0, 0, 0);
             }
         }
@@ -542,216 +577,219 @@ __device__ __forceinline__ void compress_block(
         }
         return;
     }
-    const int64_t qtile = static_cast<int64_t>(bx) * CW + wave;
-    const int64_t qrow = qtile * 32 + (lane & 31);
-    const bool wave_active = qtile * 32 < n_blk;
+    if constexpr (MODE == kStoreScores || MODE == kThreshold) {
+        const int64_t qtile = static_cast<int64_t>(bx) * CW + wave;
+        const int64_t qrow = qtile * 32 + (lane & 31);
+        const bool wave_active = qtile * 32 < n_blk;
 
-    bf16x8 qhi[4], qlo[4];
-    if (wave_active) {
-        const int64_t qb = (head_tiles + qtile) * kRowTileElems;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            qhi[s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
-            qlo[s] = *reinterpret_cast<const bf16x8 *>(qs_lo + qb + (s * 64 + lane) * 8);
-        }
-    }
-    floatx16 oacc[2];
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-    float m_run = -1e30f, l_run = 0.f;
-    float *srow = s_guide + (static_cast<int64_t>(h) * n_blk + (qrow < n_blk ? qrow : 0)) * ld_s;
-    const int64_t row_id = static_cast<int64_t>(h) * n_blk + (qrow < n_blk ? qrow : 0);
-
-    half2_t bmax[2][16];         // kThreshold: running maxima of the score registers (pairs, fp16 rounded
-                                 // toward zero), even and odd steps apart
-    if constexpr (MODE == kThreshold) {
-#pragma unroll
-        for (int par = 0; par < 2; ++par)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) bmax[par][i] = half2_t{-INFINITY, -INFINITY};
-    }
-
-    int stage = NS - 1;
-    for (int kt = 0; kt < n_kt; ++kt) {
-        stage = (stage + 1 == NS) ? 0 : stage + 1;
-        lds_barrier();
-        if (!wave_active) continue;
-        const bf16_t *k_hi = &ring[stage][0][0];
-        const bf16_t *k_lo = &ring[stage][1][0];
-
-        floatx16 sacc[2];
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[mt][r] = 0.f;
+        bf16x8 qhi[4], qlo[4];
+        if (wave_active) {
+            const int64_t qb = (head_tiles + qtile) * kRowTileElems;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const int off = mt * kRowTileElems + (s * 64 + lane) * 8;
-                const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + off);
-                const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(k_lo + off);
-                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, qhi[s], sacc[mt], 0, 0, 0);
-                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qlo[s], sacc[mt], 0, 0, 0);
-                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[s], sacc[mt], 0, 0, 0);
+                qhi[s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
+                qlo[s] = *reinterpret_cast<const bf16x8 *>(qs_lo + qb + (s * 64 + lane) * 8);
             }
         }
-        const unsigned long long fw = (forced_words != nullptr) ? forced_words[kt] : 0ull;  // wave-uniform
-        if constexpr (MODE == kStoreScores) {
-            // eq. 4: raw scores out, 4 consecutive keys of one query row per store; never waited for
-            if (qrow < n_blk) {
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        const int64_t key0 = kt * 64 + mt * 32 + 8 * r4 + 4 * g;
-                        if (key0 < ld_s) {
-                            floatx4 o;
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) o[i] = sacc[mt][4 * r4 + i];
-                            if (fw != 0ull) {  // forced blocks leave the TopK competition (Sec. 3.3)
-                                const unsigned nib = static_cast<unsigned>(fw >> (mt * 32 + 8 * r4 + 4 * g)) & 0xFu;
-#pragma unroll
-                                for (int i = 0; i < 4; ++i)
-                                    if (nib & (1u << i)) o[i] = -INFINITY;
-                            }
-                            *reinterpret_cast<floatx4 *>(srow + key0) = o;
-                        }
-                    }
-            }
-        }
-        if (kt * 64 + 64 > n_blk) {           // pooled keys past the end of the sequence do not exist
-            asm volatile("" ::: "memory");    // keep this rare path a real branch
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (kt * 64 + mt * 32 + acc_row(lane, r) >= n_blk) sacc[mt][r] = -INFINITY;
-        }
-        if constexpr (MODE == kThreshold) {
-            auto raise = [&](half2_t (&bm)[16]) {
-                if (fw == 0ull) {
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                        for (int r2 = 0; r2 < 8; ++r2)
-                            bm[mt * 8 + r2] = __builtin_elementwise_max(
-                                bm[mt * 8 + r2], pack_rtz(sacc[mt][2 * r2], sacc[mt][2 * r2 + 1]));
-                } else {  // forced blocks do not compete (Sec. 3.3)
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                        for (int r2 = 0; r2 < 8; ++r2) {
-                            const unsigned two = static_cast<unsigned>(fw >> (mt * 32 + acc_row(lane, 2 * r2))) & 3u;
-                            bm[mt * 8 + r2] = __builtin_elementwise_max(
-                                bm[mt * 8 + r2], pack_rtz((two & 1u) ? -INFINITY : sacc[mt][2 * r2],
-                                                          (two & 2u) ? -INFINITY : sacc[mt][2 * r2 + 1]));
-                        }
-                }
-            };
-            if (kt & 1) raise(bmax[1]); else raise(bmax[0]);  // wave-uniform
-        }
-        const bf16_t *v_hi = &ring[stage][NARR >= 3 ? 2 : 0][0];
-        const bf16_t *v_lo = &ring[stage][NARR - 1][0];
-        // online softmax (eq. 3), base-2 exponent with the scale folded in
-        float mx = sacc[0][0];
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mt][r]);
-        const float m_tile = compress_max_halves(mx) * scale_log2;
-        const bool grow = m_tile > m_run + kCompressRescaleSlack;
-        if (__any(grow)) {
-            const float m_new = grow ? m_tile : m_run;
-            const float alpha = fast_exp2(m_run - m_new);
-            m_run = m_new;
-            l_run *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-        }
-        float lsum[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                sacc[mt][r] = fast_exp2(sacc[mt][r] * scale_log2 - m_run);
-                lsum[r & 3] += sacc[mt][r];
-            }
-        l_run += (lsum[0] + lsum[1]) + (lsum[2] + lsum[3]);
-        // O^T += Vc^T P^T, contraction over the 64 keys in four 16-key steps
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int mt = u >> 1, w = u & 1;
-            bf16x8 p_hi, p_lo;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float p = sacc[mt][8 * w + i];
-                p_hi[i] = static_cast<bf16_t>(p);
-                if constexpr (SPLIT_PV) p_lo[i] = static_cast<bf16_t>(p - static_cast<float>(p_hi[i]));
-            }
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) {
-                const int off = mt * kRowTileElems + ((w * 2 + dt) * 64 + lane) * 8;
-                const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(v_hi + off);
-                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_hi, p_hi, oacc[dt], 0, 0, 0);
-                if constexpr (SPLIT_PV) {
-                    const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(v_lo + off);
-                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_lo, p_hi, oacc[dt], 0, 0, 0);
-                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_hi, p_lo, oacc[dt], 0, 0, 0);
-                }
-            }
-        }
-    }
-
-    if constexpr (MODE == kThreshold) {
-        if (wave_active) {
-            // k-th largest of the query's 128 bucket maxima (64 here, 64 in the lane 32 positions away),
-            // by a bitwise search over order-preserving keys.  Buckets that saw no key hold -inf; with
-            // fewer than k real maxima the bound is -inf and every key becomes a candidate.
-            // The stored maxima were rounded toward zero: step the negative ones one fp16 down so that
-            // every bucket value is at most the bucket's true maximum.
-            float bm[64];
-#pragma unroll
-            for (int par = 0; par < 2; ++par)
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        unsigned short bits = __builtin_bit_cast(unsigned short, static_cast<_Float16>(bmax[par][i][e]));
-                        if ((bits & 0x8000u) && bits != 0xfc00u) bits += 1;  // -65504 steps to -inf
-                        bm[par * 32 + i * 2 + e] = static_cast<float>(__builtin_bit_cast(_Float16, bits));
-                    }
-            uint32_t T = 0u;
-            for (int bit = 31; bit >= 0; --bit) {
-                const uint32_t trial = T | (1u << bit);
-                const float trial_f = key_to_float(trial);  // x >= trial_f  <=>  order_key(x) >= trial
-                int c = 0;
-                if (trial_f == trial_f) {  // keys above +inf's are NaN patterns: nothing reaches them
-#pragma unroll
-                    for (int i = 0; i < 64; ++i) c += bm[i] >= trial_f ? 1 : 0;
-                }
-                const auto sw = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(c), static_cast<unsigned>(c), false, false);
-                if (static_cast<int>(sw[0] + sw[1]) >= ft.k) T = trial;
-            }
-            // trial keys below the key of -inf are NaN patterns and never taken: T stays under it exactly
-            // when fewer than k buckets hold a real maximum
-            if (qrow < n_blk && g == 0) ft.thr[row_id] = T < 0x007fffffu ? -INFINITY : key_to_float(T);
-        }
-    }
-    if (wave_active && qrow < n_blk) {
-        const float inv = 1.f / compress_sum_halves(l_run);
-        float *orow = o_comp + (static_cast<int64_t>(h) * n_blk + qrow) * 64;
+        floatx16 oacc[2];
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                floatx4 o;
+            for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+        float m_run = -1e30f, l_run = 0.f;
+        float *srow = s_guide + (static_cast<int64_t>(h) * n_blk + (qrow < n_blk ? qrow : 0)) * ld_s;
+        const int64_t row_id = static_cast<int64_t>(h) * n_blk + (qrow < n_blk ? qrow : 0);
+
+        half2_t bmax[2][16];         // kThreshold: running maxima of the score registers (pairs, fp16 rounded
+                                     // toward zero), even and odd steps apart
+        if constexpr (MODE == kThreshold) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = oacc[dt][4 * r4 + i] * inv;
-                *reinterpret_cast<floatx4 *>(orow + 32 * dt + 8 * r4 + 4 * g) = o;
+            for (int par = 0; par < 2; ++par)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) bmax[par][i] = half2_t{-INFINITY, -INFINITY};
+        }
+
+        int stage = NS - 1;
+        for (int kt = 0; kt < n_kt; ++kt) {
+            stage = (stage + 1 == NS) ? 0 : stage + 1;
+            lds_barrier();
+            if (!wave_active) continue;
+            const bf16_t *k_hi = &ring[stage][0][0];
+            const bf16_t *k_lo = &ring[stage][1][0];
+
+            floatx16 sacc[2];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[mt][r] = 0.f;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int off = mt * kRowTileElems + (s * 64 + lane) * 8;
+                    const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + off);
+                    const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(k_lo + off);
+                    sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, qhi[s], sacc[mt], 0, 0, 0);
+                    sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qlo[s], sacc[mt], 0, 0, 0);
+                    sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[s], sacc[mt], 0, 0, 0);
+                }
             }
+            const unsigned long long fw = (forced_words != nullptr) ? forced_words[kt] : 0ull;  // wave-uniform
+            if constexpr (MODE == kStoreScores) {
+                // eq. 4: raw scores out, 4 consecutive keys of one query row per store; never waited for
+                if (qrow < n_blk) {
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const int64_t key0 = kt * 64 + mt * 32 + 8 * r4 + 4 * g;
+                            if (key0 < ld_s) {
+                                floatx4 o;
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) o[i] = sacc[mt][4 * r4 + i];
+                                if (fw != 0ull) {  // forced blocks leave the TopK competition (Sec. 3.3)
+                                    const unsigned nib = static_cast<unsigned>(fw >> (mt * 32 + 8 * r4 + 4 * g)) & 0xFu;
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i)
+                                        if (nib & (1u << i)) o[i] = -INFINITY;
+                                }
+                                *reinterpret_cast<floatx4 *>(srow + key0) = o;
+                            }
+                        }
+                }
+            }
+            if (kt * 64 + 64 > n_blk) {           // pooled keys past the end of the sequence do not exist
+                asm volatile("" ::: "memory");    // keep this rare path a real branch
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (kt * 64 + mt * 32 + acc_row(lane, r) >= n_blk) sacc[mt][r] = -INFINITY;
+            }
+            if constexpr (MODE == kThreshold) {
+                auto raise = [&](half2_t (&bm)[16]) {
+                    if (fw == 0ull) {
+#pragma unroll
+                        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                            for (int r2 = 0; r2 < 8; ++r2)
+                                bm[mt * 8 + r2] = __builtin_elementwise_max(
+                                    bm[mt * 8 + r2], pack_rtz(sacc[mt][2 * r2], sacc[mt][2 * r2 + 1]));
+                    } else {  // forced blocks do not compete (Sec. 3.3)
+#pragma unroll
+                        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                            for (int r2 = 0; r2 < 8; ++r2) {
+                                const unsigned two = static_cast<unsigned>(fw >> (mt * 32 + acc_row(lane, 2 * r2))) & 3u;
+                                bm[mt * 8 + r2] = __builtin_elementwise_max(
+                                    bm[mt * 8 + r2], pack_rtz((two & 1u) ? -INFINITY : sacc[mt][2 * r2],
+                                                              (two & 2u) ? -INFINITY : sacc[mt][2 * r2 + 1]));
+                            }
+                    }
+                };
+                if (kt & 1) raise(bmax[1]); else raise(bmax[0]);  // wave-uniform
+            }
+            const bf16_t *v_hi = &ring[stage][NARR >= 3 ? 2 : 0][0];
+            const bf16_t *v_lo = &ring[stage][NARR - 1][0];
+            // online softmax (eq. 3), base-2 exponent with the scale folded in
+            float mx = sacc[0][0];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mt][r]);
+            const float m_tile = compress_max_halves(mx) * scale_log2;
+            const bool grow = m_tile > m_run + kCompressRescaleSlack;
+            if (__any(grow)) {
+                const float m_new = grow ? m_tile : m_run;
+                const float alpha = fast_exp2(m_run - m_new);
+                m_run = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+            }
+            float lsum[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    sacc[mt][r] = fast_exp2(sacc[mt][r] * scale_log2 - m_run);
+                    lsum[r & 3] += sacc[mt][r];
+                }
+            l_run += (lsum[0] + lsum[1]) + (lsum[2] + lsum[3]);
+            // O^T += Vc^T P^T, contraction over the 64 keys in four 16-key steps
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int mt = u >> 1, w = u & 1;
+                bf16x8 p_hi, p_lo;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float p = sacc[mt][8 * w + i];
+                    p_hi[i] = static_cast<bf16_t>(p);
+                    if constexpr (SPLIT_PV) p_lo[i] = static_cast<bf16_t>(p - static_cast<float>(p_hi[i]));
+                }
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    const int off = mt * kRowTileElems + ((w * 2 + dt) * 64 + lane) * 8;
+                    const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(v_hi + off);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_hi, p_hi, oacc[dt], 0, 0, 0);
+                    if constexpr (SPLIT_PV) {
+                        const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(v_lo + off);
+                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_lo, p_hi, oacc[dt], 0, 0, 0);
+                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_hi, p_lo, oacc[dt], 0, 0, 0);
+                    }
+                }
+            }
+        }
+
+        if constexpr (MODE == kThreshold) {
+            if (wave_active) {
+                // k-th largest of the query's 128 bucket maxima (64 here, 64 in the lane 32 positions away),
+                // by a bitwise search over order-preserving keys.  Buckets that saw no key hold -inf; with
+                // fewer than k real maxima the bound is -inf and every key becomes a candidate.
+                // The stored maxima were rounded toward zero: step the negative ones one fp16 down so that
+                // every bucket value is at most the bucket's true maximum.
+                float bm[64];
+#pragma unroll
+                for (int par = 0; par < 2; ++par)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            unsigned short bits = __builtin_bit_cast(unsigned short, static_cast<_Float16>(bmax[par][i][e]));
+                            if ((bits & 0x8000u) && bits != 0xfc00u) bits += 1;  // -65504 steps to -inf
+                            bm[par * 32 + i * 2 + e] = static_cast<float>(__builtin_bit_cast(_Float16, bits));
+                        }
+                uint32_t T = 0u;
+                for (int bit = 31; bit >= 0; --bit) {
+                    const uint32_t trial = T | (1u << bit);
+                    const float trial_f = key_to_float(trial);  // x >= trial_f  <=>  order_key(x) >= trial
+                    int c = 0;
+                    if (trial_f == trial_f) {  // keys above +inf's are NaN patterns: nothing reaches them
+#pragma unroll
+                        for (int i = 0; i < 64; ++i) c += bm[i] >= trial_f ? 1 : 0;
+                    }
+                    const auto sw = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(c), static_cast<unsigned>(c), false, false);
+                    if (static_cast<int>(sw[0] + sw[1]) >= ft.k) T = trial;
+                }
+                // trial keys below the key of -inf are NaN patterns and never taken: T stays under it exactly
+                // when fewer than k buckets hold a real maximum
+                const float margin = topk_margin(qhi, ft.kmax2 + h * kKeyNormSlots, lane);  // the filter compares hi-only scores
+                if (qrow < n_blk && g == 0) ft.thr[row_id] = T < 0x007fffffu ? -INFINITY : key_to_float(T) - margin;
+            }
+        }
+        if (wave_active && qrow < n_blk) {
+            const float inv = 1.f / compress_sum_halves(l_run);
+            float *orow = o_comp + (static_cast<int64_t>(h) * n_blk + qrow) * 64;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    floatx4 o;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[i] = oacc[dt][4 * r4 + i] * inv;
+                    *reinterpret_cast<floatx4 *>(orow + 32 * dt + 8 * r4 + 4 * g) = o;
+                }
+        }
     }
 }
 
@@ -762,7 +800,7 @@ __device__ __forceinline__ void compress_block(
 template <int CW, int MODE> constexpr int compress_threads() { return (MODE == kThresholdPipe || MODE == kFilter) ? CW * 64 : (CW + 1) * 64; }
 
 template <bool SPLIT_PV, int NS, int CW, int MODE>
-__global__ __launch_bounds__((compress_threads<CW, MODE>()), 2) void compress_kernel(
+__global__ __launch_bounds__((compress_threads<CW, MODE>()), (MODE == kFilter ? 4 : 2)) void compress_kernel(
     const bf16_t *__restrict__ qs_hi, const bf16_t *__restrict__ qs_lo,
     const bf16_t *__restrict__ ks_hi, const bf16_t *__restrict__ ks_lo,
     const bf16_t *__restrict__ vt_hi, const bf16_t *__restrict__ vt_lo, float *__restrict__ s_guide,
@@ -824,25 +862,25 @@ hipError_t launch_compress(const void *qs_hi, const void *qs_lo, const void *ks_
 hipError_t launch_compress_threshold(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
                                      const void *vt_hi, const void *vt_lo, float *o_comp, int64_t n_blk,
                                      int heads, float scale, const unsigned long long *forced_words, int k,
-                                     float *thr, int *overflow, hipStream_t stream)
+                                     const float *kmax2, float *thr, int *overflow, hipStream_t stream)
 {
-    if (k < 1 || k > kFusedTopkMaxK) return hipErrorInvalidValue;
+    if (k < 1 || k > kFusedTopkMaxK || kmax2 == nullptr) return hipErrorInvalidValue;
     const float sl = scale * kLog2e;
     FusedTopkArgs ft{};
-    ft.thr = thr; ft.overflow = overflow; ft.k = k;
+    ft.kmax2 = kmax2; ft.thr = thr; ft.overflow = overflow; ft.k = k;
     if (vt_lo != nullptr)
         return run_compress<true, 2, 3, kThreshold>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
     return run_compress<false, 3, 4, kThresholdPipe>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
 }
 
-hipError_t launch_compress_filter(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
+hipError_t launch_compress_filter(const void *qs_hi, const void *ks_hi,
                                   int64_t n_blk, int heads, const unsigned long long *forced_words,
                                   const float *thr, int32_t *cand, int *cand_count, int cap, int *overflow,
                                   hipStream_t stream)
 {
     FusedTopkArgs ft{};
     ft.thr = const_cast<float *>(thr); ft.cand = cand; ft.cand_count = cand_count; ft.cap = cap; ft.overflow = overflow;
-    return run_compress<false, 4, 4, kFilter>(qs_hi, qs_lo, ks_hi, ks_lo, nullptr, nullptr, nullptr, 0, nullptr, n_blk, heads, 0.f, forced_words, ft, stream);
+    return run_compress<false, 4, 4, kFilter>(qs_hi, nullptr, ks_hi, nullptr, nullptr, nullptr, nullptr, 0, nullptr, n_blk, heads, 0.f, forced_words, ft, stream);
 }
 
 }  // namespace s3r

@@ -70,9 +70,12 @@ hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, f
 
 // Pooled fp32 -> bf16 hi/lo operand tiles ([heads][tiles_padded][32 * 64] each, zero padded).
 // vt_lo may be null.
+// kmax2 (optional, [heads][kKeyNormSlots]): the largest of a head's words is the largest squared L2
+// norm of a pooled key of that head.
+constexpr int kKeyNormSlots = 64;
 hipError_t launch_split(const float *qc, const float *kc, const float *vc, void *qs_hi, void *qs_lo,
                         void *ks_hi, void *ks_lo, void *vt_hi, void *vt_lo, int64_t n_blk,
-                        int heads, hipStream_t stream);
+                        int heads, float *kmax2, hipStream_t stream);
 
 // S_guide rows + compressed attention for `heads` heads (operand tiles as written by launch_split).
 // forced_words (optional): bit b of word kt set = pooled key 64 kt + b is a forced block; its
@@ -87,9 +90,11 @@ hipError_t launch_compress(const void *qs_hi, const void *qs_lo, const void *ks_
                            const unsigned long long *forced_words, const int *run_flag, hipStream_t stream);
 
 // TopK without S_guide in memory, k <= kFusedTopkMaxK, in three launches:
-//  threshold: the compression sweep (writes o_comp) that also leaves, per query row, a lower bound
-//             thr [heads][n_blk] of its k-th largest non-forced score, and clears *overflow;
-//  filter:    recomputes the scores and appends the index of every one >= the bound to
+//  threshold: the compression sweep (writes o_comp) that also leaves, per query row, thr [heads][n_blk]:
+//             a lower bound of its k-th largest non-forced score, less the margin by which the filter's
+//             hi-only scores may fall short of the fp32-grade ones (kmax2 as written by launch_split),
+//             and clears *overflow;
+//  filter:    recomputes the scores (hi parts only) and appends the index of every one >= thr to
 //             cand [heads][n_blk][2][cap] (counts in cand_count [heads][n_blk][2], which may exceed
 //             cap: the list is then cut and *overflow set);
 //  candidates (launch_topk_candidates): exact TopK among the candidates from fp32 dot products.
@@ -97,8 +102,8 @@ constexpr int kFusedTopkMaxK = 64;
 hipError_t launch_compress_threshold(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
                                      const void *vt_hi, const void *vt_lo, float *o_comp, int64_t n_blk,
                                      int heads, float scale, const unsigned long long *forced_words, int k,
-                                     float *thr, int *overflow, hipStream_t stream);
-hipError_t launch_compress_filter(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
+                                     const float *kmax2, float *thr, int *overflow, hipStream_t stream);
+hipError_t launch_compress_filter(const void *qs_hi, const void *ks_hi,
                                   int64_t n_blk, int heads, const unsigned long long *forced_words,
                                   const float *thr, int32_t *cand, int *cand_count, int cap, int *overflow,
                                   hipStream_t stream);

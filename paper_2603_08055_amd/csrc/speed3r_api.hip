@@ -67,7 +67,7 @@ struct Layout {
     int width;   // blocks attended per row: kk + n_forced
     int head_chunk;
     size_t qc, kc, vc, oc, tile[6], idx, idx_merged, forced_clean, forced_words, s, kb, vb, kb_spec, vb_spec;
-    size_t thr, cand, cand_count, overflow, blk_len, total;
+    size_t kmax2, thr, cand, cand_count, overflow, blk_len, total;
 };
 
 // n_tok: tokens on the sparse path (the image tokens); n_spec: special tokens (dense rows).
@@ -107,6 +107,7 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, 
     L.vb_spec = take(spec_tiles);
     // TopK-in-the-sweep buffers, for all heads at once (the sweeps are not chunked)
     const size_t chunk_rows = static_cast<size_t>(heads) * L.n_blk;
+    L.kmax2 = take(static_cast<size_t>(heads) * s3r::kKeyNormSlots * sizeof(float));
     L.thr = take(chunk_rows * sizeof(float));
     L.cand = take(chunk_rows * 2 * kCandCap * sizeof(int32_t));
     L.cand_count = take(chunk_rows * 2 * sizeof(int));
@@ -186,6 +187,7 @@ char *at(void *base, size_t off) { return static_cast<char *>(base) + off; }
 
 // Buffers of the TopK-in-the-sweep path (all null: TopK from scores written to s_buf).
 struct FusedBufs {
+    float *kmax2 = nullptr;   // [heads][kKeyNormSlots]: partial maxima of the pooled keys' squared norms
     float *thr = nullptr;
     int32_t *cand = nullptr;
     int *cand_count = nullptr;
@@ -206,7 +208,7 @@ s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, 
     {
         StageTimer tm(S3R_STAGE_SPLIT, stream);
         S3R_HIP(s3r::launch_split(qc, kc, vc, tile[0], tile[1], tile[2], tile[3], tile[4],
-                                  accurate_pv ? tile[5] : nullptr, n_blk, heads, stream),
+                                  accurate_pv ? tile[5] : nullptr, n_blk, heads, fused ? fb.kmax2 : nullptr, stream),
                 "split kernel launch");
     }
     const size_t tile_head = static_cast<size_t>(tiles) * 32 * 64 * 2;  // bytes per head per array
@@ -216,11 +218,11 @@ s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, 
             StageTimer tm(S3R_STAGE_COMPRESS, stream);
             S3R_HIP(s3r::launch_compress_threshold(tile[0], tile[1], tile[2], tile[3], tile[4],
                                                    accurate_pv ? tile[5] : nullptr, o_comp, n_blk, heads, scale,
-                                                   forced_words, kk, fb.thr, fb.overflow, stream),
+                                                   forced_words, kk, fb.kmax2, fb.thr, fb.overflow, stream),
                     "compress (threshold) kernel launch");
         }
         StageTimer tm(S3R_STAGE_TOPK, stream);
-        S3R_HIP(s3r::launch_compress_filter(tile[0], tile[1], tile[2], tile[3], n_blk, heads, forced_words, fb.thr,
+        S3R_HIP(s3r::launch_compress_filter(tile[0], tile[2], n_blk, heads, forced_words, fb.thr,
                                             fb.cand, fb.cand_count, kCandCap, fb.overflow, stream),
                 "compress (filter) kernel launch");
         S3R_HIP(s3r::launch_topk_candidates(qc, kc, fb.cand, fb.cand_count, kCandCap, idx, n_blk, heads, kk, stream),
@@ -460,6 +462,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
                 "pool kernel launch");
     }
     FusedBufs fb;
+    fb.kmax2 = reinterpret_cast<float *>(at(ws, L.kmax2));
     fb.thr = reinterpret_cast<float *>(at(ws, L.thr));
     fb.cand = reinterpret_cast<int32_t *>(at(ws, L.cand));
     fb.cand_count = reinterpret_cast<int *>(at(ws, L.cand_count));
@@ -595,6 +598,7 @@ s3r_status speed3r_compress_attn_topk(const float *qc, const float *kc, const fl
     if (hc > heads) hc = heads;
     size_t off = 6 * arr;
     auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
+    const size_t o_kmax = take(static_cast<size_t>(heads) * s3r::kKeyNormSlots * sizeof(float));
     const size_t o_thr = take(rows * sizeof(float));
     const size_t o_cand = take(rows * 2 * kCandCap * sizeof(int32_t));
     const size_t o_cnt = take(rows * 2 * sizeof(int));
@@ -606,6 +610,7 @@ s3r_status speed3r_compress_attn_topk(const float *qc, const float *kc, const fl
     void *tile[6];
     for (int a = 0; a < 6; ++a) tile[a] = at(ws, a * arr);
     FusedBufs fb;
+    fb.kmax2 = reinterpret_cast<float *>(at(ws, o_kmax));
     fb.thr = reinterpret_cast<float *>(at(ws, o_thr));
     fb.cand = reinterpret_cast<int32_t *>(at(ws, o_cand));
     fb.cand_count = reinterpret_cast<int *>(at(ws, o_cnt));

@@ -309,6 +309,27 @@ def test_compress_attn_topk_random(s3r, oracle, n_blk, heads, k, accurate):
     assert_close(o_comp, ref, TOL["f32"] if accurate else TOL["bf16"], "o_comp")
 
 
+@pytest.mark.parametrize("n_blk,k,offset,noise", [(1000, 16, 0.5, 0.05), (1500, 64, 0.5, 0.05), (700, 8, 0.25, 0.2)])
+def test_compress_attn_topk_large_common_component(s3r, oracle, n_blk, k, offset, noise):
+    """Pooled keys that share a large common vector: all scores of a row sit within a narrow band on
+    top of |q||k| ~ 16..64, so scores computed from the bf16 hi parts alone (error up to 2^-8 |q||k|)
+    would rank them wrongly (typical error 0.03 against a spacing of 0.01 to 0.02 between the scores
+    around rank k).  The sweeps may only use such scores to shortlist; the sets must still be the
+    TopK of fp32-grade scores: nearly every row must match the oracle's set exactly."""
+    rng = np.random.default_rng(n_blk + k)
+    heads = 2
+    base = np.full((heads, 1, 64), offset) * np.sign(rng.standard_normal((heads, 1, 64)))
+    qc = (base * 8 + rng.standard_normal((heads, n_blk, 64))).astype(np.float32)
+    kc = (base + noise * rng.standard_normal((heads, n_blk, 64))).astype(np.float32)
+    vc = rng.standard_normal((heads, n_blk, 64)).astype(np.float32)
+    o_comp, idx = compress_topk_case(s3r, qc, kc, vc, k, False)
+    s64 = oracle.scores(qc.astype(np.float64), kc.astype(np.float64))
+    n_exact, n_tie = check_topk_sets(s64, idx, k)
+    assert n_tie <= (heads * n_blk) // 20, (n_exact, n_tie)
+    ref = oracle.compressed_attn(s64, vc.astype(np.float64), 0.125)
+    assert_close(o_comp, ref, TOL["bf16"], "o_comp")
+
+
 def test_compress_attn_topk_rejects_large_k(s3r):
     z = torch.zeros((1, 128, 64), device="cuda")
     idx = torch.zeros((1, 128, 65), dtype=torch.int32, device="cuda")
