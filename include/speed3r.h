@@ -171,6 +171,10 @@ s3r_status speed3r_compress_attn_scores(const float *qc, const float *kc, const 
  *   qc, kc, vc : in  fp32 [heads][n_blk][head_dim]
  *   o_comp     : out fp32 [heads][n_blk][head_dim]
  *   idx        : out int32 [heads][n_blk][k]
+ *   accurate_pv: nonzero keeps the logits of the compressed softmax and the P.Vc product at fp32
+ *                accuracy (bf16 hi+lo operand pairs; used for S3R_F32 problems); zero computes them
+ *                from single fp16 / bf16 operands (logits good to 2^-10 |q||k|).  The index sets do
+ *                not depend on it: they are decided by fp32 dot products either way.
  * Requires k <= 64 (S3R_ERR_UNSUPPORTED otherwise: use the two entry points around this one).
  * Should the scores of a row tie so massively that its candidate lists run over, the call falls back,
  * on the device, to scores written to library scratch; the result is the same.  Library-held scratch. */

@@ -7,8 +7,9 @@
 // in registers).  In that orientation a lane holds 16 keys of ONE query per 32-key tile, so row
 // max / row sum are in-lane reductions plus one exchange with the lane 32 positions away, and the
 // probabilities already sit in the register order the next MFMA (O^T = Vc^T P^T) wants.
-// Scores use bf16 hi/lo operand pairs (hi*hi + hi*lo + lo*hi): about 2^-16 relative to |q||k|,
-// which keeps the TopK ordering at fp32 quality at bf16 MFMA rates.
+// Scores that are written out, and all scores of fp32 problems, use bf16 hi/lo operand pairs
+// (hi*hi + hi*lo + lo*hi): about 2^-16 relative to |q||k|, which keeps the TopK ordering at fp32
+// quality at bf16 MFMA rates.
 //
 // Waves are specialised.  The kernel streams 4 N_b^2 H bytes of scores out while it streams the
 // pooled keys in.  On this ISA vector loads and stores share one in-flight counter (vmcnt) and
@@ -24,21 +25,26 @@
 //   THRESHOLD mode: same sweep, no score stores.  Each lane keeps the running maximum of each of its
 //     32 score registers, even and odd steps apart: 128 buckets per query (two lanes), every pooled
 //     key falling in exactly one.  The maxima are kept as packed fp16 rounded down (32 registers):
-//     a value below a bucket's true maximum is still a valid bound.  The k-th largest of the 128 bucket maxima is a lower bound of the
-//     query's k-th largest score (k <= 64: that many distinct keys reach it); it is written out per
-//     query.
+//     a value below a bucket's true maximum is still a valid bound.  The k-th largest of the 128
+//     bucket maxima is a lower bound of the query's k-th largest score (k <= 64: that many distinct
+//     keys reach it); it is written out per query.
 //   FILTER mode: the scores are recomputed and the index of every score at or above the query's
 //     bound is appended to that lane's private candidate list (about a hundred per query instead of
 //     N_b).  No softmax, no Vc, no atomics, deterministic.
 // The exact TopK among the candidates is a small kernel of its own (topk.hip), which recomputes their
-// scores as fp32 dot products.  Because of that the filter needs no fp32-grade scores, only a
-// rigorous error bound, and uses the hi parts alone (one MFMA instead of three, half the LDS reads).
-// With 2^-9 the rounding unit of bf16, a hi-only score s~ and the fp32 score s of the same pair differ
-// by at most eps = 2^-8 (1 + small) |q| |k| (two operand roundings plus fp32 accumulation).  Every key
-// of the exact TopK has s >= T, the threshold sweep's bound, hence s~ >= T - eps: the threshold sweep
-// writes T - eps, with eps from the query's own norm and the largest key norm of the head, and the
-// filter keeps every s~ at or above that.  (The threshold sweep itself keeps the three-MFMA scores:
-// they also feed the softmax of the compressed attention, whose logits need the accuracy.)
+// scores as fp32 dot products.  Because of that the sweeps need no fp32-grade scores for TopK, only
+// a rigorous error bound, and work on single fp16 copies of the pooled tensors (one MFMA per tile
+// and channel step instead of three, a third of the LDS reads), scaled per head by powers of two so
+// that fp16's range is never an issue (split.hip).  An fp16 score s~ and the fp32-grade score s of
+// the same pair differ by at most eps = 2^-10 (1 + small) |q||k| (two operand roundings of 2^-11
+// plus fp32 accumulation).  With T the k-th largest bucket maximum of the s~: k keys have
+// s >= T - eps, so every key of the exact TopK has s >= T - eps and s~ >= T - 2 eps.  The threshold
+// sweep therefore writes T - 2 eps, with eps from the query's own norm and the largest key norm of
+// the head (topk_margin), and the filter keeps every s~ at or above that.
+// For bf16 problems the threshold sweep's fp16 scores also feed the softmax of the compressed
+// attention: their 2^-10 |q||k| is an eighth of what rounding the pooled tensors to bf16 would cost
+// (that was measured: 2.7 % error in Oc' on N(0,1) pooled inputs, over the 2 % bar; fp16 stays far
+// inside it).  fp32 problems keep the three-MFMA scores and split P and Vc as well.
 #include "s3r_device.h"
 #include "s3r_kernels.h"
 
@@ -74,6 +80,7 @@ __device__ __forceinline__ float compress_sum_halves(float x)
 }
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 
 // Two floats to packed fp16, rounded toward zero (out-of-range values clamp to the largest finite).
 __device__ __forceinline__ half2_t pack_rtz(float a, float b)
@@ -91,35 +98,53 @@ __device__ __forceinline__ half2_t pk_max(half2_t a, half2_t b)
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-// eps for the query whose hi operands this lane and the lane 32 positions away hold: the largest
-// possible distance between a score computed from the hi parts alone and the fp32-grade score of the
-// same (query, key) pair.  |q| <= |q_hi| (1 + 2^-9); the factor 1.03 covers that, the fp32
-// accumulations, the 2^-16 |q||k| of the three-MFMA scores and the roundings of this computation.
-__device__ __forceinline__ float topk_margin(const bf16x8 (&qhi)[4], const float *__restrict__ kmax2_head, int lane)
+// Sum over the lane pair (lane, lane + 32) that holds one query's operands.
+__device__ __forceinline__ float sum_lane_pair(float x)
 {
-    static_assert(kKeyNormSlots == 64, "one partial maximum per lane");
-    float kmax2 = kmax2_head[lane];
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// L2 norm of the query whose operands this lane and the lane 32 positions away hold.
+__device__ __forceinline__ float query_norm_f16(const bf16x8 (&q)[4])  // registers hold fp16 bits
+{
+    float ss = 0.f;
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) kmax2 = fmaxf(kmax2, __shfl_xor(kmax2, d, 64));
+    for (int s = 0; s < 4; ++s) {
+        const half8_t hv = __builtin_bit_cast(half8_t, q[s]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ss = fmaf(static_cast<float>(hv[i]), static_cast<float>(hv[i]), ss);
+    }
+    return __builtin_sqrtf(sum_lane_pair(ss));
+}
+__device__ __forceinline__ float query_norm_bf16(const bf16x8 (&q)[4])
+{
     float ss = 0.f;
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float f = static_cast<float>(qhi[s][i]);
-            ss = fmaf(f, f, ss);
-        }
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(ss), __float_as_uint(ss), false, false);
-    ss = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-    return (1.03f / 256.f) * __builtin_sqrtf(ss * kmax2);
+        for (int i = 0; i < 8; ++i) ss = fmaf(static_cast<float>(q[s][i]), static_cast<float>(q[s][i]), ss);
+    return __builtin_sqrtf(sum_lane_pair(ss));
+}
+
+// How far the bound of a query must be lowered, in the scaled units of the fp16 tiles: qn = norm of the
+// scaled query, kn = largest norm of a scaled key of the head.  An fp16 score and the fp32-grade score
+// of the same pair differ by at most eps = 2^-10 |q||k| (two operand roundings of 2^-11 each), plus
+// 2^-22 (|q| + |k|) for components that fp16 flushes or holds as subnormals (scaled components are
+// below 1), plus fp32 accumulation; the bound comes from such scores and the filter compares such
+// scores: 2 eps.  The factor 1.03 covers the accumulations, the roundings of the norms and of this
+// expression, and (fp32 problems, whose bound comes from three-MFMA bf16 scores) the 2^-16 of those.
+__device__ __forceinline__ float topk_margin(float qn, float kn)
+{
+    return 1.03f * (1.f / 512.f) * qn * kn + (1.f / 1048576.f) * (qn + kn);
 }
 
 enum CompressMode { kStoreScores = 0, kThreshold = 1, kFilter = 2, kThresholdPipe = 3 };
 
 // What the TopK-in-the-sweep modes read and write besides the operands.
 struct FusedTopkArgs {
-    const float *kmax2;    // [heads][kKeyNormSlots]: partial maxima of the squared L2 norms of the pooled keys (threshold modes)
-    float *thr;            // [heads][n_blk]: what a key's hi-only score must reach to be a candidate
+    const HeadStats *stats;  // [heads]: scale factors of the fp16 tiles, largest scaled key norm (threshold modes)
+    float *thr;            // [heads][n_blk]: what a key's fp16 score (scaled units) must reach to be a candidate
     int32_t *cand;         // [heads][n_blk][2][cap] candidate key indices, one list per lane of a query
     int *cand_count;       // [heads][n_blk][2] entries asked for (may exceed cap: the list is then cut)
     int *overflow;         // set to 1 when any list was cut (the caller then redoes TopK the plain way)
@@ -138,7 +163,7 @@ __device__ __forceinline__ void compress_block(
     const unsigned long long *__restrict__ forced_words, const FusedTopkArgs &ft, unsigned bx, unsigned by)
 {
     // operand arrays staged per step: ks_hi, ks_lo [, vt_hi [, vt_lo]]; the filter sweep: ks_hi alone
-    constexpr int NARR = (MODE == kFilter) ? 1 : (SPLIT_PV ? 4 : 3);
+    constexpr int NARR = (MODE == kFilter) ? 1 : (MODE == kThresholdPipe) ? 2 : (SPLIT_PV ? 4 : 3);
     constexpr int STAGE_ELEMS = 2 * kRowTileElems;   // 64 keys x 64 channels per array: 8 KiB
     constexpr int CPS = NARR * 8;                    // 1 KiB chunks per step, all issued by the loader wave
     constexpr int D = NS - 1;                        // steps in flight
@@ -192,18 +217,20 @@ __device__ __forceinline__ void compress_block(
         // matrix pipe computes the scores of the next half step and the P.V product of the previous
         // one, the vector ALU runs the softmax of the current one.  (Without this every wave runs
         // MFMA and VALU phases one after the other, and the waves of a CU fall into step.)
+        // the fp16 tiles hold scaled values: scores come out multiplied by sq sk
+        const float scale_log2_h = scale_log2 * ft.stats[h].inv_sqsk;
         const int64_t qtile = static_cast<int64_t>(bx) * CW + wave;
         const int64_t qrow = qtile * 32 + (lane & 31);
         const bool wave_active = qtile * 32 < n_blk;
         const int64_t row_id = static_cast<int64_t>(h) * n_blk + (qrow < n_blk ? qrow : 0);
         // Loads.  The keys of step t are read one barrier before its values, so request group t =
         // {keys of step t -> stage t % 3, values of step t - 1 -> stage (t - 1) % 3}, t = 0 .. n_kt,
-        // out-of-range steps clamped (loaded, never used) so that every group has the same 24 chunks of
+        // out-of-range steps clamped (loaded, never used) so that every group has the same 16 chunks of
         // 1 KiB; each wave issues CPW of them.  Group t + 2 is requested right after the barrier that
         // publishes group t; before a barrier a wave waits until only its newest request is in flight.
-        static_assert(NS == 3 && NARR == 3 && 24 % CW == 0, "pipelined sweep: three stages, bf16 values");
-        constexpr int CPW = 24 / CW;
-        const bf16_t *src_k_hi = ks_hi + head_tiles * kRowTileElems, *src_k_lo = ks_lo + head_tiles * kRowTileElems;
+        static_assert(NS == 3 && NARR == 2 && 16 % CW == 0, "pipelined sweep: three stages, hi parts only");
+        constexpr int CPW = 16 / CW;
+        const bf16_t *src_k_hi = ks_hi + head_tiles * kRowTileElems;
         const bf16_t *src_v = vt_hi + head_tiles * kRowTileElems;
         const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0][0]));
         auto issue_group = [&](int t, int kstage, int vstage) __attribute__((always_inline)) {
@@ -211,10 +238,10 @@ __device__ __forceinline__ void compress_block(
 #pragma unroll
             for (int i = 0; i < CPW; ++i) {
                 static_assert(CW == 4, "chunk i * CW + wave: the array (i / 2) is then known at compile time");
-                const int a = i >> 1, c = (i & 1) * 4 + wave;  // chunk i * 4 + wave of 0..7 k_hi, 8..15 k_lo, 16..23 v
-                const bf16_t *src = (a == 0 ? src_k_hi : a == 1 ? src_k_lo : src_v) +
-                                    static_cast<int64_t>(a < 2 ? tk : tv) * STAGE_ELEMS + c * 512 + lane * 8;
-                const unsigned dst = ring_base + static_cast<unsigned>(a < 2 ? kstage : vstage) * (NARR * STAGE_ELEMS * 2) +
+                const int a = i >> 1, c = (i & 1) * 4 + wave;  // chunk i * 4 + wave of 0..7 k_hi, 8..15 v
+                const bf16_t *src = (a == 0 ? src_k_hi : src_v) +
+                                    static_cast<int64_t>(a == 0 ? tk : tv) * STAGE_ELEMS + c * 512 + lane * 8;
+                const unsigned dst = ring_base + static_cast<unsigned>(a == 0 ? kstage : vstage) * (NARR * STAGE_ELEMS * 2) +
                                      (a * 8 + c) * 1024;
                 compress_lds_dma_16(src, __builtin_amdgcn_readfirstlane(dst));
             }
@@ -231,17 +258,14 @@ __device__ __forceinline__ void compress_block(
                 issue_group(j + 2, g_kstage, g_vstage);
             }
         };
-        bf16x8 qhi[4], qlo[4];
+        bf16x8 qhi[4];
         {
             // query tiles past the end of the head's range (inactive waves) still take part in the loads
             // and barriers; they compute on the last tile and write nothing
             const int64_t qt = wave_active ? qtile : (n_blk - 1) / 32;
             const int64_t qb = (head_tiles + qt) * kRowTileElems;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                qhi[s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
-                qlo[s] = *reinterpret_cast<const bf16x8 *>(qs_lo + qb + (s * 64 + lane) * 8);
-            }
+            for (int s = 0; s < 4; ++s) qhi[s] = *reinterpret_cast<const bf16x8 *>(qs_hi + qb + (s * 64 + lane) * 8);
         }
         floatx16 oacc[2];
 #pragma unroll
@@ -257,22 +281,18 @@ __device__ __forceinline__ void compress_block(
 
         // scores of half step mt of the keys in `stage` (only used before the loop)
         auto scores = [&](int stage, int mt, floatx16 &acc) __attribute__((always_inline)) {
-            const bf16_t *k_hi = &ring[stage][0][0], *k_lo = &ring[stage][1][0];
+            const bf16_t *k_hi = &ring[stage][0][0];
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const int off = mt * kRowTileElems + (s * 64 + lane) * 8;
-                const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + off);
-                const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(k_lo + off);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, qhi[s], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qlo[s], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[s], acc, 0, 0, 0);
+                const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + mt * kRowTileElems + (s * 64 + lane) * 8);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a_hi), __builtin_bit_cast(half8_t, qhi[s]), acc, 0, 0, 0);
             }
         };
         // O^T += Vc^T P^T for half step mt of the values in `stage` (only used after the loop)
         auto pv = [&](int stage, int mt, const bf16x8 (&p)[2]) __attribute__((always_inline)) {
-            const bf16_t *v_hi = &ring[stage][2][0];
+            const bf16_t *v_hi = &ring[stage][1][0];
 #pragma unroll
             for (int w = 0; w < 2; ++w)
 #pragma unroll
@@ -292,7 +312,7 @@ __device__ __forceinline__ void compress_block(
             float mx = acc[0];
 #pragma unroll
             for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
-            const float m_tile = compress_max_halves(mx) * scale_log2;
+            const float m_tile = compress_max_halves(mx) * scale_log2_h;
             const bool grow = m_tile > m_run + kCompressRescaleSlack;
             if (__any(grow)) {
                 const float m_new = grow ? m_tile : m_run;
@@ -305,24 +325,22 @@ __device__ __forceinline__ void compress_block(
                     for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
             }
         };
-        // One half step, written out as 16 slots of {one MFMA, one LDS operand read for the MFMA three
-        // slots later, the vector work on one score register}, with a scheduling fence after every
-        // slot so that the order stays as written.  The MFMAs: P.V of the half step before (values in
-        // stage pv_stage, half pv_mt, operands p_in), then the scores of the half step after (keys in
-        // stage k_stage, half k_mt, into acc_next).  The vector work: the softmax of this half step
-        // (scores acc, half mt): bucket maxima, probabilities, their sum, bf16 operands p_out.
+        // One half step, written out as 16 slots of vector work on one score register each, every other
+        // one led by an MFMA and by the LDS operand read for the MFMA three places later, with a
+        // scheduling fence after every slot so that the order stays as written.  The MFMAs: P.V of the
+        // half step before (values in stage pv_stage, half pv_mt, operands p_in), then the scores of the
+        // half step after (keys in stage k_stage, half k_mt, into acc_next).  The vector work: the softmax
+        // of this half step (scores acc, half mt): bucket maxima, probabilities, their sum, bf16 operands
+        // p_out.
         auto half_step = [&](auto forced_tag, unsigned long long fw, int mt, floatx16 &acc, half2_t (&bm)[16],
                              bf16x8 (&p_out)[2], int pv_stage, int pv_mt, const bf16x8 (&p_in)[2], int k_stage,
                              int k_mt, floatx16 &acc_next) __attribute__((always_inline)) {
             constexpr bool FORCED = decltype(forced_tag)::value;
-            const bf16_t *v_src = &ring[pv_stage][2][0] + pv_mt * kRowTileElems + lane * 8;
+            const bf16_t *v_src = &ring[pv_stage][1][0] + pv_mt * kRowTileElems + lane * 8;
             const bf16_t *khi_src = &ring[k_stage][0][0] + k_mt * kRowTileElems + lane * 8;
-            const bf16_t *klo_src = &ring[k_stage][1][0] + k_mt * kRowTileElems + lane * 8;
-            bf16x8 rd[12];  // reads in order of need: V chunks 0..3, then (k_lo, k_hi) of channel steps 0..3
+            bf16x8 rd[8];  // reads in order of need: V chunks 0..3, then the keys of channel steps 0..3
             auto read = [&](int i) __attribute__((always_inline)) {
-                if (i < 4) rd[i] = *reinterpret_cast<const bf16x8 *>(v_src + i * 512);
-                else if ((i & 1) == 0) rd[i] = *reinterpret_cast<const bf16x8 *>(klo_src + ((i - 4) >> 1) * 512);
-                else rd[i] = *reinterpret_cast<const bf16x8 *>(khi_src + ((i - 4) >> 1) * 512);
+                rd[i] = *reinterpret_cast<const bf16x8 *>(i < 4 ? v_src + i * 512 : khi_src + (i - 4) * 512);
             };
             read(0); read(1); read(2);
 #pragma unroll
@@ -332,14 +350,12 @@ __device__ __forceinline__ void compress_block(
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 // ---- matrix pipe
-                if (j < 4) {
-                    oacc[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd[j], p_in[j >> 1], oacc[j & 1], 0, 0, 0);
-                } else {
-                    const int t = j - 4, cs = t / 3, which = t % 3;  // channel step, term of the hi/lo sum
-                    const bf16x8 &a = rd[4 + 2 * cs + (which == 0 ? 0 : 1)];
-                    acc_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, which == 1 ? qlo[cs] : qhi[cs], acc_next, 0, 0, 0);
+                if ((j & 1) == 0) {
+                    const int m = j >> 1;
+                    if (m < 4) oacc[m & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd[m], p_in[m >> 1], oacc[m & 1], 0, 0, 0);
+                    else acc_next = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, rd[m]), __builtin_bit_cast(half8_t, qhi[m - 4]), acc_next, 0, 0, 0);
+                    if (m + 3 < 8) read(m + 3);
                 }
-                if (j + 3 < 12) read(j + 3);
                 // ---- vector ALU, score register j
                 if ((j & 1) == 0) {
                     float a0 = acc[j], a1 = acc[j + 1];
@@ -350,7 +366,7 @@ __device__ __forceinline__ void compress_block(
                     }
                     bm[mt * 8 + (j >> 1)] = pk_max(bm[mt * 8 + (j >> 1)], pack_rtz(a0, a1));
                 }
-                acc[j] = fast_exp2(acc[j] * scale_log2 - m_run);
+                acc[j] = fast_exp2(acc[j] * scale_log2_h - m_run);
                 if (j & 1) {
                     // the pair as bf16 operands of P.V; the row sum adds the same rounded values (one
                     // dot-product instruction per pair)
@@ -431,7 +447,7 @@ __device__ __forceinline__ void compress_block(
                 const auto sw = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(c), static_cast<unsigned>(c), false, false);
                 if (static_cast<int>(sw[0] + sw[1]) >= ft.k) T = trial;
             }
-            const float margin = topk_margin(qhi, ft.kmax2 + h * kKeyNormSlots, lane);  // the filter compares hi-only scores
+            const float margin = topk_margin(query_norm_f16(qhi), ft.stats[h].kn);
             if (qrow < n_blk && g == 0) ft.thr[row_id] = T < 0x007fffffu ? -INFINITY : key_to_float(T) - margin;
         }
         if (qrow < n_blk) {
@@ -533,7 +549,8 @@ __device__ __forceinline__ void compress_block(
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                acc_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd[j], qhi[j], j == 0 ? neg_thr : acc_next, 0, 0, 0);
+                acc_next = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, rd[j]), __builtin_bit_cast(half8_t, qhi[j]),
+                                                                  j == 0 ? neg_thr : acc_next, 0, 0, 0);
                 if (j + 2 < 4) read(j + 2);
 #pragma unroll
                 for (int r = 4 * j; r < 4 * j + 4; ++r)
@@ -558,7 +575,7 @@ __device__ __forceinline__ void compress_block(
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(k_hi + (s * 64 + lane) * 8);
-                sacc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, qhi[s], sacc0, 0, 0, 0);
+                sacc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a_hi), __builtin_bit_cast(half8_t, qhi[s]), sacc0, 0, 0, 0);
             }
         }
         int kst = 0;
@@ -773,8 +790,10 @@ __device__ __forceinline__ void compress_block(
                 }
                 // trial keys below the key of -inf are NaN patterns and never taken: T stays under it exactly
                 // when fewer than k buckets hold a real maximum
-                const float margin = topk_margin(qhi, ft.kmax2 + h * kKeyNormSlots, lane);  // the filter compares hi-only scores
-                if (qrow < n_blk && g == 0) ft.thr[row_id] = T < 0x007fffffu ? -INFINITY : key_to_float(T) - margin;
+                // these scores are in the inputs' own units; the filter works in the scaled units of the fp16 tiles
+                const HeadStats st = ft.stats[h];
+                const float margin = topk_margin(query_norm_bf16(qhi) * st.sq * 1.004f, st.kn);
+                if (qrow < n_blk && g == 0) ft.thr[row_id] = T < 0x007fffffu ? -INFINITY : key_to_float(T) * st.sqsk - margin;
             }
         }
         if (wave_active && qrow < n_blk) {
@@ -860,27 +879,30 @@ hipError_t launch_compress(const void *qs_hi, const void *qs_lo, const void *ks_
 }
 
 hipError_t launch_compress_threshold(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
-                                     const void *vt_hi, const void *vt_lo, float *o_comp, int64_t n_blk,
-                                     int heads, float scale, const unsigned long long *forced_words, int k,
-                                     const float *kmax2, float *thr, int *overflow, hipStream_t stream)
+                                     const void *vt_hi, const void *vt_lo, const void *q_f16, const void *k_f16,
+                                     float *o_comp, int64_t n_blk, int heads, float scale,
+                                     const unsigned long long *forced_words, int k, const HeadStats *stats,
+                                     float *thr, int *overflow, hipStream_t stream)
 {
-    if (k < 1 || k > kFusedTopkMaxK || kmax2 == nullptr) return hipErrorInvalidValue;
+    if (k < 1 || k > kFusedTopkMaxK || stats == nullptr) return hipErrorInvalidValue;
     const float sl = scale * kLog2e;
     FusedTopkArgs ft{};
-    ft.kmax2 = kmax2; ft.thr = thr; ft.overflow = overflow; ft.k = k;
+    ft.stats = stats; ft.thr = thr; ft.overflow = overflow; ft.k = k;
     if (vt_lo != nullptr)
         return run_compress<true, 2, 3, kThreshold>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
-    return run_compress<false, 3, 4, kThresholdPipe>(qs_hi, qs_lo, ks_hi, ks_lo, vt_hi, vt_lo, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
+    // (the fp16 tiles travel through the kernel's bf16-typed operand pointers: same size, same tile layout)
+    return run_compress<false, 3, 4, kThresholdPipe>(q_f16, nullptr, k_f16, nullptr, vt_hi, nullptr, nullptr, 0, o_comp, n_blk, heads, sl, forced_words, ft, stream);
 }
 
-hipError_t launch_compress_filter(const void *qs_hi, const void *ks_hi,
+hipError_t launch_compress_filter(const void *q_f16, const void *k_f16,
                                   int64_t n_blk, int heads, const unsigned long long *forced_words,
                                   const float *thr, int32_t *cand, int *cand_count, int cap, int *overflow,
                                   hipStream_t stream)
 {
     FusedTopkArgs ft{};
     ft.thr = const_cast<float *>(thr); ft.cand = cand; ft.cand_count = cand_count; ft.cap = cap; ft.overflow = overflow;
-    return run_compress<false, 4, 4, kFilter>(qs_hi, nullptr, ks_hi, nullptr, nullptr, nullptr, nullptr, 0, nullptr, n_blk, heads, 0.f, forced_words, ft, stream);
+    // (the fp16 tiles travel through the kernel's bf16-typed operand pointers: same size, same tile layout)
+    return run_compress<false, 4, 4, kFilter>(q_f16, nullptr, k_f16, nullptr, nullptr, nullptr, nullptr, 0, nullptr, n_blk, heads, 0.f, forced_words, ft, stream);
 }
 
 }  // namespace s3r

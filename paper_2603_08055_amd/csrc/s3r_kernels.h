@@ -68,14 +68,21 @@ hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, f
                        void *kb, void *vb, int64_t n_tok, int heads, int block, bool is_bf16,
                        TokenMap map, hipStream_t stream);
 
+// Per-head figures the TopK sweeps need: power-of-two factors that bring the largest |component| of the
+// head's pooled queries (sq) and keys (sk) into [0.5, 1), their product and its inverse, and the largest
+// L2 norm of a scaled pooled key (rounded up).
+struct HeadStats { float sq, sk, sqsk, inv_sqsk, kn; };
+constexpr int kStatSlots = 64;
+// slots: scratch of heads * 3 * kStatSlots words; stats: [heads].
+hipError_t launch_pooled_stats(const float *qc, const float *kc, int64_t n_blk, int heads, void *slots,
+                               HeadStats *stats, hipStream_t stream);
+
 // Pooled fp32 -> bf16 hi/lo operand tiles ([heads][tiles_padded][32 * 64] each, zero padded).
-// vt_lo may be null.
-// kmax2 (optional, [heads][kKeyNormSlots]): the largest of a head's words is the largest squared L2
-// norm of a pooled key of that head.
-constexpr int kKeyNormSlots = 64;
+// vt_lo may be null.  q_f16, k_f16 (optional, need stats): Qc and Kc as fp16 tiles of the same
+// shape, scaled by the head's sq and sk.
 hipError_t launch_split(const float *qc, const float *kc, const float *vc, void *qs_hi, void *qs_lo,
-                        void *ks_hi, void *ks_lo, void *vt_hi, void *vt_lo, int64_t n_blk,
-                        int heads, float *kmax2, hipStream_t stream);
+                        void *ks_hi, void *ks_lo, void *vt_hi, void *vt_lo, void *q_f16, void *k_f16,
+                        const HeadStats *stats, int64_t n_blk, int heads, hipStream_t stream);
 
 // S_guide rows + compressed attention for `heads` heads (operand tiles as written by launch_split).
 // forced_words (optional): bit b of word kt set = pooled key 64 kt + b is a forced block; its
@@ -91,19 +98,21 @@ hipError_t launch_compress(const void *qs_hi, const void *qs_lo, const void *ks_
 
 // TopK without S_guide in memory, k <= kFusedTopkMaxK, in three launches:
 //  threshold: the compression sweep (writes o_comp) that also leaves, per query row, thr [heads][n_blk]:
-//             a lower bound of its k-th largest non-forced score, less the margin by which the filter's
-//             hi-only scores may fall short of the fp32-grade ones (kmax2 as written by launch_split),
-//             and clears *overflow;
-//  filter:    recomputes the scores (hi parts only) and appends the index of every one >= thr to
+//             a lower bound of its k-th largest non-forced score, in the scaled units of the fp16
+//             tiles, less the margin by which fp16 scores may differ from the fp32-grade ones, and
+//             clears *overflow.  bf16 problems (vt_lo null) sweep over the fp16 tiles, fp32 problems
+//             over the bf16 hi/lo tiles;
+//  filter:    recomputes the scores from the fp16 tiles and appends the index of every one >= thr to
 //             cand [heads][n_blk][2][cap] (counts in cand_count [heads][n_blk][2], which may exceed
 //             cap: the list is then cut and *overflow set);
 //  candidates (launch_topk_candidates): exact TopK among the candidates from fp32 dot products.
 constexpr int kFusedTopkMaxK = 64;
 hipError_t launch_compress_threshold(const void *qs_hi, const void *qs_lo, const void *ks_hi, const void *ks_lo,
-                                     const void *vt_hi, const void *vt_lo, float *o_comp, int64_t n_blk,
-                                     int heads, float scale, const unsigned long long *forced_words, int k,
-                                     const float *kmax2, float *thr, int *overflow, hipStream_t stream);
-hipError_t launch_compress_filter(const void *qs_hi, const void *ks_hi,
+                                     const void *vt_hi, const void *vt_lo, const void *q_f16, const void *k_f16,
+                                     float *o_comp, int64_t n_blk, int heads, float scale,
+                                     const unsigned long long *forced_words, int k, const HeadStats *stats,
+                                     float *thr, int *overflow, hipStream_t stream);
+hipError_t launch_compress_filter(const void *q_f16, const void *k_f16,
                                   int64_t n_blk, int heads, const unsigned long long *forced_words,
                                   const float *thr, int32_t *cand, int *cand_count, int cap, int *overflow,
                                   hipStream_t stream);

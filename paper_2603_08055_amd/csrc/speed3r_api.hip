@@ -66,8 +66,8 @@ struct Layout {
     int kk;      // blocks TopK picks per row (among the non-forced ones)
     int width;   // blocks attended per row: kk + n_forced
     int head_chunk;
-    size_t qc, kc, vc, oc, tile[6], idx, idx_merged, forced_clean, forced_words, s, kb, vb, kb_spec, vb_spec;
-    size_t kmax2, thr, cand, cand_count, overflow, blk_len, total;
+    size_t qc, kc, vc, oc, tile[8], idx, idx_merged, forced_clean, forced_words, s, kb, vb, kb_spec, vb_spec;
+    size_t stat_slots, head_stats, thr, cand, cand_count, overflow, blk_len, total;
 };
 
 // n_tok: tokens on the sparse path (the image tokens); n_spec: special tokens (dense rows).
@@ -93,7 +93,7 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, 
     L.kc = take(pooled);
     L.vc = take(pooled);
     L.oc = take(pooled);
-    for (int a = 0; a < 6; ++a) L.tile[a] = take(static_cast<size_t>(heads) * L.tiles * 32 * 64 * 2);
+    for (int a = 0; a < 8; ++a) L.tile[a] = take(static_cast<size_t>(heads) * L.tiles * 32 * 64 * 2);
     L.idx = take(static_cast<size_t>(heads) * L.n_blk * L.kk * sizeof(int32_t));
     L.idx_merged = take(n_forced > 0 ? static_cast<size_t>(heads) * L.n_blk * L.width * sizeof(int32_t) : 0);
     L.forced_clean = take(static_cast<size_t>(n_forced) * sizeof(int32_t));
@@ -107,7 +107,8 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, 
     L.vb_spec = take(spec_tiles);
     // TopK-in-the-sweep buffers, for all heads at once (the sweeps are not chunked)
     const size_t chunk_rows = static_cast<size_t>(heads) * L.n_blk;
-    L.kmax2 = take(static_cast<size_t>(heads) * s3r::kKeyNormSlots * sizeof(float));
+    L.stat_slots = take(static_cast<size_t>(heads) * 3 * s3r::kStatSlots * sizeof(unsigned));
+    L.head_stats = take(static_cast<size_t>(heads) * sizeof(s3r::HeadStats));
     L.thr = take(chunk_rows * sizeof(float));
     L.cand = take(chunk_rows * 2 * kCandCap * sizeof(int32_t));
     L.cand_count = take(chunk_rows * 2 * sizeof(int));
@@ -187,7 +188,8 @@ char *at(void *base, size_t off) { return static_cast<char *>(base) + off; }
 
 // Buffers of the TopK-in-the-sweep path (all null: TopK from scores written to s_buf).
 struct FusedBufs {
-    float *kmax2 = nullptr;   // [heads][kKeyNormSlots]: partial maxima of the pooled keys' squared norms
+    void *stat_slots = nullptr;             // scratch of launch_pooled_stats
+    s3r::HeadStats *head_stats = nullptr;   // [heads]
     float *thr = nullptr;
     int32_t *cand = nullptr;
     int *cand_count = nullptr;
@@ -195,7 +197,7 @@ struct FusedBufs {
 };
 
 // pooled fp32 -> operand tiles -> S_guide / Oc' -> TopK, in head chunks bounded by the S buffer
-s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, void *const tile[6],
+s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, void *const tile[8],
                              float *s_buf, int64_t ld_s, int head_chunk, float *o_comp, int32_t *idx,
                              int64_t n_blk, int64_t tiles, int heads, int kk, float scale,
                              bool accurate_pv, bool want_topk, const unsigned long long *forced_words,
@@ -207,8 +209,12 @@ s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, 
     const bool fused = want_topk && fb.thr != nullptr && kk >= 1 && kk <= s3r::kFusedTopkMaxK && g_kernel_choice != 2;
     {
         StageTimer tm(S3R_STAGE_SPLIT, stream);
+        if (fused)
+            S3R_HIP(s3r::launch_pooled_stats(qc, kc, n_blk, heads, fb.stat_slots, fb.head_stats, stream),
+                    "pooled statistics kernel launch");
         S3R_HIP(s3r::launch_split(qc, kc, vc, tile[0], tile[1], tile[2], tile[3], tile[4],
-                                  accurate_pv ? tile[5] : nullptr, n_blk, heads, fused ? fb.kmax2 : nullptr, stream),
+                                  accurate_pv ? tile[5] : nullptr, fused ? tile[6] : nullptr, fused ? tile[7] : nullptr,
+                                  fused ? fb.head_stats : nullptr, n_blk, heads, stream),
                 "split kernel launch");
     }
     const size_t tile_head = static_cast<size_t>(tiles) * 32 * 64 * 2;  // bytes per head per array
@@ -217,12 +223,12 @@ s3r_status run_compress_topk(const float *qc, const float *kc, const float *vc, 
         {
             StageTimer tm(S3R_STAGE_COMPRESS, stream);
             S3R_HIP(s3r::launch_compress_threshold(tile[0], tile[1], tile[2], tile[3], tile[4],
-                                                   accurate_pv ? tile[5] : nullptr, o_comp, n_blk, heads, scale,
-                                                   forced_words, kk, fb.kmax2, fb.thr, fb.overflow, stream),
+                                                   accurate_pv ? tile[5] : nullptr, tile[6], tile[7], o_comp, n_blk, heads, scale,
+                                                   forced_words, kk, fb.head_stats, fb.thr, fb.overflow, stream),
                     "compress (threshold) kernel launch");
         }
         StageTimer tm(S3R_STAGE_TOPK, stream);
-        S3R_HIP(s3r::launch_compress_filter(tile[0], tile[2], n_blk, heads, forced_words, fb.thr,
+        S3R_HIP(s3r::launch_compress_filter(tile[6], tile[7], n_blk, heads, forced_words, fb.thr,
                                             fb.cand, fb.cand_count, kCandCap, fb.overflow, stream),
                 "compress (filter) kernel launch");
         S3R_HIP(s3r::launch_topk_candidates(qc, kc, fb.cand, fb.cand_count, kCandCap, idx, n_blk, heads, kk, stream),
@@ -445,8 +451,8 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     int32_t *forced_clean = reinterpret_cast<int32_t *>(at(ws, L.forced_clean));
     unsigned long long *forced_words =
         n_forced > 0 ? reinterpret_cast<unsigned long long *>(at(ws, L.forced_words)) : nullptr;
-    void *tile[6];
-    for (int a = 0; a < 6; ++a) tile[a] = at(ws, L.tile[a]);
+    void *tile[8];
+    for (int a = 0; a < 8; ++a) tile[a] = at(ws, L.tile[a]);
     void *kb = mfma ? at(ws, L.kb) : nullptr;
     void *vb = mfma ? at(ws, L.vb) : nullptr;
 
@@ -462,7 +468,8 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
                 "pool kernel launch");
     }
     FusedBufs fb;
-    fb.kmax2 = reinterpret_cast<float *>(at(ws, L.kmax2));
+    fb.stat_slots = at(ws, L.stat_slots);
+    fb.head_stats = reinterpret_cast<s3r::HeadStats *>(at(ws, L.head_stats));
     fb.thr = reinterpret_cast<float *>(at(ws, L.thr));
     fb.cand = reinterpret_cast<int32_t *>(at(ws, L.cand));
     fb.cand_count = reinterpret_cast<int *>(at(ws, L.cand_count));
@@ -563,10 +570,10 @@ s3r_status speed3r_compress_attn_scores(const float *qc, const float *kc, const 
     const int64_t tiles = s3r::pooled_tiles_padded(n_blk);
     const size_t arr = align_up(static_cast<size_t>(heads) * tiles * 32 * 64 * 2);
     void *ws = nullptr;
-    s3r_status st = scratch_get(6 * arr, &ws);
+    s3r_status st = scratch_get(8 * arr, &ws);
     if (st != S3R_OK) return st;
-    void *tile[6];
-    for (int a = 0; a < 6; ++a) tile[a] = at(ws, a * arr);
+    void *tile[8];
+    for (int a = 0; a < 8; ++a) tile[a] = at(ws, a * arr);
     return run_compress_topk(qc, kc, vc, tile, s_guide, ld_s, heads, o_comp, nullptr, n_blk, tiles, heads, 0,
                              resolve_scale(softmax_scale, head_dim), accurate_pv != 0, false, nullptr, FusedBufs{},
                              static_cast<hipStream_t>(stream));
@@ -596,9 +603,10 @@ s3r_status speed3r_compress_attn_topk(const float *qc, const float *kc, const fl
     int64_t hc = static_cast<int64_t>(kScoreBytesCap / per_head_s);
     if (hc < 1) hc = 1;
     if (hc > heads) hc = heads;
-    size_t off = 6 * arr;
+    size_t off = 8 * arr;
     auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
-    const size_t o_kmax = take(static_cast<size_t>(heads) * s3r::kKeyNormSlots * sizeof(float));
+    const size_t o_slots = take(static_cast<size_t>(heads) * 3 * s3r::kStatSlots * sizeof(unsigned));
+    const size_t o_stats = take(static_cast<size_t>(heads) * sizeof(s3r::HeadStats));
     const size_t o_thr = take(rows * sizeof(float));
     const size_t o_cand = take(rows * 2 * kCandCap * sizeof(int32_t));
     const size_t o_cnt = take(rows * 2 * sizeof(int));
@@ -607,10 +615,11 @@ s3r_status speed3r_compress_attn_topk(const float *qc, const float *kc, const fl
     void *ws = nullptr;
     s3r_status st = scratch_get(off, &ws);
     if (st != S3R_OK) return st;
-    void *tile[6];
-    for (int a = 0; a < 6; ++a) tile[a] = at(ws, a * arr);
+    void *tile[8];
+    for (int a = 0; a < 8; ++a) tile[a] = at(ws, a * arr);
     FusedBufs fb;
-    fb.kmax2 = reinterpret_cast<float *>(at(ws, o_kmax));
+    fb.stat_slots = at(ws, o_slots);
+    fb.head_stats = reinterpret_cast<s3r::HeadStats *>(at(ws, o_stats));
     fb.thr = reinterpret_cast<float *>(at(ws, o_thr));
     fb.cand = reinterpret_cast<int32_t *>(at(ws, o_cand));
     fb.cand_count = reinterpret_cast<int *>(at(ws, o_cnt));

@@ -268,13 +268,13 @@ def test_config5_pi3_block128_small(s3r, oracle, topk):
 
 # ---------------------------------------- compressed attention + TopK without S_guide in memory --
 
-def compress_topk_case(s3r, qc, kc, vc, k, accurate):
+def compress_topk_case(s3r, qc, kc, vc, k, accurate, scale=0.0):
     heads, n_blk, _ = qc.shape
     kk = min(k, n_blk)
     o_comp = torch.full((heads, n_blk, 64), float("nan"), device="cuda")
     idx = torch.full((heads, n_blk, kk), -1, dtype=torch.int32, device="cuda")
     s3r.speed3r_compress_attn_topk(torch.from_numpy(qc).cuda(), torch.from_numpy(kc).cuda(), torch.from_numpy(vc).cuda(),
-                                   o_comp, idx, k, accurate_pv=accurate)
+                                   o_comp, idx, k, softmax_scale=scale, accurate_pv=accurate)
     torch.cuda.synchronize()
     return o_comp.cpu().numpy(), idx.cpu().numpy()
 
@@ -327,6 +327,30 @@ def test_compress_attn_topk_large_common_component(s3r, oracle, n_blk, k, offset
     n_exact, n_tie = check_topk_sets(s64, idx, k)
     assert n_tie <= (heads * n_blk) // 20, (n_exact, n_tie)
     ref = oracle.compressed_attn(s64, vc.astype(np.float64), 0.125)
+    assert_close(o_comp, ref, TOL["bf16"], "o_comp")
+
+
+@pytest.mark.parametrize("q_mag,k_mag", [(3e4, 1e-5), (1e-7, 1e-6), (2e6, 5e5), (1.0, 1.0)])
+def test_compress_attn_topk_input_magnitudes(s3r, oracle, q_mag, k_mag):
+    """The sweeps work on fp16 copies of the pooled tensors, scaled per head by a power of two: sets and
+    outputs must not depend on the magnitude of the inputs (far outside fp16's range here), heads of
+    very different magnitude must not disturb each other, and rows of tiny norm beside rows of large
+    norm must still get valid sets."""
+    rng = np.random.default_rng(5)
+    heads, n_blk, k = 3, 900, 16
+    qc, kc, vc = (rng.standard_normal((heads, n_blk, 64)) for _ in range(3))
+    head_mag = np.array([1.0, 1e-3, 64.0])[:, None, None]
+    qc = qc * q_mag * head_mag
+    kc = kc * k_mag / head_mag
+    qc[:, 5] *= 1e-6                     # a query row far below the head's scale
+    kc[:, 7] *= 1e-5                     # and such a key
+    qc, kc, vc = (x.astype(np.float32) for x in (qc, kc, vc))
+    scale = 0.125 / (q_mag * k_mag)
+    o_comp, idx = compress_topk_case(s3r, qc, kc, vc, k, False, scale=scale)
+    s64 = oracle.scores(qc.astype(np.float64), kc.astype(np.float64))
+    n_exact, n_tie = check_topk_sets(s64, idx, k)
+    assert n_tie <= max(1, (heads * n_blk) // 100)
+    ref = oracle.compressed_attn(s64, vc.astype(np.float64), scale)
     assert_close(o_comp, ref, TOL["bf16"], "o_comp")
 
 
