@@ -98,13 +98,6 @@ __device__ __forceinline__ half2_t pk_max(half2_t a, half2_t b)
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-// Sum over the lane pair (lane, lane + 32) that holds one query's operands.
-__device__ __forceinline__ float sum_lane_pair(float x)
-{
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
 // L2 norm of the query whose operands this lane and the lane 32 positions away hold.
 __device__ __forceinline__ float query_norm_f16(const bf16x8 (&q)[4])  // registers hold fp16 bits
 {
@@ -115,7 +108,7 @@ __device__ __forceinline__ float query_norm_f16(const bf16x8 (&q)[4])  // regist
 #pragma unroll
         for (int i = 0; i < 8; ++i) ss = fmaf(static_cast<float>(hv[i]), static_cast<float>(hv[i]), ss);
     }
-    return __builtin_sqrtf(sum_lane_pair(ss));
+    return __builtin_sqrtf(compress_sum_halves(ss));
 }
 __device__ __forceinline__ float query_norm_bf16(const bf16x8 (&q)[4])
 {
@@ -124,7 +117,7 @@ __device__ __forceinline__ float query_norm_bf16(const bf16x8 (&q)[4])
     for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int i = 0; i < 8; ++i) ss = fmaf(static_cast<float>(q[s][i]), static_cast<float>(q[s][i]), ss);
-    return __builtin_sqrtf(sum_lane_pair(ss));
+    return __builtin_sqrtf(compress_sum_halves(ss));
 }
 
 // How far the bound of a query must be lowered, in the scaled units of the fp16 tiles: qn = norm of the
@@ -162,7 +155,9 @@ __device__ __forceinline__ void compress_block(
     int64_t ld_s, float *__restrict__ o_comp, int64_t n_blk, int64_t tiles_padded, float scale_log2,
     const unsigned long long *__restrict__ forced_words, const FusedTopkArgs &ft, unsigned bx, unsigned by)
 {
-    // operand arrays staged per step: ks_hi, ks_lo [, vt_hi [, vt_lo]]; the filter sweep: ks_hi alone
+    // operand arrays staged per step: ks_hi, ks_lo [, vt_hi [, vt_lo]]; the sweeps on fp16 tiles: the keys'
+    // fp16 tile [, vt_hi] (their q and k pointers arrive in the qs_hi / ks_hi arguments: same element size and
+    // tile layout, reinterpreted where the MFMA is issued)
     constexpr int NARR = (MODE == kFilter) ? 1 : (MODE == kThresholdPipe) ? 2 : (SPLIT_PV ? 4 : 3);
     constexpr int STAGE_ELEMS = 2 * kRowTileElems;   // 64 keys x 64 channels per array: 8 KiB
     constexpr int CPS = NARR * 8;                    // 1 KiB chunks per step, all issued by the loader wave
@@ -217,7 +212,8 @@ __device__ __forceinline__ void compress_block(
         // matrix pipe computes the scores of the next half step and the P.V product of the previous
         // one, the vector ALU runs the softmax of the current one.  (Without this every wave runs
         // MFMA and VALU phases one after the other, and the waves of a CU fall into step.)
-        // the fp16 tiles hold scaled values: scores come out multiplied by sq sk
+        // Queries and keys come as fp16 tiles scaled by the head's sq and sk (qs_hi, ks_hi point at them;
+        // qhi, k_hi below hold fp16 bits): scores come out multiplied by sq sk, which the logits undo.
         const float scale_log2_h = scale_log2 * ft.stats[h].inv_sqsk;
         const int64_t qtile = static_cast<int64_t>(bx) * CW + wave;
         const int64_t qrow = qtile * 32 + (lane & 31);
@@ -228,7 +224,7 @@ __device__ __forceinline__ void compress_block(
         // out-of-range steps clamped (loaded, never used) so that every group has the same 16 chunks of
         // 1 KiB; each wave issues CPW of them.  Group t + 2 is requested right after the barrier that
         // publishes group t; before a barrier a wave waits until only its newest request is in flight.
-        static_assert(NS == 3 && NARR == 2 && 16 % CW == 0, "pipelined sweep: three stages, hi parts only");
+        static_assert(NS == 3 && NARR == 2 && 16 % CW == 0, "pipelined sweep: three stages, one key and one value array");
         constexpr int CPW = 16 / CW;
         const bf16_t *src_k_hi = ks_hi + head_tiles * kRowTileElems;
         const bf16_t *src_v = vt_hi + head_tiles * kRowTileElems;
