@@ -328,7 +328,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_stream_kernel(const float *
 
 // Exact TopK among the candidates the filter sweep of the compression kernel left for a row (two
 // lists per row, see compress.hip).  One wave per row.  The scores are recomputed here as plain fp32
-// dot products of the pooled query and key (channels in order, fused multiply-add), so the result
+// dot products of the pooled query and key (fused multiply-adds in a fixed order), so the result
 // does not depend on how the filter computed its own copy beyond which keys became candidates.
 // Ties go to the smaller index; output ascending.  Requires k <= 64 and at most 2 * cap <= 2048
 // candidates (lists that were cut are read up to cap: the caller redoes such launches).
@@ -338,7 +338,8 @@ __global__ __launch_bounds__(64) void topk_candidates_kernel(const float *__rest
                                                             const int *__restrict__ cand_count, int cap,
                                                             int32_t *__restrict__ idx, int n_blk, int k)
 {
-    __shared__ __attribute__((aligned(16))) float qs[64];
+    __shared__ int32_t ids[kCandSlots * 64];
+    __shared__ float sc[kCandSlots * 64];
     __shared__ int32_t ties[kCandSlots * 64];
     __shared__ int32_t win[64];
     const int lane = threadIdx.x;
@@ -349,9 +350,48 @@ __global__ __launch_bounds__(64) void topk_candidates_kernel(const float *__rest
     const int n = n0 + n1;
     const int32_t *l0 = cand + row * 2 * cap, *l1 = l0 + cap;
     const float *kh = kc + head * n_blk * 64;
-    qs[lane] = qc[row * 64 + lane];
-    __syncthreads();
     const int kk = k < n ? k : n;
+
+    // the two lists, one after the other
+#pragma unroll
+    for (int s = 0; s < kCandSlots; ++s)
+        if (s * 64 < n) {  // wave-uniform
+            const int c = s * 64 + lane;
+            if (c < n) ids[c] = c < n0 ? l0[c] : l1[c - n0];
+        }
+    // Scores.  16 lanes per candidate, 4 consecutive channels each, so that a pooled-key row is read as
+    // one contiguous 256 bytes (one lane per candidate would touch 64 cache lines per load
+    // instruction).  Fixed order of operations: 4 fused multiply-adds per lane,
+    // then a butterfly over the 16 lanes.
+    const int sub = lane & 15, quad = lane >> 4;
+    const floatx4 qv = *reinterpret_cast<const floatx4 *>(qc + row * 64 + 4 * sub);
+    __syncthreads();
+    constexpr int U = 8;  // loads in flight per lane: 4 U candidates per pass
+    for (int p0 = 0; p0 < n; p0 += 4 * U) {
+        int32_t j[U];
+        floatx4 kv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = p0 + 4 * u + quad;
+            j[u] = c < n ? ids[c] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            kv[u] = *reinterpret_cast<const floatx4 *>(kh + static_cast<int64_t>(j[u]) * 64 + 4 * sub);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = p0 + 4 * u + quad;
+            float acc = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc = __builtin_fmaf(qv[i], kv[u][i], acc);
+            acc += __shfl_xor(acc, 1, 64);
+            acc += __shfl_xor(acc, 2, 64);
+            acc += __shfl_xor(acc, 4, 64);
+            acc += __shfl_xor(acc, 8, 64);
+            if (sub == 0 && c < n) sc[c] = acc;
+        }
+    }
+    __syncthreads();
 
     uint32_t key[kCandSlots];
     int32_t id[kCandSlots];
@@ -362,18 +402,8 @@ __global__ __launch_bounds__(64) void topk_candidates_kernel(const float *__rest
         if (s * 64 < n) {  // wave-uniform
             const int c = s * 64 + lane;
             if (c < n) {
-                const int32_t j = c < n0 ? l0[c] : l1[c - n0];
-                const floatx4 *kr = reinterpret_cast<const floatx4 *>(kh + static_cast<int64_t>(j) * 64);
-                float acc = 0.f;
-#pragma unroll
-                for (int d4 = 0; d4 < 16; ++d4) {
-                    const floatx4 kv = kr[d4];
-                    const floatx4 qv = *reinterpret_cast<const floatx4 *>(&qs[4 * d4]);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) acc = __builtin_fmaf(qv[i], kv[i], acc);
-                }
-                key[s] = order_key(acc);
-                id[s] = j;
+                key[s] = order_key(sc[c]);
+                id[s] = ids[c];
             }
         }
     }
