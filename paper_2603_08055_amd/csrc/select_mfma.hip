@@ -263,15 +263,16 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     floatx16 sacc[2];
     bf16x8 pb[4];  // probabilities of one unit as MFMA operands
     const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    // S^T = K Q^T of the unit whose K sits in `ks`
+    // S^T = K Q^T of the unit whose K sits in `ks`.  Selection: the two 32-key tiles take turns, so that
+    // no MFMA waits for the one issued just before it (7 % faster where the loop, not the memory
+    // fabric, is the limit: long index rows).  Dense attention: one tile after the other, which the
+    // compiler schedules better around the LDS reads there (the alternating order costs it 15 %).
     auto scores = [&](const bf16_t *ks) __attribute__((always_inline)) {
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(ks + ((mt * 4 + c) * 64 + lane) * 8);
-                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[c], c == 0 ? zero16 : sacc[mt], 0, 0, 0);
-            }
+        for (int i = 0; i < 8; ++i) {
+            const int mt = DENSE ? i >> 2 : i & 1, c = DENSE ? i & 3 : i >> 1;
+            const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(ks + ((mt * 4 + c) * 64 + lane) * 8);
+            sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[c], c == 0 ? zero16 : sacc[mt], 0, 0, 0);
         }
     };
     // keys past the end of a block or of the sequence do not exist
