@@ -264,9 +264,9 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     bf16x8 pb[4];  // probabilities of one unit as MFMA operands
     const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     // S^T = K Q^T of the unit whose K sits in `ks`.  Selection: the two 32-key tiles take turns, so that
-    // no MFMA waits for the one issued just before it (7 % faster where the loop, not the memory
-    // fabric, is the limit: long index rows).  Dense attention: one tile after the other, which the
-    // compiler schedules better around the LDS reads there (the alternating order costs it 15 %).
+    // no MFMA waits for the one issued just before it (3 % faster at 64 blocks per row, 7 % at 288).
+    // Dense attention: one tile after the other; alternating takes a few registers more there, which
+    // costs a workgroup per CU (15 % slower), and with the register count capped the two orders tie.
     auto scores = [&](const bf16_t *ks) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
