@@ -658,3 +658,43 @@ def test_errors_on_device_arguments(s3r):
     with pytest.raises(s3r.Speed3rError) as e:
         s3r.speed3r_sparse_global_attn_ex(q, q, q, q, 64, 2)
     assert e.value.status == s3r.S3R_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------- HIP graph capture --
+
+def test_full_path_replays_from_a_hip_graph(s3r):
+    """With a caller workspace the whole path is kernel launches on the caller's stream and nothing
+    else (no allocation, no host synchronisation, no memset nodes), so it can be captured into a HIP
+    graph.  Every replay, on new inputs written into the captured buffers and with eager work in
+    between, must reproduce the eager result bit for bit."""
+    wl = workloads.config(2)
+    q, k, v = workloads.make_inputs(wl, device="cuda")
+    forced = torch.tensor(workloads.vggt_forced_blocks(wl), dtype=torch.int32, device="cuda")
+    n_forced = forced.numel()
+    ws = torch.empty(s3r.speed3r_workspace_bytes(wl.n_tok, wl.heads, 64, wl.block, wl.topk, s3r.S3R_BF16, n_forced),
+                     dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(q)
+
+    def run(o):
+        s3r.speed3r_sparse_global_attn_ex(q, k, v, o, wl.block, wl.topk, workspace=ws, forced_blocks=forced)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(out)                                     # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run(out)
+    for seed in (11, 12, 13):
+        g = torch.Generator(device="cuda").manual_seed(seed)
+        for t in (q, k, v):
+            t.copy_(torch.randn(t.shape, generator=g, device="cuda").to(t.dtype))
+        eager = torch.empty_like(q)
+        run(eager)                                   # eager work between the replays
+        torch.cuda.synchronize()
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay with seed {seed} differs from the eager call"
