@@ -354,6 +354,37 @@ def test_compress_attn_topk_input_magnitudes(s3r, oracle, q_mag, k_mag):
     assert_close(o_comp, ref, TOL["bf16"], "o_comp")
 
 
+@pytest.mark.parametrize("kind", ["row_norms_6_decades", "heavy_tails", "sparse_vectors", "nearly_equal_scores"])
+def test_compress_attn_topk_hard_distributions(s3r, oracle, kind):
+    """Inputs that stress the shortlist margin of the sweeps: rows whose norms span six decades inside
+    one head (the small ones sit in fp16's subnormal range after the per-head scaling), heavy-tailed
+    components, vectors with few non-zeros, and scores that differ only in the 4th digit (the margin
+    then admits nearly every key and the call must fall back without changing the result)."""
+    rng = np.random.default_rng({"row_norms_6_decades": 1, "heavy_tails": 2, "sparse_vectors": 3, "nearly_equal_scores": 4}[kind])
+    heads, n_blk, k = 2, 1100, 24
+    qc, kc = (rng.standard_normal((heads, n_blk, 64)) for _ in range(2))
+    if kind == "row_norms_6_decades":
+        qc *= 10.0 ** rng.uniform(-6, 0, (heads, n_blk, 1))
+        kc *= 10.0 ** rng.uniform(-6, 0, (heads, n_blk, 1))
+    elif kind == "heavy_tails":
+        qc = rng.standard_t(1.5, (heads, n_blk, 64))
+        kc = rng.standard_t(1.5, (heads, n_blk, 64))
+    elif kind == "sparse_vectors":
+        qc *= rng.random((heads, n_blk, 64)) < 0.08
+        kc *= rng.random((heads, n_blk, 64)) < 0.08
+    else:
+        kc = 1.0 + 1e-4 * kc
+        qc = 1.0 + 0.0 * qc
+    qc, kc = qc.astype(np.float32), kc.astype(np.float32)
+    vc = rng.standard_normal((heads, n_blk, 64)).astype(np.float32)
+    s64 = oracle.scores(qc.astype(np.float64), kc.astype(np.float64))
+    scale = 1.0 / max(1e-30, float(np.abs(s64).max()))          # logits within [-1, 1]
+    o_comp, idx = compress_topk_case(s3r, qc, kc, vc, k, False, scale=scale)
+    check_topk_sets(s64, idx, k)
+    ref = oracle.compressed_attn(s64, vc.astype(np.float64), scale)
+    assert_close(o_comp, ref, TOL["bf16"], f"o_comp {kind}")
+
+
 def test_compress_attn_topk_rejects_large_k(s3r):
     z = torch.zeros((1, 128, 64), device="cuda")
     idx = torch.zeros((1, 128, 65), dtype=torch.int32, device="cuda")
