@@ -62,7 +62,7 @@ typedef enum { S3R_F32 = 0, S3R_BF16 = 1 } s3r_dtype;
 /* Stages of the path, for speed3r_get_stage_ms(). */
 enum {
     S3R_STAGE_POOL = 0,     /* block pooling (+ K/V tile re-layout for the MFMA path) */
-    S3R_STAGE_SPLIT = 1,    /* pooled fp32 -> bf16 hi/lo operand tiles                */
+    S3R_STAGE_SPLIT = 1,    /* pooled fp32 -> operand tiles (+ their per-head statistics) */
     S3R_STAGE_COMPRESS = 2, /* S_guide + compressed attention                         */
     S3R_STAGE_TOPK = 3,     /* per-query-block TopK (incl. its filter sweep)          */
     S3R_STAGE_SELECT = 4,   /* block-sparse attention + merge                         */
