@@ -231,8 +231,40 @@ def dense_attn(q, k, v, scale: float, q_tok=None, want_lse: bool = False):
     return (out, lse) if want_lse else out
 
 
+def compressed_attn_tokens(q, kc, vc, scale: float, q_tok=None) -> np.ndarray:
+    """Variant of eq. 3 in which the queries are NOT pooled: every token's own query attends the
+    pooled keys ("coarse attention of queries against the pooled keys"),
+        O_comp[t, h] = sum_j softmax_j(scale * q[t, h] . Kc[h, j]) Vc[h, j].
+    The block scores S_guide and TopK stay those of the pooled queries (eq. 4).
+    Plain numpy in float64.  Returns [n_q, heads, d] for the tokens q_tok (all if None)."""
+    q = np.asarray(_f32(q), dtype=np.float64)
+    kc = np.asarray(kc, dtype=np.float64)
+    vc = np.asarray(vc, dtype=np.float64)
+    if q_tok is None:
+        q_tok = np.arange(q.shape[0], dtype=np.int64)
+    q_tok = np.asarray(q_tok, dtype=np.int64)
+    heads = q.shape[1]
+    out = np.empty((q_tok.size, heads, q.shape[2]), dtype=np.float64)
+    for h in range(heads):
+        logits = scale * (q[q_tok, h, :] @ kc[h].T)                 # [n_q, n_blk]
+        logits -= logits.max(axis=1, keepdims=True)
+        p = np.exp(logits)
+        p /= p.sum(axis=1, keepdims=True)
+        out[:, h, :] = p @ vc[h]
+    return out
+
+
+def merge_tokens(oc_tok, o_sel_tok, gate_tok) -> np.ndarray:
+    """Eqs. 7, 8 on per-token compressed outputs (no upsampling needed): g * O_comp + (1 - g) * O_sel,
+    g = sigmoid(gate logits) or 1/2 when gate_tok is None.  All arrays [m, heads, d]."""
+    oc_tok = np.asarray(oc_tok, dtype=np.float64)
+    o_sel_tok = np.asarray(o_sel_tok, dtype=np.float64)
+    g = 0.5 if gate_tok is None else 1.0 / (1.0 + np.exp(-np.asarray(gate_tok, dtype=np.float64)))
+    return g * oc_tok + (1.0 - g) * o_sel_tok
+
+
 def gsa_forward(q, k, v, block: int, topk_blocks: int, gate=None, scale=None, rows=None,
-                idx_override=None, forced=None) -> dict:
+                idx_override=None, forced=None, token_queries: bool = False) -> dict:
     """The whole GSA path of Sec. 3.2 for the query blocks `rows` (all if None).
 
     Steps, in the paper's order: pool (compression branch), S_guide (eq. 4),
@@ -241,7 +273,10 @@ def gsa_forward(q, k, v, block: int, topk_blocks: int, gate=None, scale=None, ro
     the selection set to the hybrid of Sec. 3.3: those blocks always, TopK over the
     rest.  `idx_override` replaces the TopK
     result for the selection step (used to score a valid alternative resolution
-    of a near-tie).  Returns every intermediate."""
+    of a near-tie).  `token_queries` switches the compression branch's output to the unpooled-query
+    variant (compressed_attn_tokens): "out" then has the tokens' own compressed outputs merged in,
+    "o_comp_tok" holds them ([n_rows, block, heads, d], zero beyond n_tok) and "o_comp" remains the
+    pooled-query result.  Returns every intermediate."""
     q = _f32(q)
     n_tok, heads, d = q.shape
     n_blk = n_blocks(n_tok, block)
@@ -255,9 +290,21 @@ def gsa_forward(q, k, v, block: int, topk_blocks: int, gate=None, scale=None, ro
     idx = topk(s, kk) if forced is None else topk_with_forced(s, int(topk_blocks), forced)
     use_idx = idx if idx_override is None else np.ascontiguousarray(idx_override, dtype=np.int32)
     o_sel, lse = select_attn(q, k, v, block, use_idx, scale, rows)
-    out = merge(oc, o_sel, gate, n_tok, block, rows)
-    return {"qc": qc, "kc": kc, "vc": vc, "s": s, "o_comp": oc, "idx": idx, "o_sel": o_sel,
-            "lse": lse, "out": out, "rows": rows, "k": kk, "scale": scale}
+    res = {"qc": qc, "kc": kc, "vc": vc, "s": s, "o_comp": oc, "idx": idx, "o_sel": o_sel,
+           "lse": lse, "rows": rows, "k": kk, "scale": scale}
+    if not token_queries:
+        res["out"] = merge(oc, o_sel, gate, n_tok, block, rows)
+        return res
+    tok = (rows[:, None] * block + np.arange(block)[None, :]).reshape(-1)
+    keep = tok < n_tok
+    oc_tok = np.zeros((tok.size, heads, d), dtype=np.float64)
+    oc_tok[keep] = compressed_attn_tokens(q, kc, vc, scale, tok[keep])
+    out = np.zeros_like(oc_tok)
+    g_tok = None if gate is None else _f32(gate, q.shape)[tok[keep]]
+    out[keep] = merge_tokens(oc_tok[keep], o_sel.reshape(tok.size, heads, d)[keep], g_tok)
+    res["o_comp_tok"] = oc_tok.reshape(rows.size, block, heads, d)
+    res["out"] = out.reshape(rows.size, block, heads, d)
+    return res
 
 
 def rows_to_tokens(x_rows, rows, n_tok: int, block: int):

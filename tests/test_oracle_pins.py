@@ -351,6 +351,80 @@ def test_forward_full_topk_and_block1_reduce_to_dense(oracle):
     assert np.allclose(flat_tokens(oracle, res1["out"], n, 1), dense, atol=1e-13)
 
 
+# ---- variant: unpooled queries in the compression branch ("queries against the pooled keys") ----
+
+def test_token_queries_block1_is_dense_attention(oracle):
+    """Block size 1: pooled keys/values are the keys/values themselves, so every token's compressed
+    output is plain softmax attention (library cross-check), and with all blocks selected the merged
+    output is dense attention too."""
+    n, h, d = 50, 2, 8
+    q, k, v = rnd((n, h, d), 60), rnd((n, h, d), 61), rnd((n, h, d), 62)
+    scale = 1 / math.sqrt(d)
+    dense = sdpa64(q, k, v, scale)
+    kc, vc = oracle.pool(k, 1), oracle.pool(v, 1)
+    assert np.allclose(oracle.compressed_attn_tokens(q, kc, vc, scale), dense, atol=1e-13)
+    res = oracle.gsa_forward(q, k, v, 1, n, token_queries=True, gate=rnd((n, h, d), 63))
+    assert np.allclose(flat_tokens(oracle, res["out"], n, 1), dense, atol=1e-13)
+
+
+def test_token_queries_bruteforce_loops(oracle):
+    """Tiny case against pure-Python loops written from the definition."""
+    n, h, d, block = 11, 2, 4, 4
+    q, k, v = rnd((n, h, d), 64), rnd((n, h, d), 65), rnd((n, h, d), 66)
+    scale = 0.37
+    kc, vc = oracle.pool(k, block), oracle.pool(v, block)
+    got = oracle.compressed_attn_tokens(q, kc, vc, scale)
+    n_blk = kc.shape[1]
+    for t in range(n):
+        for hh in range(h):
+            logit = [scale * sum(float(q[t, hh, c]) * kc[hh, j, c] for c in range(d)) for j in range(n_blk)]
+            mx = max(logit)
+            w = [math.exp(x - mx) for x in logit]
+            for c in range(d):
+                want = sum(w[j] * vc[hh, j, c] for j in range(n_blk)) / sum(w)
+                assert abs(got[t, hh, c] - want) < 1e-13
+
+
+def test_token_queries_equal_pooled_queries_when_a_block_shares_one_query(oracle):
+    """If all tokens of a block carry the same query, pooling the queries changes nothing: the two
+    variants must agree, compressed outputs and merged outputs alike (ragged last block included)."""
+    n, h, d, block = 45, 2, 8, 8
+    n_blk = (n + block - 1) // block
+    qb = rnd((n_blk, h, d), 67)
+    q = np.repeat(qb, block, axis=0)[:n].copy()
+    k, v, gate = rnd((n, h, d), 68), rnd((n, h, d), 69), rnd((n, h, d), 70)
+    a = oracle.gsa_forward(q, k, v, block, 3, gate=gate)
+    b = oracle.gsa_forward(q, k, v, block, 3, gate=gate, token_queries=True)
+    assert np.array_equal(a["idx"], b["idx"])
+    up = np.repeat(a["o_comp"].transpose(1, 0, 2)[:, None], block, axis=1)       # [n_blk, block, h, d]
+    valid = (np.arange(n_blk * block) < n).reshape(n_blk, block)
+    assert np.allclose(b["o_comp_tok"][valid], up[valid], atol=1e-13)
+    assert np.allclose(b["out"][valid], a["out"][valid], atol=1e-13)
+
+
+def test_token_queries_invariants(oracle):
+    """Constant values give that constant; permuting the pooled keys and values together changes
+    nothing; the gate at +-80 returns one branch or the other; rows beyond n_tok are zero."""
+    n, h, d, block = 37, 2, 8, 8
+    q, k, v = rnd((n, h, d), 71), rnd((n, h, d), 72), rnd((n, h, d), 73)
+    kc, vc = oracle.pool(k, block), oracle.pool(v, block)
+    ones = np.full_like(vc, 3.5)
+    assert np.allclose(oracle.compressed_attn_tokens(q, kc, ones, 0.2), 3.5, atol=1e-13)
+    perm = np.random.default_rng(0).permutation(kc.shape[1])
+    assert np.allclose(oracle.compressed_attn_tokens(q, kc[:, perm], vc[:, perm], 0.2),
+                       oracle.compressed_attn_tokens(q, kc, vc, 0.2), atol=1e-13)
+    hi = oracle.gsa_forward(q, k, v, block, 2, gate=np.full((n, h, d), 80.0, np.float32), token_queries=True)
+    lo = oracle.gsa_forward(q, k, v, block, 2, gate=np.full((n, h, d), -80.0, np.float32), token_queries=True)
+    assert np.allclose(hi["out"], hi["o_comp_tok"], atol=1e-13)
+    valid = (np.arange(hi["out"].shape[0] * block) < n).reshape(-1, block)
+    assert np.allclose(lo["out"][valid], lo["o_sel"][valid], atol=1e-13)
+    assert np.all(hi["out"][~valid] == 0.0)
+    rows = np.array([4, 1])
+    part = oracle.gsa_forward(q, k, v, block, 2, token_queries=True, rows=rows)
+    full = oracle.gsa_forward(q, k, v, block, 2, token_queries=True)
+    assert np.allclose(part["out"], full["out"][rows], atol=1e-13)
+
+
 def test_forward_agrees_with_bruteforce_route(oracle):
     # Two independently written CPU routes on one small problem (ragged tail, 3 heads).
     n, h, d, b, kk = 77, 3, 8, 8, 3
