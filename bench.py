@@ -110,6 +110,8 @@ def main():
                     help="treat the first N tokens of every view as special tokens (dense rows); not the headline metric")
     ap.add_argument("--forced-vggt", action="store_true",
                     help="force the blocks of the reference view and of every 100th view; not the headline metric")
+    ap.add_argument("--compress-queries", action="store_true",
+                    help="compression branch with every token's own query against the pooled keys; not the headline metric")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense denominator run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget-s", type=float, default=20.0)
@@ -148,13 +150,14 @@ def main():
     dt_code = s3r.S3R_BF16 if wl.dtype == "bf16" else s3r.S3R_F32
     tpv = wl.tokens_per_view if args.special else 0
     ws_bytes = s3r.speed3r_workspace_bytes_ex(wl.n_tok, wl.heads, wl.head_dim, wl.block, wl.topk, dt_code,
-                                              n_forced, tpv, args.special)
+                                              n_forced, tpv, args.special, compress_queries=int(args.compress_queries))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     say(f"workspace {ws_bytes / 2**30:.2f} GiB")
 
     def step():
         s3r.speed3r_sparse_global_attn_ex(q, k, v, out, wl.block, wl.topk, topk_idx=idx, workspace=ws,
-                                          forced_blocks=forced, tokens_per_view=tpv, special_per_view=args.special)
+                                          forced_blocks=forced, tokens_per_view=tpv, special_per_view=args.special,
+                                          compress_queries=int(args.compress_queries))
 
     if args.pmc_calibration:
         src = torch.ones(2 ** 29, dtype=torch.bfloat16, device=dev)      # 1 GiB read + 1 GiB written
@@ -211,7 +214,8 @@ def main():
         "metric": ("sparse global-attn tokens/s at 1000 views" if wl.views == 1000 else "sparse global-attn tokens/s")
                   + (" (VGGT-variant layer: " + ", ".join(x for x in (f"{args.special} special tokens per view" if args.special else "",
                                                                        f"{n_forced} forced blocks" if n_forced else "") if x) + ")"
-                     if args.special or n_forced else ""),
+                     if args.special or n_forced else "")
+                  + (" (compression branch with unpooled queries)" if args.compress_queries else ""),
         "value": wl.n_tok / (ms_per_step * 1e-3),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -225,6 +229,9 @@ def main():
         "hbm_stages": hbm,
         "paper_context": PAPER_CONTEXT,
     }
+    if args.compress_queries:
+        result["config"]["compress_queries"] = 1
+        result["compress_queries_flops_per_step"] = 4.0 * wl.head_dim * float(seq.n_tok) * float(seq.n_blk) * wl.heads
     if args.special:
         result["stage_ms_per_step"]["dense_special_rows"] = stage_ms["dense"] / args.steps
         result["config"]["special_per_view"] = args.special

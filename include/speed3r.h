@@ -96,6 +96,13 @@ typedef struct s3r_params {
      * ceil(grid_w / window).  Windows on the right and bottom edges are cut where the grid ends and hold
      * fewer tokens.  All 0: blocks are runs of `block` consecutive image rows. */
     int grid_h, grid_w, window;
+    /* Queries of the compression branch.  0: pooled like the keys (Q_comp, eq. 3; the paper's form): one
+     * compressed output per block, upsampled to its tokens (eq. 5).  1: every image row's own query
+     * attends the pooled keys, O_comp[t] = softmax_j(scale * q[t] . Kc[j]) Vc, and that row's result is
+     * merged (eq. 8); block scores and TopK remain those of the pooled queries, and the optional
+     * output o_comp remains the per-block result.  bf16 data: Kc and Vc enter this product rounded to
+     * bf16.  Costs n_tok x n_blk attention (at 1000 views several times the rest of the path). */
+    int compress_queries;
     int64_t n_tok;
     int heads, head_dim, block, topk;
     s3r_dtype dtype;

@@ -134,6 +134,18 @@ hipError_t launch_merge_forced(const int32_t *dyn, int k_dyn, const int32_t *for
 hipError_t launch_topk(const float *s_guide, int64_t ld_s, int32_t *idx, int64_t n_blk,
                        int64_t n_rows, int k, const int *run_flag, hipStream_t stream);
 
+// Rarely used arguments of the selection / dense kernels (all optional).
+struct SelectExtras {
+    const float *o_comp_tok = nullptr;  // selection: compressed outputs per query slot [n_tok][heads][64], merged
+                                        // instead of the per-block o_comp (unpooled-query compression branch)
+    float *out_f32 = nullptr;           // dense: fp32 result per query slot [n_tok][heads][64] instead of `out`
+    int64_t kv_head_stride = 0;         // dense, MFMA: elements between the heads' tile arrays (0: n_blk * block * 64)
+    const int32_t *q_blk_len = nullptr; // dense: the query slots come in blocks of q_block slots of which only
+    int q_block = 0;                    //        the first q_blk_len[j] exist (spatial windows)
+    int64_t k_row_stride = 0;           // dense, generic: elements between consecutive keys of one head in k and v,
+    int64_t k_head_stride = 0;          //        and between heads (0, 0: the [rows][heads][64] layout)
+};
+
 struct SelectArgs {
     const void *q, *k, *v;     // [rows][heads][64], the caller's layout
     const void *kb, *vb;       // operand-order tiles of the keys (MFMA path only)
@@ -154,6 +166,7 @@ struct SelectArgs {
     int heads, block, kk;
     float scale;
     bool is_bf16;
+    SelectExtras x;
 };
 
 // One thread per query row, fp32 FMA; any dtype, any supported block size.

@@ -18,7 +18,7 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
                                       T *__restrict__ out, T *__restrict__ o_sel, float *__restrict__ lse,
                                       int64_t n_tok, int64_t n_qblk, int64_t n_keys, int heads, int block,
                                       int kk, float scale_log2, TokenMap qmap, TokenMap kmap,
-                                      int64_t lse_stride, const int32_t *__restrict__ blk_len)
+                                      int64_t lse_stride, const int32_t *__restrict__ blk_len, SelectExtras x)
 {
     __shared__ __attribute__((aligned(16))) float ks[kChunk][64];
     __shared__ __attribute__((aligned(16))) float vs[kChunk][64];
@@ -30,9 +30,13 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
     const int64_t t = i * block + tid;
     // blk_len (spatial windows) describes the key blocks; it applies to the query blocks too when
     // the queries are the same sequence (selection: idx given)
-    const bool active = tid < block && t < n_tok && (blk_len == nullptr || idx == nullptr || tid < blk_len[i]);
+    const bool active = tid < block && t < n_tok && (blk_len == nullptr || idx == nullptr || tid < blk_len[i]) &&
+                        (idx != nullptr || x.q_blk_len == nullptr || t % x.q_block < x.q_blk_len[t / x.q_block]);
     const int64_t trow = qmap.row(active ? t : 0);  // the caller's row of this query
     const int64_t n_kblk = (n_keys + block - 1) / block;
+    // layout of k and v: [rows][heads][64] unless strides are given (dense attention over pooled tensors)
+    const int64_t k_rs = x.k_row_stride != 0 ? x.k_row_stride : static_cast<int64_t>(heads) * 64;
+    const int64_t k_hs = x.k_row_stride != 0 ? x.k_head_stride : 64;
 
     float qr[64], acc[64];
 #pragma unroll
@@ -54,7 +58,7 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
             __syncthreads();
             for (int e = tid; e < nk * 64; e += nthr) {
                 const int r = e >> 6, c = e & 63;
-                const int64_t src = (kmap.row(u0 + c0 + r) * heads + h) * 64 + c;
+                const int64_t src = kmap.row(u0 + c0 + r) * k_rs + h * k_hs + c;
                 ks[r][c] = to_float(k[src]);
                 vs[r][c] = to_float(v[src]);
             }
@@ -106,6 +110,12 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
     const int64_t o = (trow * heads + h) * 64;
     if (lse != nullptr) lse[static_cast<int64_t>(h) * lse_stride + trow] = (m_run + __builtin_log2f(l_run)) * kLn2;
     const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_qblk + i) * 64 : nullptr;
+    if (x.o_comp_tok != nullptr) oc = x.o_comp_tok + (t * heads + h) * 64;  // this query's own compressed output
+    if (x.out_f32 != nullptr) {  // fp32, by query slot
+#pragma unroll
+        for (int c = 0; c < 64; ++c) x.out_f32[(t * heads + h) * 64 + c] = acc[c] * inv;
+        return;
+    }
 #pragma unroll
     for (int c = 0; c < 64; ++c) {
         const float os = acc[c] * inv;
@@ -136,14 +146,14 @@ hipError_t launch_select_generic(const SelectArgs &a, hipStream_t stream)
                            static_cast<const bf16_t *>(a.v), a.idx, a.o_comp,
                            static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
                            static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, n_qblk, a.n_keys, a.heads,
-                           a.block, a.kk, scale_log2, a.qmap, a.kmap, a.lse_stride, a.blk_len);
+                           a.block, a.kk, scale_log2, a.qmap, a.kmap, a.lse_stride, a.blk_len, a.x);
     } else {
         hipLaunchKernelGGL(select_generic_kernel<float>, dim3(static_cast<unsigned>(grid)), dim3(threads),
                            0, stream, static_cast<const float *>(a.q), static_cast<const float *>(a.k),
                            static_cast<const float *>(a.v), a.idx, a.o_comp,
                            static_cast<const float *>(a.gate), static_cast<float *>(a.out),
                            static_cast<float *>(a.o_sel), a.lse, a.n_tok, n_qblk, a.n_keys, a.heads, a.block,
-                           a.kk, scale_log2, a.qmap, a.kmap, a.lse_stride, a.blk_len);
+                           a.kk, scale_log2, a.qmap, a.kmap, a.lse_stride, a.blk_len, a.x);
     }
     return hipGetLastError();
 }

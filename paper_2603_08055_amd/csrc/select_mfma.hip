@@ -82,7 +82,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     bf16_t *__restrict__ out, bf16_t *__restrict__ o_sel, float *__restrict__ lse, int64_t n_tok,
     int64_t n_blk, int heads, int block, int kk, float scale_log2, int64_t set_offset, int64_t n_sets,
     int map_mode, TokenMap qmap, int64_t n_keys, int64_t lse_stride, const bf16_t *__restrict__ kb2,
-    const bf16_t *__restrict__ vb2, int64_t n_keys2, const int32_t *__restrict__ blk_len)
+    const bf16_t *__restrict__ vb2, int64_t n_keys2, const int32_t *__restrict__ blk_len, SelectExtras x)
 {
     constexpr int NW = QW;             // waves per workgroup
     constexpr int CPW = 16 / NW;       // 1 KiB chunks of a unit (8 K + 8 V) issued by each wave
@@ -120,6 +120,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         row_valid = (lane & 31) < block && t < n_tok;
     }
     if (!DENSE && blk_len != nullptr) row_valid = wave * 32 + (lane & 31) < blk_len[qgroup];  // spatial windows
+    if (DENSE && x.q_blk_len != nullptr && row_valid) row_valid = t % x.q_block < x.q_blk_len[t / x.q_block];
     const int64_t trow = qmap.row(row_valid ? t : 0);  // the caller's row of this query
     bf16x8 qb[4];
 #pragma unroll
@@ -156,8 +157,9 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         return static_cast<int>(left < block ? left : block);
     };
 
-    const bf16_t *kb_h = kb + static_cast<int64_t>(h) * n_blk * block * 64;
-    const bf16_t *vb_h = vb + static_cast<int64_t>(h) * n_blk * block * 64;
+    const int64_t kv_head_stride = x.kv_head_stride != 0 ? x.kv_head_stride : n_blk * block * 64;
+    const bf16_t *kb_h = kb + static_cast<int64_t>(h) * kv_head_stride;
+    const bf16_t *vb_h = vb + static_cast<int64_t>(h) * kv_head_stride;
     const bf16_t *kb2_h = DENSE ? kb2 + static_cast<int64_t>(h) * n_units2 * kUnitElems : nullptr;
     const bf16_t *vb2_h = DENSE ? vb2 + static_cast<int64_t>(h) * n_units2 * kUnitElems : nullptr;
     const unsigned ring_base = static_cast<unsigned>(reinterpret_cast<size_t>(&ring[0][0]));
@@ -362,6 +364,19 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         lse[static_cast<int64_t>(h) * lse_stride + trow] = (m_run + __builtin_log2f(l_tot)) * kLn2;
     const int64_t o = (trow * heads + h) * 64;
     const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_blk + t / block) * 64 : nullptr;
+    if (x.o_comp_tok != nullptr) oc = x.o_comp_tok + (t * heads + h) * 64;  // this query's own compressed output
+    if (DENSE && x.out_f32 != nullptr) {  // fp32, by query slot
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                floatx4 o4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o4[i] = oacc[dt][4 * r4 + i] * inv;
+                *reinterpret_cast<floatx4 *>(x.out_f32 + (t * heads + h) * 64 + 32 * dt + 8 * r4 + 4 * g) = o4;
+            }
+        return;
+    }
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
@@ -406,6 +421,7 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
         const double flops_per_set = 4.0 * 64.0 * rows_per_group * static_cast<double>(a.n_keys + a.n_keys2) * a.heads;
         per_launch = static_cast<int64_t>(2e14 / flops_per_set);
         if (per_launch < 1) per_launch = 1;
+        if (per_launch > sets) per_launch = sets;
     }
     if ((per_launch + 8) * a.heads > 0x7fffffffLL) return hipErrorInvalidValue;
     const int map_mode = DENSE ? 0 : 2;
@@ -419,7 +435,7 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
                            static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.block,
                            a.kk, a.scale * kLog2e, s0, ns, map_mode, a.qmap, a.n_keys, a.lse_stride,
                            static_cast<const bf16_t *>(a.kb2), static_cast<const bf16_t *>(a.vb2), a.n_keys2,
-                           a.blk_len);
+                           a.blk_len, a.x);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -67,12 +67,12 @@ struct Layout {
     int width;   // blocks attended per row: kk + n_forced
     int head_chunk;
     size_t qc, kc, vc, oc, tile[8], idx, idx_merged, forced_clean, forced_words, s, kb, vb, kb_spec, vb_spec;
-    size_t stat_slots, head_stats, thr, cand, cand_count, overflow, blk_len, total;
+    size_t stat_slots, head_stats, thr, cand, cand_count, overflow, blk_len, oc_tok, total;
 };
 
 // n_tok: tokens on the sparse path (the image tokens); n_spec: special tokens (dense rows).
 Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, s3r_dtype dtype,
-                   int64_t n_spec = 0)
+                   int64_t n_spec = 0, bool token_queries = false)
 {
     Layout L{};
     L.n_blk = (n_tok + block - 1) / block;
@@ -114,6 +114,8 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, 
     L.cand_count = take(chunk_rows * 2 * sizeof(int));
     L.overflow = take(sizeof(int));
     L.blk_len = take(static_cast<size_t>(L.n_blk) * sizeof(int32_t));
+    // compression branch with unpooled queries: fp32 compressed output per query slot
+    L.oc_tok = take(token_queries ? static_cast<size_t>(L.n_blk) * block * heads * 64 * sizeof(float) : 0);
     L.total = off;
     return L;
 }
@@ -386,7 +388,11 @@ size_t speed3r_workspace_bytes_ex(const s3r_params *p)
         fail(S3R_ERR_INVALID_ARG, "n_forced (%d) must lie in [0, n_blk]", p->n_forced);
         return 0;
     }
-    return make_layout(sp.n_img, p->heads, p->block, p->topk, p->n_forced, p->dtype, sp.n_spec).total;
+    if (p->compress_queries != 0 && p->compress_queries != 1) {
+        fail(S3R_ERR_INVALID_ARG, "compress_queries (%d) must be 0 or 1", p->compress_queries);
+        return 0;
+    }
+    return make_layout(sp.n_img, p->heads, p->block, p->topk, p->n_forced, p->dtype, sp.n_spec, p->compress_queries == 1).total;
 }
 
 int64_t speed3r_num_blocks(const s3r_params *p)
@@ -428,7 +434,12 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     if (st != S3R_OK) return st;
     if (n_forced > (sp.n_img + p->block - 1) / p->block)
         return fail(S3R_ERR_INVALID_ARG, "n_forced (%d) exceeds the number of blocks", n_forced);
-    const Layout L = make_layout(sp.n_img, p->heads, p->block, p->topk, n_forced, p->dtype, sp.n_spec);
+    if (p->compress_queries != 0 && p->compress_queries != 1)
+        return fail(S3R_ERR_INVALID_ARG, "compress_queries (%d) must be 0 or 1", p->compress_queries);
+    const bool token_queries = p->compress_queries == 1;
+    if (token_queries && p->dtype == S3R_BF16 && !mfma_ok(p->dtype, p->block))
+        return fail(S3R_ERR_UNSUPPORTED, "compress_queries = 1 on bf16 data needs the MFMA kernels (kernel choice 1 is set)");
+    const Layout L = make_layout(sp.n_img, p->heads, p->block, p->topk, n_forced, p->dtype, sp.n_spec, token_queries);
     if (!p->workspace) return fail(S3R_ERR_WORKSPACE, "workspace is null (%zu bytes needed)", L.total);
     if ((reinterpret_cast<uintptr_t>(p->workspace) & (kAlign - 1)) != 0)
         return fail(S3R_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
@@ -489,7 +500,32 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
                 "forced-block merge kernel launch");
     }
 
+    float *oc_tok = nullptr;
+    if (token_queries) {
+        // Compression branch with unpooled queries: every image row's own query against the pooled keys,
+        // i.e. dense attention over the pooled tensors (n_blk keys per head), result in fp32 per query
+        // slot.  bf16 problems: the bf16 hi tiles of Kc, Vc written by the split kernel are already in
+        // the unit layout of the MFMA kernel; fp32 problems: the generic kernel on Kc, Vc themselves.
+        oc_tok = reinterpret_cast<float *>(at(ws, L.oc_tok));
+        s3r::SelectArgs c{};
+        c.q = p->q; c.qmap = sp.img; c.n_tok = sp.n_img; c.lse_stride = p->n_tok;
+        c.n_keys = L.n_blk; c.n_blk = (L.n_blk + 63) / 64; c.block = 64; c.heads = p->heads;
+        c.scale = scale; c.is_bf16 = is_bf16;
+        c.x.out_f32 = oc_tok; c.x.q_blk_len = blk_len; c.x.q_block = p->block;
+        StageTimer tm(S3R_STAGE_COMPRESS, stream);
+        if (mfma) {
+            c.kb = tile[2]; c.vb = tile[4];
+            c.x.kv_head_stride = L.tiles * 32 * 64;
+            S3R_HIP(s3r::launch_select_mfma(c, stream), "compression branch (unpooled queries) kernel launch");
+        } else {
+            c.k = kc; c.v = vc;
+            c.x.k_row_stride = 64; c.x.k_head_stride = L.n_blk * 64;
+            S3R_HIP(s3r::launch_select_generic(c, stream), "compression branch (unpooled queries) kernel launch");
+        }
+    }
+
     s3r::SelectArgs a{};
+    a.x.o_comp_tok = oc_tok;
     a.q = p->q; a.k = p->k; a.v = p->v; a.kb = kb; a.vb = vb; a.idx = idx_sel; a.o_comp = oc;
     a.gate = p->gate_logits; a.out = p->out; a.o_sel = p->o_sel; a.lse = p->lse_sel;
     a.n_tok = sp.n_img; a.n_keys = sp.n_img; a.n_blk = L.n_blk; a.lse_stride = p->n_tok;

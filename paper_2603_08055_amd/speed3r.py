@@ -27,7 +27,7 @@ class s3r_params(ctypes.Structure):
     _fields_ = [("q", _vp), ("k", _vp), ("v", _vp), ("out", _vp), ("gate_logits", _vp),
                 ("forced_blocks", _vp), ("n_forced", _int),
                 ("tokens_per_view", _int), ("special_per_view", _int),
-                ("grid_h", _int), ("grid_w", _int), ("window", _int),
+                ("grid_h", _int), ("grid_w", _int), ("window", _int), ("compress_queries", _int),
                 ("n_tok", _i64), ("heads", _int), ("head_dim", _int), ("block", _int),
                 ("topk", _int), ("dtype", _int), ("softmax_scale", _flt), ("topk_idx", _vp),
                 ("lse_sel", _vp), ("o_comp", _vp), ("o_sel", _vp), ("workspace", _vp),
@@ -125,8 +125,10 @@ def speed3r_workspace_bytes(n_tok, heads, head_dim, block, topk, dtype, n_forced
     return int(load().speed3r_workspace_bytes(n_tok, heads, head_dim, block, topk, n_forced, dtype))
 
 
-def _shape_params(n_tok, heads, head_dim, block, topk, dtype, n_forced, tokens_per_view, special_per_view, grid):
+def _shape_params(n_tok, heads, head_dim, block, topk, dtype, n_forced, tokens_per_view, special_per_view, grid,
+                  compress_queries=0):
     p = s3r_params()
+    p.compress_queries = int(compress_queries)
     p.n_tok, p.heads, p.head_dim, p.block, p.topk, p.dtype = n_tok, heads, head_dim, block, topk, dtype
     p.n_forced, p.tokens_per_view, p.special_per_view = n_forced, tokens_per_view, special_per_view
     p.grid_h, p.grid_w, p.window = grid if grid else (0, 0, 0)
@@ -134,9 +136,10 @@ def _shape_params(n_tok, heads, head_dim, block, topk, dtype, n_forced, tokens_p
 
 
 def speed3r_workspace_bytes_ex(n_tok, heads, head_dim, block, topk, dtype, n_forced=0, tokens_per_view=0,
-                               special_per_view=0, grid=None) -> int:
+                               special_per_view=0, grid=None, compress_queries=0) -> int:
     """grid = (grid_h, grid_w, window) for spatial pooling windows."""
-    p = _shape_params(n_tok, heads, head_dim, block, topk, dtype, n_forced, tokens_per_view, special_per_view, grid)
+    p = _shape_params(n_tok, heads, head_dim, block, topk, dtype, n_forced, tokens_per_view, special_per_view, grid,
+                      compress_queries)
     return int(load().speed3r_workspace_bytes_ex(ctypes.byref(p)))
 
 
@@ -159,19 +162,20 @@ def speed3r_selected_per_row(n_tok, block, topk, n_forced=0) -> int:
 def speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, *, gate_logits=None, softmax_scale=0.0,
                                   topk_idx=None, lse_sel=None, o_comp=None, o_sel=None,
                                   forced_blocks=None, tokens_per_view=0, special_per_view=0, grid=None,
-                                  workspace=None, stream=None):
+                                  compress_queries=0, workspace=None, stream=None):
     """The whole path on caller-provided buffers.  `workspace` is a uint8 CUDA tensor of at least
     speed3r_workspace_bytes(...) bytes (allocated here when None).  `forced_blocks` is an int32
     CUDA tensor of ascending distinct block indices attended by every query block.  With
     special_per_view > 0 the first rows of every view of tokens_per_view rows are special tokens
     (dense attention over all rows); the other rows form the sequence of the sparse path.
     grid = (grid_h, grid_w, window) makes the blocks spatial windows of each view's patch grid.
-    Returns the workspace used."""
+    compress_queries = 1: every row's own query (instead of its block's pooled query) attends the
+    pooled keys in the compression branch.  Returns the workspace used."""
     n_tok, heads, head_dim, dt = _qkv(q, k, v)
     n_forced = 0 if forced_blocks is None else int(forced_blocks.numel())
     if workspace is None:
         need = speed3r_workspace_bytes_ex(n_tok, heads, head_dim, block, topk, dt, n_forced, tokens_per_view,
-                                          special_per_view, grid)
+                                          special_per_view, grid, compress_queries)
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)   # 0: the call below says why
     p = s3r_params()
     p.q, p.k, p.v = _dev(q, "q"), _dev(k, "k"), _dev(v, "v")
@@ -181,6 +185,7 @@ def speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, *, gate_logits=None
     p.n_forced = n_forced
     p.tokens_per_view, p.special_per_view = int(tokens_per_view), int(special_per_view)
     p.grid_h, p.grid_w, p.window = grid if grid else (0, 0, 0)
+    p.compress_queries = int(compress_queries)
     p.n_tok, p.heads, p.head_dim, p.block, p.topk, p.dtype = n_tok, heads, head_dim, block, topk, dt
     p.softmax_scale = float(softmax_scale)
     p.topk_idx = _dev(topk_idx, "topk_idx", torch.int32)

@@ -90,7 +90,7 @@ def to_host_f32(t: torch.Tensor) -> np.ndarray:
 
 
 def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "lse", "o_comp", "o_sel"),
-               forced=None, tokens_per_view=0, special_per_view=0, grid=None):
+               forced=None, tokens_per_view=0, special_per_view=0, grid=None, compress_queries=0):
     """One call of the whole path through the C ABI; returns device tensors.  `forced`: ascending
     block indices (host array) every query block attends besides its TopK.  With special tokens
     the block-level outputs are sized for the image-only sequence."""
@@ -114,7 +114,7 @@ def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "ls
     s3r.speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, gate_logits=gate,
                                       softmax_scale=scale, forced_blocks=forced_t,
                                       tokens_per_view=tokens_per_view, special_per_view=special_per_view,
-                                      grid=grid, **bufs)
+                                      grid=grid, compress_queries=compress_queries, **bufs)
     torch.cuda.synchronize()
     res = {"out": out}
     res.update({"idx": bufs.get("topk_idx"), "lse": bufs.get("lse_sel"),
@@ -123,13 +123,14 @@ def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "ls
 
 
 def compare_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, dtype, rows=None, scale=None,
-                        label="", forced=None):
+                        label="", forced=None, token_queries=False):
     """Element-by-element comparison of a device result (tensors from run_device) with the oracle
     on the query blocks `rows` (all when None).  qf, kf, vf, gate_f: host float32 arrays holding
     exactly the device inputs.  TopK sets are checked with the near-tie rule; selection outputs are
     compared against the oracle evaluated on the device's (validated) index sets.  With `forced`
     blocks every device set must hold them all, and what remains is checked as the TopK of the
-    scores with the forced columns removed from the competition."""
+    scores with the forced columns removed from the competition.  `token_queries`: the merged output
+    is checked against the variant whose compression branch keeps every token's own query."""
     n_tok, heads, d = qf.shape
     n_blk = (n_tok + block - 1) // block
     kk = min(topk, n_blk)
@@ -185,12 +186,18 @@ def compare_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, dtype,
         err = float(np.max(np.abs(g - lse_v)))
         assert err <= tol, f"{label} lse abs err {err:.3e} > {tol:.1e}"
         stats["lse_abs"] = err
+    if token_queries:
+        tok = (rows[:, None] * block + np.arange(block)[None, :]).reshape(-1)
+        tok = tok[tok < n_tok]
+        oc_tok = oracle.compressed_attn_tokens(qf, kc, vc, scale, tok)
+        out_v = oracle.merge_tokens(oc_tok, o_sel_v, None if gate_f is None else gate_f[tok])
     stats["out"] = assert_close(tok_sel(dev_res["out"]), out_v, tol, f"{label} out")
     return stats
 
 
 def compare_layer_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, dtype, tokens_per_view,
-                              special_per_view, rows=None, spec_sample=None, forced=None, label=""):
+                              special_per_view, rows=None, spec_sample=None, forced=None, label="",
+                              token_queries=False):
     """Layer with special tokens: the image rows go through compare_with_oracle on the image-only
     sequence (device outputs gathered from their original rows), the special rows (all, or the
     sample `spec_sample` of them) against the oracle's dense attention over every row."""
@@ -205,7 +212,7 @@ def compare_layer_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, 
         sub["lse"] = dev_res["lse"].index_select(1, img_t).contiguous()
     stats = compare_with_oracle(oracle, sub, qf[img_rows], kf[img_rows], vf[img_rows],
                                 None if gate_f is None else gate_f[img_rows], block, topk, dtype, rows=rows,
-                                label=label, forced=forced)
+                                label=label, forced=forced, token_queries=token_queries)
     pick = spec_rows if spec_sample is None else spec_rows[np.asarray(spec_sample, dtype=np.int64)]
     if pick.size:
         ref = oracle.dense_attn(qf, kf, vf, 1.0 / math.sqrt(qf.shape[2]), q_tok=pick)
@@ -215,7 +222,7 @@ def compare_layer_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, 
 
 
 def compare_windows_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, topk, dtype, views, tokens_per_view,
-                                special_per_view, grid, forced=None, label=""):
+                                special_per_view, grid, forced=None, label="", token_queries=False):
     """Blocks = spatial windows: everything against the oracle's explicit-rows route (all rows; sizes
     are kept small), special rows against its dense attention."""
     grid_h, grid_w, window = grid
@@ -239,6 +246,12 @@ def compare_windows_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, topk, dtype
     if stats["topk_tie_resolved"]:
         ref = oracle.gsa_forward_blocks(qf, kf, vf, blocks, topk, gate=gate_f, forced=forced, idx_override=gidx)
     img_rows = np.concatenate(blocks)
+    if token_queries:
+        kc = np.stack([kf[b].astype(np.float64).mean(axis=0) for b in blocks], axis=1)
+        vc = np.stack([vf[b].astype(np.float64).mean(axis=0) for b in blocks], axis=1)
+        oc_tok = oracle.compressed_attn_tokens(qf, kc, vc, 1.0 / math.sqrt(qf.shape[2]), img_rows)
+        ref["out"][img_rows] = oracle.merge_tokens(oc_tok, ref["o_sel"][img_rows],
+                                                   None if gate_f is None else gate_f[img_rows])
     stats["o_comp"] = assert_close(dev_res["o_comp"].cpu().numpy(), ref["o_comp"], tol, f"{label} o_comp")
     take = torch.from_numpy(img_rows).to(dev_res["out"].device)
     stats["o_sel"] = assert_close(to_host_f32(dev_res["o_sel"].index_select(0, take)), ref["o_sel"][img_rows], tol,

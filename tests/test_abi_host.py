@@ -83,6 +83,10 @@ def test_workspace_bytes_and_shape_validation(s3r):
     w_plain = s3r.speed3r_workspace_bytes_ex(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16)
     assert w_plain == s3r.speed3r_workspace_bytes(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16)
     assert s3r.speed3r_workspace_bytes_ex(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16, 0, 1374, 5, (37, 37, 8)) > w_plain
+    # compression branch with unpooled queries: one more fp32 row per query slot and head
+    w_tokq = s3r.speed3r_workspace_bytes_ex(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16, compress_queries=1)
+    assert w_tokq >= w_plain + 215 * 64 * 16 * 64 * 4
+    assert s3r.speed3r_workspace_bytes_ex(n_vggt, 16, 64, 64, 16, s3r.S3R_BF16, compress_queries=2) == 0
     bad = [dict(tokens_per_view=1000, special_per_view=5),                     # 13740 is not a multiple of 1000
            dict(tokens_per_view=1374, special_per_view=1374),                  # nothing left for the sparse path
            dict(tokens_per_view=1374, special_per_view=5, grid=(37, 37, 4)),   # block 64 is not 4 x 4
@@ -124,6 +128,10 @@ def test_workspace_bytes_and_shape_validation(s3r):
     p.forced_blocks, p.n_forced = 0x3000, 3                                                   # more than n_blk = 2
     assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_INVALID_ARG
     p.forced_blocks, p.n_forced = None, 0
+    p.compress_queries = 3
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_INVALID_ARG
+    assert "compress_queries" in s3r.speed3r_last_error()
+    p.compress_queries = 0
     assert lib.speed3r_topk_blocks(None, 8, None, 8, 1, 2, None) == s3r.S3R_ERR_INVALID_ARG
     assert lib.speed3r_compress_attn_scores(0x1000, 0x1000, 0x1000, 0x1000, 6, 0x1000, 8, 1, 64, 0.0, 0,
                                             None) == s3r.S3R_ERR_INVALID_ARG                  # ld_s < n_blk

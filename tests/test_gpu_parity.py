@@ -197,7 +197,8 @@ def test_dense_attn(s3r, oracle, dtype, n_tok, choice):
 
 # ------------------------------------------------------------------------------- end to end --
 
-def end_to_end(s3r, oracle, wl, rows=None, with_gate=False, device_gen="cpu", label=None, forced=None):
+def end_to_end(s3r, oracle, wl, rows=None, with_gate=False, device_gen="cpu", label=None, forced=None,
+               token_queries=False):
     label = label or wl.name
     log(f"{label}: drawing inputs n_tok={wl.n_tok} heads={wl.heads} block={wl.block} topk={wl.topk}")
     q, k, v = workloads.make_inputs(wl, device=device_gen)
@@ -205,11 +206,12 @@ def end_to_end(s3r, oracle, wl, rows=None, with_gate=False, device_gen="cpu", la
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
     gd = None if gate is None else gate.cuda()
     log(f"{label}: device path")
-    res = run_device(s3r, qd, kd, vd, wl.block, wl.topk, gate=gd, forced=forced)
+    res = run_device(s3r, qd, kd, vd, wl.block, wl.topk, gate=gd, forced=forced,
+                     compress_queries=int(token_queries))
     log(f"{label}: oracle")
     stats = compare_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v),
                                 None if gate is None else to_host_f32(gate), wl.block, wl.topk,
-                                wl.dtype, rows=rows, label=label, forced=forced)
+                                wl.dtype, rows=rows, label=label, forced=forced, token_queries=token_queries)
     log(f"{label}: {stats}")
     return stats
 
@@ -498,7 +500,7 @@ def test_forced_blocks_leave_compressed_branch_unchanged(s3r):
 # ------------------------------------- special tokens: dense rows + concat (Sec. 3.2 eqs. 1-2) --
 
 def layer_case(s3r, oracle, wl, special, rows=None, spec_sample=None, with_gate=False, forced=None,
-               device_gen="cpu", label=None):
+               device_gen="cpu", label=None, token_queries=False):
     label = label or f"{wl.name}+{special} special"
     log(f"{label}: drawing inputs n_tok={wl.n_tok} views={wl.views} block={wl.block} topk={wl.topk}")
     q, k, v = workloads.make_inputs(wl, device=device_gen)
@@ -506,12 +508,13 @@ def layer_case(s3r, oracle, wl, special, rows=None, spec_sample=None, with_gate=
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
     gd = None if gate is None else gate.cuda()
     res = run_device(s3r, qd, kd, vd, wl.block, wl.topk, gate=gd, forced=forced,
-                     tokens_per_view=wl.tokens_per_view, special_per_view=special)
+                     tokens_per_view=wl.tokens_per_view, special_per_view=special,
+                     compress_queries=int(token_queries))
     log(f"{label}: oracle")
     stats = compare_layer_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v),
                                       None if gate is None else to_host_f32(gate), wl.block, wl.topk, wl.dtype,
                                       wl.tokens_per_view, special, rows=rows, spec_sample=spec_sample,
-                                      forced=forced, label=label)
+                                      forced=forced, label=label, token_queries=token_queries)
     log(f"{label}: {stats}")
     return res, stats
 
@@ -689,6 +692,97 @@ def test_errors_on_device_arguments(s3r):
     with pytest.raises(s3r.Speed3rError) as e:
         s3r.speed3r_sparse_global_attn_ex(q, q, q, q, 64, 2)
     assert e.value.status == s3r.S3R_ERR_INVALID_ARG
+
+
+# -------------------------- compression branch with unpooled queries (every token's own query) --
+
+def test_token_queries_config1_f32(s3r, oracle):
+    end_to_end(s3r, oracle, workloads.config(1), with_gate=True, token_queries=True, label="config1 token queries")
+    end_to_end(s3r, oracle, workloads.config(1), token_queries=True, label="config1 token queries, no gate")
+
+
+def test_token_queries_vggt_8_views(s3r, oracle):
+    end_to_end(s3r, oracle, workloads.config(2), with_gate=True, token_queries=True, label="config2 token queries")
+
+
+@pytest.mark.parametrize("dtype,block,n_tok,topk", [
+    ("bf16", 64, 1000, 4),       # ragged last block: 15.6 blocks, a quarter of one key unit
+    ("bf16", 64, 64 * 65 + 1, 3),  # 66 pooled keys: a second, nearly empty key unit
+    ("bf16", 128, 128 * 9 + 5, 2),
+    ("bf16", 32, 700, 5),
+    ("bf16", 16, 333, 6),
+    ("f32", 16, 200, 3),
+    ("f32", 128, 900, 2),
+    ("bf16", 64, 50, 2),         # a single short block
+])
+def test_token_queries_edge_cases(s3r, oracle, dtype, block, n_tok, topk):
+    wl = workloads.Workload(f"tokq_{dtype}_{block}_{n_tok}", 1, n_tok, 2, 64, dtype, block, topk, 97, "normal")
+    end_to_end(s3r, oracle, wl, with_gate=True, token_queries=True)
+
+
+def test_token_queries_with_forced_and_special_tokens(s3r, oracle):
+    wl = workloads.config(2, views=6)
+    img = workloads.Workload("img_only", wl.views, wl.tokens_per_view - 5, wl.heads, 64, wl.dtype, wl.block,
+                             wl.topk, wl.seed, wl.kind)
+    forced = workloads.vggt_forced_blocks(img)
+    layer_case(s3r, oracle, wl, 5, forced=forced, with_gate=True, token_queries=True,
+               label="config2/6views+special+reference view, token queries")
+    wl32 = workloads.Workload("tokq_special_f32", 3, 111, 2, 64, "f32", 16, 3, 98, "normal")
+    layer_case(s3r, oracle, wl32, 2, with_gate=True, token_queries=True)
+
+
+@pytest.mark.parametrize("dtype,views,special,grid_h,grid_w,window,topk", [
+    ("bf16", 3, 5, 37, 37, 8, 6),        # cut edge windows: query slots past a window's cells do not exist
+    ("bf16", 2, 3, 11, 13, 4, 4),
+    ("f32", 2, 2, 9, 10, 4, 3),
+])
+def test_token_queries_spatial_windows(s3r, oracle, dtype, views, special, grid_h, grid_w, window, topk):
+    tpv = special + grid_h * grid_w
+    wl = workloads.Workload(f"tokq_windows_{dtype}_{views}x{grid_h}x{grid_w}_w{window}", views, tpv, 2, 64, dtype,
+                            window * window, topk, 99, "normal")
+    q, k, v = workloads.make_inputs(wl)
+    gate = workloads.make_gate_logits(wl)
+    grid = (grid_h, grid_w, window)
+    res = run_device(s3r, q.cuda(), k.cuda(), v.cuda(), wl.block, topk, gate=gate.cuda(),
+                     tokens_per_view=tpv, special_per_view=special, grid=grid, compress_queries=1)
+    stats = compare_windows_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v),
+                                        to_host_f32(gate), topk, dtype, views, tpv, special, grid,
+                                        label=wl.name, token_queries=True)
+    log(f"{wl.name}: {stats}")
+
+
+def test_token_queries_sampled_100_views(s3r, oracle):
+    """100 views (2147 pooled keys per head): sampled query blocks against the oracle."""
+    wl = workloads.config(3)
+    n_blk = (wl.n_tok + wl.block - 1) // wl.block
+    rng = np.random.default_rng(19)
+    rows = np.unique(np.concatenate([[0, n_blk - 1], rng.choice(n_blk, 10, replace=False)]))
+    end_to_end(s3r, oracle, wl, rows=rows, with_gate=True, device_gen="cuda", token_queries=True,
+               label="config3 token queries")
+
+
+def test_token_queries_leave_everything_else_unchanged_and_reject_bad_values(s3r):
+    """Only `out` depends on the option: TopK, the selection branch and the per-block compressed
+    output are those of the default path bit for bit.  Values other than 0 and 1 are refused, and
+    so is the option on bf16 data while the generic kernels are forced."""
+    wl = workloads.config(2, views=3)
+    q, k, v = (t.cuda() for t in workloads.make_inputs(wl))
+    a = run_device(s3r, q, k, v, wl.block, wl.topk)
+    b = run_device(s3r, q, k, v, wl.block, wl.topk, compress_queries=1)
+    for key in ("idx", "lse", "o_comp", "o_sel"):
+        assert torch.equal(a[key], b[key]), key
+    assert not torch.equal(a["out"], b["out"])
+    out = torch.empty_like(q)
+    with pytest.raises(s3r.Speed3rError) as e:
+        s3r.speed3r_sparse_global_attn_ex(q, k, v, out, wl.block, wl.topk, compress_queries=2)
+    assert e.value.status == s3r.S3R_ERR_INVALID_ARG
+    s3r.speed3r_set_kernel_choice(1)
+    try:
+        with pytest.raises(s3r.Speed3rError) as e:
+            s3r.speed3r_sparse_global_attn_ex(q, k, v, out, wl.block, wl.topk, compress_queries=1)
+        assert e.value.status == s3r.S3R_ERR_UNSUPPORTED
+    finally:
+        s3r.speed3r_set_kernel_choice(0)
 
 
 # ------------------------------------------------------------------- HIP graph capture --
