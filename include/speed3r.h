@@ -71,7 +71,7 @@ enum {
 };
 
 typedef struct s3r_params {
-    const void *q, *k, *v;   /* in   [n_tok][heads][head_dim]                                   */
+    const void *q, *k, *v;   /* in   [n_tok][heads][head_dim] (or stride_tok, stride_head below)  */
     void *out;               /* out  [n_tok][heads][head_dim], merged result (eq. 8)            */
     const void *gate_logits; /* in, optional (NULL: g = 1/2), same layout and dtype as q        */
     /* Forced blocks (Sec. 3.3: the fixed global context of the VGGT variant, e.g. all blocks of the
@@ -104,6 +104,11 @@ typedef struct s3r_params {
      * bf16.  Costs n_tok x n_blk attention (at 1000 views several times the rest of the path). */
     int compress_queries;
     int64_t n_tok;
+    /* Layout of q, k and v (all three alike; Sec. 3.2 takes Q, K, V as given, e.g. as three views of one
+     * packed projection output): elements between consecutive rows and between heads; the head_dim
+     * channels of a head are contiguous.  0: the packed default (stride_tok = heads * head_dim,
+     * stride_head = head_dim).  Multiples of 8 elements.  out, gate_logits and o_sel are always packed. */
+    int64_t stride_tok, stride_head;
     int heads, head_dim, block, topk;
     s3r_dtype dtype;
     float softmax_scale;     /* <= 0: 1/sqrt(head_dim).  Used by both branches.                 */

@@ -34,7 +34,8 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ q, cons
                                                    const T *__restrict__ v, float *__restrict__ qc,
                                                    float *__restrict__ kc, float *__restrict__ vc,
                                                    bf16_t *__restrict__ kb, bf16_t *__restrict__ vb,
-                                                   int64_t n_tok, int heads, int64_t n_blk, TokenMap map)
+                                                   int64_t n_tok, int heads, int64_t n_blk, TokenMap map,
+                                                   InStride in)
 {
     constexpr int VS_STRIDE = 72;  // bf16 elements per staged V row (64 + pad: conflict-free columns)
     __shared__ float red[3][32][65];
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ q, cons
         float f[8];
         bf16x8 raw;
         const bool valid = r < len;
-        const int64_t off = (map.row(valid ? t0 + r : t0) * heads + h) * 64 + c * 8;
+        const int64_t off = in.at(map.row(valid ? t0 + r : t0), h, heads) + c * 8;
         if (valid) {
             Load8<T>::run(q + off, f, raw);
 #pragma unroll
@@ -122,13 +123,13 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ q, cons
 template <typename T, int B, bool REPACK>
 static hipError_t run_pool(const void *q, const void *k, const void *v, float *qc, float *kc,
                            float *vc, void *kb, void *vb, int64_t n_tok, int heads, int64_t n_blk,
-                           TokenMap map, hipStream_t stream)
+                           TokenMap map, InStride in, hipStream_t stream)
 {
     const int64_t grid = n_blk * heads;
     hipLaunchKernelGGL((pool_kernel<T, B, REPACK>), dim3(static_cast<unsigned>(grid)), dim3(256), 0,
                        stream, static_cast<const T *>(q), static_cast<const T *>(k),
                        static_cast<const T *>(v), qc, kc, vc, static_cast<bf16_t *>(kb),
-                       static_cast<bf16_t *>(vb), n_tok, heads, n_blk, map);
+                       static_cast<bf16_t *>(vb), n_tok, heads, n_blk, map, in);
     return hipGetLastError();
 }
 
@@ -151,7 +152,7 @@ hipError_t launch_block_lens(TokenMap map, int block, int64_t n_tok, int64_t n_b
 
 hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, float *kc, float *vc,
                        void *kb, void *vb, int64_t n_tok, int heads, int block, bool is_bf16,
-                       TokenMap map, hipStream_t stream)
+                       TokenMap map, InStride in, hipStream_t stream)
 {
     const int64_t n_blk = (n_tok + block - 1) / block;
     if (n_blk * heads > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -159,7 +160,7 @@ hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, f
     const bool repack = kb != nullptr;
     if (repack && !is_bf16) return hipErrorInvalidValue;
 #define S3R_POOL_CASE(TT, BB, RR) \
-    return run_pool<TT, BB, RR>(q, k, v, qc, kc, vc, kb, vb, n_tok, heads, n_blk, map, stream)
+    return run_pool<TT, BB, RR>(q, k, v, qc, kc, vc, kb, vb, n_tok, heads, n_blk, map, in, stream)
     if (is_bf16) {
         switch (block) {
         case 16: if (repack) S3R_POOL_CASE(bf16_t, 16, true); else S3R_POOL_CASE(bf16_t, 16, false);

@@ -55,6 +55,16 @@ struct TokenMap {
     }
 };
 
+// Where row r, head h of the caller's q, k, v starts: element strides between consecutive rows and between
+// heads (the 64 channels of a head are contiguous).  {0, 0}: the packed [rows][heads][64] layout.
+struct InStride {
+    int64_t tok = 0, head = 0;
+    __host__ __device__ int64_t at(int64_t row, int h, int heads) const
+    {
+        return tok != 0 ? row * tok + h * head : (row * heads + h) * 64;
+    }
+};
+
 // blk_len[j] = map.block_len(j, block, n_tok) for every block (the table the attention kernels read
 // when blocks are spatial windows).
 hipError_t launch_block_lens(TokenMap map, int block, int64_t n_tok, int64_t n_blk, int32_t *blk_len,
@@ -66,7 +76,7 @@ hipError_t launch_block_lens(TokenMap map, int block, int64_t n_tok, int64_t n_b
 // sub-sequence `map` picks out of q, k, v; blocks are runs of that sub-sequence.
 hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, float *kc, float *vc,
                        void *kb, void *vb, int64_t n_tok, int heads, int block, bool is_bf16,
-                       TokenMap map, hipStream_t stream);
+                       TokenMap map, InStride in, hipStream_t stream);
 
 // Per-head figures the TopK sweeps need: power-of-two factors that bring the largest |component| of the
 // head's pooled queries (sq) and keys (sk) into [0.5, 1), their product and its inverse, and the largest
@@ -143,11 +153,12 @@ struct SelectExtras {
     const int32_t *q_blk_len = nullptr; // dense: the query slots come in blocks of q_block slots of which only
     int q_block = 0;                    //        the first q_blk_len[j] exist (spatial windows)
     int64_t k_row_stride = 0;           // dense, generic: elements between consecutive keys of one head in k and v,
-    int64_t k_head_stride = 0;          //        and between heads (0, 0: the [rows][heads][64] layout)
+    int64_t k_head_stride = 0;          //        and between heads (0, 0: as q, see `in`)
+    InStride in;                        // layout of q (generic kernels: of k and v too)
 };
 
 struct SelectArgs {
-    const void *q, *k, *v;     // [rows][heads][64], the caller's layout
+    const void *q, *k, *v;     // the caller's layout: [rows][heads][64], or the strides x.in
     const void *kb, *vb;       // operand-order tiles of the keys (MFMA path only)
     const void *kb2 = nullptr, *vb2 = nullptr;  // MFMA dense only: a second key segment, 64-key tiles
     const int32_t *idx;        // [heads][n_blk][kk]; null = every key (dense attention)

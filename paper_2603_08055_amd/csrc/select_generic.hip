@@ -34,14 +34,14 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
                         (idx != nullptr || x.q_blk_len == nullptr || t % x.q_block < x.q_blk_len[t / x.q_block]);
     const int64_t trow = qmap.row(active ? t : 0);  // the caller's row of this query
     const int64_t n_kblk = (n_keys + block - 1) / block;
-    // layout of k and v: [rows][heads][64] unless strides are given (dense attention over pooled tensors)
-    const int64_t k_rs = x.k_row_stride != 0 ? x.k_row_stride : static_cast<int64_t>(heads) * 64;
-    const int64_t k_hs = x.k_row_stride != 0 ? x.k_head_stride : 64;
+    // layout of k and v: that of q unless strides of their own are given (dense attention over pooled tensors)
+    const int64_t k_rs = x.k_row_stride != 0 ? x.k_row_stride : x.in.tok != 0 ? x.in.tok : static_cast<int64_t>(heads) * 64;
+    const int64_t k_hs = x.k_row_stride != 0 ? x.k_head_stride : x.in.tok != 0 ? x.in.head : 64;
 
     float qr[64], acc[64];
 #pragma unroll
     for (int c = 0; c < 64; ++c) {
-        qr[c] = active ? to_float(q[(trow * heads + h) * 64 + c]) : 0.f;
+        qr[c] = active ? to_float(q[x.in.at(trow, h, heads) + c]) : 0.f;
         acc[c] = 0.f;
     }
     float m_run = -1e30f, l_run = 0.f;

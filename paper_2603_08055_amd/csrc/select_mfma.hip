@@ -126,7 +126,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         if (row_valid) {
-            qb[s] = *reinterpret_cast<const bf16x8 *>(q + (trow * heads + h) * 64 + 16 * s + 8 * g);
+            qb[s] = *reinterpret_cast<const bf16x8 *>(q + x.in.at(trow, h, heads) + 16 * s + 8 * g);
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) qb[s][i] = static_cast<bf16_t>(0.f);

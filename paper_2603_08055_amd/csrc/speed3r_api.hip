@@ -426,6 +426,15 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
         !aligned16(p->topk_idx) || !aligned16(p->lse_sel))
         return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     if (p->out == p->q || p->out == p->k || p->out == p->v) return fail(S3R_ERR_INVALID_ARG, "out must not alias an input");
+    // 16-byte vector loads: rows and heads of q, k, v must start on 16-byte boundaries
+    if (p->stride_tok < 0 || p->stride_head < 0 || p->stride_tok % 8 != 0 || p->stride_head % 8 != 0)
+        return fail(S3R_ERR_INVALID_ARG, "stride_tok (%lld) and stride_head (%lld) must be non-negative multiples of 8 elements",
+                    static_cast<long long>(p->stride_tok), static_cast<long long>(p->stride_head));
+    s3r::InStride in{};  // {0, 0} = packed
+    if (p->stride_tok != 0 || p->stride_head != 0) {
+        in.tok = p->stride_tok != 0 ? p->stride_tok : static_cast<int64_t>(p->heads) * 64;
+        in.head = p->stride_head != 0 ? p->stride_head : 64;
+    }
     const int n_forced = p->forced_blocks ? p->n_forced : 0;
     if (p->n_forced < 0 || (p->n_forced > 0 && !p->forced_blocks) || (p->forced_blocks && p->n_forced == 0))
         return fail(S3R_ERR_INVALID_ARG, "forced_blocks and n_forced (%d) must be given together", p->n_forced);
@@ -475,7 +484,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
             S3R_HIP(s3r::launch_block_lens(sp.img, p->block, sp.n_img, L.n_blk, blk_len, stream), "block length kernel launch");
         }
         S3R_HIP(s3r::launch_pool(p->q, p->k, p->v, qc, kc, vc, kb, vb, sp.n_img, p->heads, p->block, is_bf16,
-                                 sp.img, stream),
+                                 sp.img, in, stream),
                 "pool kernel launch");
     }
     FusedBufs fb;
@@ -511,7 +520,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
         c.q = p->q; c.qmap = sp.img; c.n_tok = sp.n_img; c.lse_stride = p->n_tok;
         c.n_keys = L.n_blk; c.n_blk = (L.n_blk + 63) / 64; c.block = 64; c.heads = p->heads;
         c.scale = scale; c.is_bf16 = is_bf16;
-        c.x.out_f32 = oc_tok; c.x.q_blk_len = blk_len; c.x.q_block = p->block;
+        c.x.out_f32 = oc_tok; c.x.q_blk_len = blk_len; c.x.q_block = p->block; c.x.in = in;
         StageTimer tm(S3R_STAGE_COMPRESS, stream);
         if (mfma) {
             c.kb = tile[2]; c.vb = tile[4];
@@ -525,7 +534,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     }
 
     s3r::SelectArgs a{};
-    a.x.o_comp_tok = oc_tok;
+    a.x.o_comp_tok = oc_tok; a.x.in = in;
     a.q = p->q; a.k = p->k; a.v = p->v; a.kb = kb; a.vb = vb; a.idx = idx_sel; a.o_comp = oc;
     a.gate = p->gate_logits; a.out = p->out; a.o_sel = p->o_sel; a.lse = p->lse_sel;
     a.n_tok = sp.n_img; a.n_keys = sp.n_img; a.n_blk = L.n_blk; a.lse_stride = p->n_tok;
@@ -544,12 +553,13 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
         d.out = p->out; d.o_sel = nullptr; d.lse = nullptr;
         d.n_tok = sp.n_spec; d.qmap = sp.spec; d.lse_stride = p->n_tok;
         d.heads = p->heads; d.block = p->block; d.kk = 0; d.scale = scale; d.is_bf16 = is_bf16;
+        d.x.in = in;
         if (mfma) {
             void *kb_s = at(ws, L.kb_spec), *vb_s = at(ws, L.vb_spec);
             {
                 StageTimer tm(S3R_STAGE_POOL, stream);
                 S3R_HIP(s3r::launch_pool(p->q, p->k, p->v, nullptr, nullptr, nullptr, kb_s, vb_s, sp.n_spec, p->heads,
-                                         64, true, sp.spec, stream),
+                                         64, true, sp.spec, in, stream),
                         "pool kernel launch (special tokens)");
             }
             d.kb = kb; d.vb = vb; d.n_keys = sp.n_img; d.n_blk = L.n_blk;      // image keys, then special keys
@@ -589,7 +599,7 @@ s3r_status speed3r_pool_blocks(const void *q, const void *k, const void *v, floa
     if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     StageTimer tm(S3R_STAGE_POOL, static_cast<hipStream_t>(stream));
     S3R_HIP(s3r::launch_pool(q, k, v, qc, kc, vc, nullptr, nullptr, n_tok, heads, block, dtype == S3R_BF16,
-                             s3r::TokenMap{}, static_cast<hipStream_t>(stream)),
+                             s3r::TokenMap{}, s3r::InStride{}, static_cast<hipStream_t>(stream)),
             "pool kernel launch");
     return S3R_OK;
 }
@@ -704,7 +714,7 @@ s3r_status speed3r_select_attn(const void *q, const void *k, const void *v, cons
         a.vb = at(ws, blocked);
         StageTimer tm(S3R_STAGE_POOL, s);
         S3R_HIP(s3r::launch_pool(q, k, v, nullptr, nullptr, nullptr, const_cast<void *>(a.kb),
-                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s3r::TokenMap{}, s),
+                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s3r::TokenMap{}, s3r::InStride{}, s),
                 "pool kernel launch");
     }
     a.q = q; a.k = k; a.v = v; a.idx = idx; a.o_comp = o_comp; a.gate = gate_logits; a.out = out;
@@ -738,7 +748,7 @@ s3r_status speed3r_dense_attn(const void *q, const void *k, const void *v, void 
         a.vb = at(ws, blocked);
         StageTimer tm(S3R_STAGE_POOL, s);
         S3R_HIP(s3r::launch_pool(q, k, v, nullptr, nullptr, nullptr, const_cast<void *>(a.kb),
-                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s3r::TokenMap{}, s),
+                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s3r::TokenMap{}, s3r::InStride{}, s),
                 "pool kernel launch");
     }
     a.q = q; a.k = k; a.v = v; a.idx = nullptr; a.o_comp = nullptr; a.gate = nullptr; a.out = out;

@@ -28,7 +28,7 @@ class s3r_params(ctypes.Structure):
                 ("forced_blocks", _vp), ("n_forced", _int),
                 ("tokens_per_view", _int), ("special_per_view", _int),
                 ("grid_h", _int), ("grid_w", _int), ("window", _int), ("compress_queries", _int),
-                ("n_tok", _i64), ("heads", _int), ("head_dim", _int), ("block", _int),
+                ("n_tok", _i64), ("stride_tok", _i64), ("stride_head", _i64), ("heads", _int), ("head_dim", _int), ("block", _int),
                 ("topk", _int), ("dtype", _int), ("softmax_scale", _flt), ("topk_idx", _vp),
                 ("lse_sel", _vp), ("o_comp", _vp), ("o_sel", _vp), ("workspace", _vp),
                 ("workspace_bytes", ctypes.c_size_t), ("stream", _vp)]
@@ -109,6 +109,22 @@ def _dev(t, name, dtype=None):
     return t.data_ptr()
 
 
+def _strided_qkv(q, k, v):
+    """data_ptrs and the common (stride_tok, stride_head) of q, k, v: CUDA tensors [n_tok, heads, head_dim]
+    whose channels are contiguous (views of a packed projection output are fine)."""
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if not (isinstance(t, torch.Tensor) and t.is_cuda):
+            raise TypeError(f"{name} must be a tensor on the GPU")
+        if t.stride(2) != 1 and t.shape[2] > 1:
+            raise TypeError(f"the channels of {name} must be contiguous")
+    st = (q.stride(0), q.stride(1))
+    if (k.stride(0), k.stride(1)) != st or (v.stride(0), v.stride(1)) != st:
+        raise TypeError("q, k and v must share their row and head strides")
+    if q.is_contiguous():
+        st = (0, 0)
+    return q.data_ptr(), k.data_ptr(), v.data_ptr(), st
+
+
 def _stream(stream):
     if stream is None:
         stream = torch.cuda.current_stream()
@@ -170,7 +186,8 @@ def speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, *, gate_logits=None
     (dense attention over all rows); the other rows form the sequence of the sparse path.
     grid = (grid_h, grid_w, window) makes the blocks spatial windows of each view's patch grid.
     compress_queries = 1: every row's own query (instead of its block's pooled query) attends the
-    pooled keys in the compression branch.  Returns the workspace used."""
+    pooled keys in the compression branch.  q, k, v may be strided views with contiguous channels
+    and common strides (slices of one packed tensor).  Returns the workspace used."""
     n_tok, heads, head_dim, dt = _qkv(q, k, v)
     n_forced = 0 if forced_blocks is None else int(forced_blocks.numel())
     if workspace is None:
@@ -178,7 +195,7 @@ def speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, *, gate_logits=None
                                           special_per_view, grid, compress_queries)
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)   # 0: the call below says why
     p = s3r_params()
-    p.q, p.k, p.v = _dev(q, "q"), _dev(k, "k"), _dev(v, "v")
+    p.q, p.k, p.v, (p.stride_tok, p.stride_head) = _strided_qkv(q, k, v)
     p.out = _dev(out, "out", q.dtype)
     p.gate_logits = _dev(gate_logits, "gate_logits", q.dtype)
     p.forced_blocks = _dev(forced_blocks, "forced_blocks", torch.int32) if n_forced else None

@@ -100,7 +100,7 @@ def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "ls
     n_blk = s3r.speed3r_num_blocks(n_tok, heads, d, block, topk, dt_code, tokens_per_view, special_per_view, grid)
     kk = s3r.speed3r_selected_per_row(n_blk * block, block, topk, n_forced)
     dev = q.device
-    out = torch.full_like(q, float("nan"))
+    out = torch.full(q.shape, float("nan"), dtype=q.dtype, device=dev)     # packed whatever the strides of q
     bufs = {}
     if "idx" in want:
         bufs["topk_idx"] = torch.full((heads, n_blk, kk), -1, dtype=torch.int32, device=dev)
@@ -109,7 +109,7 @@ def run_device(s3r, q, k, v, block, topk, gate=None, scale=0.0, want=("idx", "ls
     if "o_comp" in want:
         bufs["o_comp"] = torch.full((heads, n_blk, d), float("nan"), dtype=torch.float32, device=dev)
     if "o_sel" in want:
-        bufs["o_sel"] = torch.full_like(q, float("nan"))
+        bufs["o_sel"] = torch.full(q.shape, float("nan"), dtype=q.dtype, device=dev)
     forced_t = None if n_forced == 0 else torch.from_numpy(np.asarray(forced, dtype=np.int32)).to(dev)
     s3r.speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, gate_logits=gate,
                                       softmax_scale=scale, forced_blocks=forced_t,

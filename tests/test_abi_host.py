@@ -132,6 +132,13 @@ def test_workspace_bytes_and_shape_validation(s3r):
     assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_INVALID_ARG
     assert "compress_queries" in s3r.speed3r_last_error()
     p.compress_queries = 0
+    for bad_strides in ((-128, 64), (132, 64), (128, 4)):
+        p.stride_tok, p.stride_head = bad_strides
+        assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_INVALID_ARG
+        assert "stride" in s3r.speed3r_last_error()
+    p.stride_tok, p.stride_head = 384, 64                                                     # rows of a packed qkv tensor
+    assert lib.speed3r_sparse_global_attn_ex(ctypes.byref(p)) == s3r.S3R_ERR_WORKSPACE
+    p.stride_tok, p.stride_head = 0, 0
     assert lib.speed3r_topk_blocks(None, 8, None, 8, 1, 2, None) == s3r.S3R_ERR_INVALID_ARG
     assert lib.speed3r_compress_attn_scores(0x1000, 0x1000, 0x1000, 0x1000, 6, 0x1000, 8, 1, 64, 0.0, 0,
                                             None) == s3r.S3R_ERR_INVALID_ARG                  # ld_s < n_blk

@@ -785,6 +785,70 @@ def test_token_queries_leave_everything_else_unchanged_and_reject_bad_values(s3r
         s3r.speed3r_set_kernel_choice(0)
 
 
+# ------------------------------------------------- strided q, k, v (views of a packed tensor) --
+
+@pytest.mark.parametrize("dtype,block,views,tpv,special,topk,grid,layout", [
+    ("bf16", 64, 4, 333, 0, 4, None, "packed_qkv"),        # [n_tok, 3, heads, 64]: slices of one projection output
+    ("bf16", 64, 4, 333, 5, 4, None, "packed_qkv"),        # special tokens: both pooling launches and the dense rows
+    ("bf16", 128, 3, 500, 0, 2, None, "head_major"),       # [heads, n_tok, 64] seen as [n_tok, heads, 64]
+    ("bf16", 16, 2, 3 + 11 * 13, 3, 4, (11, 13, 4), "padded_heads"),   # windows; heads padded to 96 channels
+    ("f32", 64, 2, 300, 7, 2, None, "packed_qkv"),         # generic kernels: k and v follow the same strides
+    ("f32", 16, 3, 111, 0, 3, None, "head_major"),
+])
+def test_strided_inputs_match_packed_inputs(s3r, oracle, dtype, block, views, tpv, special, topk, grid, layout):
+    """q, k, v given as strided views: every output equals, bit for bit, that of the same call on packed
+    copies (which the other tests hold against the oracle); `out` is checked against the oracle as well
+    on the plain layouts."""
+    wl = workloads.Workload(f"strided_{dtype}_{block}_{layout}", views, tpv, 2, 64, dtype, block, topk, 101, "normal")
+    q, k, v = (t.cuda() for t in workloads.make_inputs(wl))
+    gate = workloads.make_gate_logits(wl).cuda()
+    n, h = wl.n_tok, wl.heads
+    if layout == "packed_qkv":
+        big = torch.stack([q, k, v], dim=1).contiguous()               # [n, 3, h, 64]
+        qs, ks, vs = big[:, 0], big[:, 1], big[:, 2]
+    elif layout == "head_major":
+        qs, ks, vs = (t.permute(1, 0, 2).contiguous().permute(1, 0, 2) for t in (q, k, v))
+    else:
+        pad = [torch.zeros((n, h, 96), dtype=q.dtype, device="cuda") for _ in range(3)]
+        for dst, src in zip(pad, (q, k, v)):
+            dst[:, :, 16:80] = src
+        qs, ks, vs = (t[:, :, 16:80] for t in pad)
+    assert not qs.is_contiguous() and torch.equal(qs, q)
+    kw = dict(gate=gate, tokens_per_view=tpv if (special or grid) else 0, special_per_view=special, grid=grid)
+    ref = run_device(s3r, q, k, v, block, topk, **kw)
+    for cq in (0, 1):
+        want = ref if cq == 0 else run_device(s3r, q, k, v, block, topk, compress_queries=1, **kw)
+        got = run_device(s3r, qs, ks, vs, block, topk, compress_queries=cq, **kw)
+        for key in ("idx", "o_comp", "out"):
+            assert torch.equal(got[key], want[key]), (key, cq)
+        for key in ("o_sel", "lse"):                                      # special rows stay NaN in both
+            assert torch.equal(torch.nan_to_num(got[key].float(), nan=-7.0),
+                               torch.nan_to_num(want[key].float(), nan=-7.0)), (key, cq)
+    if grid is None:
+        res = run_device(s3r, qs, ks, vs, block, topk, **kw)
+        host = [to_host_f32(t) for t in (q, k, v, gate)]
+        if special:
+            stats = compare_layer_with_oracle(oracle, res, *host, block, topk, dtype, tpv, special, label=wl.name)
+        else:
+            stats = compare_with_oracle(oracle, res, *host, block, topk, dtype, label=wl.name)
+        log(f"{wl.name}: {stats}")
+
+
+def test_strides_are_validated(s3r):
+    q = torch.zeros((128, 2, 64), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty_like(q)
+    big = torch.zeros((128, 2, 68), dtype=torch.bfloat16, device="cuda")     # rows of 68 elements: not 16-byte steps
+    with pytest.raises(s3r.Speed3rError) as e:
+        s3r.speed3r_sparse_global_attn_ex(big[:, :, :64], big[:, :, :64], big[:, :, :64], out, 64, 2)
+    assert e.value.status == s3r.S3R_ERR_INVALID_ARG and "stride" in str(e.value)
+    with pytest.raises(TypeError):                                             # channels not contiguous
+        t = torch.zeros((128, 64, 2), dtype=torch.bfloat16, device="cuda").permute(0, 2, 1)
+        s3r.speed3r_sparse_global_attn_ex(t, t, t, out, 64, 2)
+    with pytest.raises(TypeError):                                             # q and k laid out differently
+        kt = q.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+        s3r.speed3r_sparse_global_attn_ex(q, kt, q, out, 64, 2)
+
+
 # ------------------------------------------------------------------- HIP graph capture --
 
 def test_full_path_replays_from_a_hip_graph(s3r):
