@@ -75,7 +75,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 //         same operand order), and a query block fills only the first `block` of a wave's 32 query
 //         columns.  At 16 FLOP per byte of K/V such blocks are bound by the gather alone, so the
 //         empty MFMA columns cost nothing.
-template <int QW, bool DENSE, int NS, bool SMALL>
+// EXTRA : the rarely used arguments of SelectExtras are honoured (a second instantiation, so that the plain
+//         path carries none of their instructions: they cost the selection kernel 2.4 % when always compiled in)
+template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA>
 __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ kb, const bf16_t *__restrict__ vb,
     const int32_t *__restrict__ idx, const float *__restrict__ o_comp, const bf16_t *__restrict__ gate,
@@ -120,13 +122,15 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         row_valid = (lane & 31) < block && t < n_tok;
     }
     if (!DENSE && blk_len != nullptr) row_valid = wave * 32 + (lane & 31) < blk_len[qgroup];  // spatial windows
-    if (DENSE && x.q_blk_len != nullptr && row_valid) row_valid = t % x.q_block < x.q_blk_len[t / x.q_block];
+    if constexpr (EXTRA && DENSE)
+        if (x.q_blk_len != nullptr && row_valid) row_valid = t % x.q_block < x.q_blk_len[t / x.q_block];
     const int64_t trow = qmap.row(row_valid ? t : 0);  // the caller's row of this query
     bf16x8 qb[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         if (row_valid) {
-            qb[s] = *reinterpret_cast<const bf16x8 *>(q + x.in.at(trow, h, heads) + 16 * s + 8 * g);
+            const int64_t qo = EXTRA ? x.in.at(trow, h, heads) : (trow * heads + h) * 64;
+            qb[s] = *reinterpret_cast<const bf16x8 *>(q + qo + 16 * s + 8 * g);
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) qb[s][i] = static_cast<bf16_t>(0.f);
@@ -157,7 +161,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         return static_cast<int>(left < block ? left : block);
     };
 
-    const int64_t kv_head_stride = x.kv_head_stride != 0 ? x.kv_head_stride : n_blk * block * 64;
+    const int64_t kv_head_stride = (EXTRA && x.kv_head_stride != 0) ? x.kv_head_stride : n_blk * block * 64;
     const bf16_t *kb_h = kb + static_cast<int64_t>(h) * kv_head_stride;
     const bf16_t *vb_h = vb + static_cast<int64_t>(h) * kv_head_stride;
     const bf16_t *kb2_h = DENSE ? kb2 + static_cast<int64_t>(h) * n_units2 * kUnitElems : nullptr;
@@ -364,8 +368,9 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         lse[static_cast<int64_t>(h) * lse_stride + trow] = (m_run + __builtin_log2f(l_tot)) * kLn2;
     const int64_t o = (trow * heads + h) * 64;
     const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_blk + t / block) * 64 : nullptr;
-    if (x.o_comp_tok != nullptr) oc = x.o_comp_tok + (t * heads + h) * 64;  // this query's own compressed output
-    if (DENSE && x.out_f32 != nullptr) {  // fp32, by query slot
+    if constexpr (EXTRA)
+        if (x.o_comp_tok != nullptr) oc = x.o_comp_tok + (t * heads + h) * 64;  // this query's own compressed output
+    if (EXTRA && DENSE && x.out_f32 != nullptr) {  // fp32, by query slot
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
@@ -408,8 +413,8 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         }
 }
 
-template <int QW, bool DENSE, int NS, bool SMALL = false>
-static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
+template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA>
+static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
 {
     const int64_t rows_per_group = 32 * QW;
     const int64_t groups = DENSE ? (a.n_tok + rows_per_group - 1) / rows_per_group : a.n_blk;
@@ -428,7 +433,7 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
     for (int64_t s0 = 0; s0 < sets; s0 += per_launch) {
         const int64_t ns = (sets - s0 < per_launch) ? sets - s0 : per_launch;
         const int64_t grid = (map_mode == 2) ? (ns + 7) / 8 * 8 * a.heads : ns * a.heads;
-        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL>), dim3(static_cast<unsigned>(grid)),
+        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA>), dim3(static_cast<unsigned>(grid)),
                            dim3(QW * 64), 0, stream, static_cast<const bf16_t *>(a.q),
                            static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
                            a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
@@ -440,6 +445,16 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+template <int QW, bool DENSE, int NS, bool SMALL = false>
+static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
+{
+    const SelectExtras &x = a.x;
+    const bool extra = x.o_comp_tok != nullptr || x.out_f32 != nullptr || x.kv_head_stride != 0 ||
+                       x.q_blk_len != nullptr || x.in.tok != 0;
+    return extra ? run_select_x<QW, DENSE, NS, SMALL, true>(a, stream)
+                 : run_select_x<QW, DENSE, NS, SMALL, false>(a, stream);
 }
 
 hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
