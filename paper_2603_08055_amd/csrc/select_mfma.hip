@@ -125,17 +125,46 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     if constexpr (EXTRA && DENSE)
         if (x.q_blk_len != nullptr && row_valid) row_valid = t % x.q_block < x.q_blk_len[t / x.q_block];
     const int64_t trow = qmap.row(row_valid ? t : 0);  // the caller's row of this query
+    // Q.  Dense attention (rings of three stages, two units on their way while one is worked on) loads it with
+    // inline-asm loads that carry their wait in the same statement: the compiler does not count the LDS-direct
+    // loads of the key units, so a wait of its own for a load it knows of comes out as vmcnt(0), and with Q
+    // loaded in plain code that wait lands in front of the first MFMA of the loop, in every iteration, where it
+    // holds each unit back until the requests for the units after it have landed too (3.6 % of the dense
+    // kernel's time).  That load is issued once the first units have been requested (its wait covers them as
+    // well); rows that do not exist read row 0.  The selection kernels wait for every load at the head of
+    // each step anyway (two stages), and a plain early load of Q is 1 % faster there.
     bf16x8 qb[4];
+    if constexpr (!DENSE) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        if (row_valid) {
-            const int64_t qo = EXTRA ? x.in.at(trow, h, heads) : (trow * heads + h) * 64;
-            qb[s] = *reinterpret_cast<const bf16x8 *>(q + qo + 16 * s + 8 * g);
-        } else {
+        for (int s = 0; s < 4; ++s) {
+            if (row_valid) {
+                const int64_t qo = EXTRA ? x.in.at(trow, h, heads) : (trow * heads + h) * 64;
+                qb[s] = *reinterpret_cast<const bf16x8 *>(q + qo + 16 * s + 8 * g);
+            } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) qb[s][i] = static_cast<bf16_t>(0.f);
+                for (int i = 0; i < 8; ++i) qb[s][i] = static_cast<bf16_t>(0.f);
+            }
         }
     }
+    auto load_q_dense = [&]() __attribute__((always_inline)) {
+        typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+        u32x4 q0, q1, q2, q3;
+        const int64_t qo = EXTRA ? x.in.at(trow, h, heads) : (trow * heads + h) * 64;
+        const bf16_t *qrow = q + qo + 8 * g;
+        asm volatile("global_load_dwordx4 %0, %4, off\n\t"
+                     "global_load_dwordx4 %1, %4, off offset:32\n\t"
+                     "global_load_dwordx4 %2, %4, off offset:64\n\t"
+                     "global_load_dwordx4 %3, %4, off offset:96\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(q0), "=&v"(q1), "=&v"(q2), "=&v"(q3)
+                     : "v"(qrow)
+                     : "memory");
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        qb[0] = __builtin_bit_cast(bf16x8, row_valid ? q0 : zero);
+        qb[1] = __builtin_bit_cast(bf16x8, row_valid ? q1 : zero);
+        qb[2] = __builtin_bit_cast(bf16x8, row_valid ? q2 : zero);
+        qb[3] = __builtin_bit_cast(bf16x8, row_valid ? q3 : zero);
+    };
     const int64_t n_units1 = SMALL ? (n_blk + (1 << bpu_shift) - 1) >> bpu_shift
                                    : (n_keys + kUnitKeys - 1) / kUnitKeys;  // units of the first key segment
     const int64_t n_units2 = (n_keys2 + kUnitKeys - 1) / kUnitKeys;    // dense only: second segment
@@ -344,6 +373,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     };
 
     for (int s = 0; s < D && s < n_steps; ++s) issue(s, s);  // D < NS: stage = s
+    if constexpr (DENSE) load_q_dense();
 
     int stage = NS - 1, stage_ahead = D - 1;  // stages of unit s and of unit s + D, stepped at the loop head
     for (int s = 0; s < n_steps; ++s) {
