@@ -77,7 +77,8 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 //         empty MFMA columns cost nothing.
 // EXTRA : the rarely used arguments of SelectExtras are honoured (a second instantiation, so that the plain
 //         path carries none of their instructions: they cost the selection kernel 2.4 % when always compiled in)
-template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA>
+// ASMQ  : Q is loaded by inline asm after the first unit requests instead of by plain loads (see below)
+template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ>
 __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ kb, const bf16_t *__restrict__ vb,
     const int32_t *__restrict__ idx, const float *__restrict__ o_comp, const bf16_t *__restrict__ gate,
@@ -132,9 +133,11 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     // holds each unit back until the requests for the units after it have landed too (3.6 % of the dense
     // kernel's time).  That load is issued once the first units have been requested (its wait covers them as
     // well); rows that do not exist read row 0.  The selection kernels wait for every load at the head of
-    // each step anyway (two stages), and a plain early load of Q is 1 % faster there.
+    // each step anyway (two stages), and a plain early load of Q is 1 % faster there, except on long index
+    // rows (ASMQ chooses).
     bf16x8 qb[4];
-    if constexpr (!DENSE) {
+    constexpr bool kAsmQ = ASMQ;
+    if constexpr (!kAsmQ) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             if (row_valid) {
@@ -373,7 +376,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     };
 
     for (int s = 0; s < D && s < n_steps; ++s) issue(s, s);  // D < NS: stage = s
-    if constexpr (DENSE) load_q_dense();
+    if constexpr (kAsmQ) load_q_dense();
 
     int stage = NS - 1, stage_ahead = D - 1;  // stages of unit s and of unit s + D, stepped at the loop head
     for (int s = 0; s < n_steps; ++s) {
@@ -443,7 +446,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         }
 }
 
-template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA>
+template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ>
 static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
 {
     const int64_t rows_per_group = 32 * QW;
@@ -463,7 +466,7 @@ static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
     for (int64_t s0 = 0; s0 < sets; s0 += per_launch) {
         const int64_t ns = (sets - s0 < per_launch) ? sets - s0 : per_launch;
         const int64_t grid = (map_mode == 2) ? (ns + 7) / 8 * 8 * a.heads : ns * a.heads;
-        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA>), dim3(static_cast<unsigned>(grid)),
+        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ>), dim3(static_cast<unsigned>(grid)),
                            dim3(QW * 64), 0, stream, static_cast<const bf16_t *>(a.q),
                            static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
                            a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
@@ -477,14 +480,14 @@ static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
     return hipSuccess;
 }
 
-template <int QW, bool DENSE, int NS, bool SMALL = false>
+template <int QW, bool DENSE, int NS, bool SMALL = false, bool ASMQ = DENSE>
 static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
 {
     const SelectExtras &x = a.x;
     const bool extra = x.o_comp_tok != nullptr || x.out_f32 != nullptr || x.kv_head_stride != 0 ||
                        x.q_blk_len != nullptr || x.in.tok != 0;
-    return extra ? run_select_x<QW, DENSE, NS, SMALL, true>(a, stream)
-                 : run_select_x<QW, DENSE, NS, SMALL, false>(a, stream);
+    return extra ? run_select_x<QW, DENSE, NS, SMALL, true, ASMQ>(a, stream)
+                 : run_select_x<QW, DENSE, NS, SMALL, false, ASMQ>(a, stream);
 }
 
 hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
@@ -500,7 +503,11 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
         return hipErrorInvalidValue;
     }
     if (a.n_keys != a.n_tok || a.n_keys2 != 0) return hipErrorInvalidValue;  // selection: keys = the query sequence
-    if (a.block == 64) return run_select<2, false, 2>(a, stream);
+    // Long index rows (forced blocks, which every query block shares and the L2 keeps) are bound by the loop
+    // itself rather than by the memory fabric; letting each unit's arithmetic overlap the next unit's loads
+    // (Q loaded by inline asm, see the kernel) is 3.5 % faster there and 1 % slower on short rows.
+    if (a.block == 64)
+        return a.kk > 96 ? run_select<2, false, 2, false, true>(a, stream) : run_select<2, false, 2>(a, stream);
     if (a.block == 128) return run_select<4, false, 2>(a, stream);
     if (a.block == 16 || a.block == 32) return run_select<1, false, 2, true>(a, stream);
     return hipErrorInvalidValue;
