@@ -493,8 +493,10 @@ static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
 hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
 {
     if (!a.is_bf16 || a.kb == nullptr || a.vb == nullptr) return hipErrorInvalidValue;
-    // One query block per workgroup, two LDS stages: measured best on MI355X (deeper rings only add
-    // queueing once the memory fabric is saturated).
+    // One query block per workgroup, two LDS stages: measured best on MI355X.  A third stage is slower even
+    // where it costs no occupancy (blocks of 128 tokens: 18.2 against 16.8 ms on 300 views, top-64): the fabric
+    // is saturated already, and the units on their way (3 workgroups x 2 units x 16 KiB on each of an XCD's 32
+    // CUs) then take up most of that XCD's 4 MiB of L2.
     if (a.qmap.period != 0 && a.n_tok > 0x7fffffffLL) return hipErrorInvalidValue;
     if (a.idx == nullptr) {
         if (a.n_keys2 > 0 && (a.kb2 == nullptr || a.vb2 == nullptr)) return hipErrorInvalidValue;
@@ -508,8 +510,10 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
     // (Q loaded by inline asm, see the kernel) is 3.5 % faster there and 1 % slower on short rows.
     if (a.block == 64)
         return a.kk > 96 ? run_select<2, false, 2, false, true>(a, stream) : run_select<2, false, 2>(a, stream);
-    if (a.block == 128) return run_select<4, false, 2>(a, stream);
-    if (a.block == 16 || a.block == 32) return run_select<1, false, 2, true>(a, stream);
+    // measured: the inline-asm Q load is 2 % faster for blocks of 128 and 32 tokens, 2 % slower for 16
+    if (a.block == 128) return run_select<4, false, 2, false, true>(a, stream);
+    if (a.block == 32) return run_select<1, false, 2, true, true>(a, stream);
+    if (a.block == 16) return run_select<1, false, 2, true>(a, stream);
     return hipErrorInvalidValue;
 }
 
