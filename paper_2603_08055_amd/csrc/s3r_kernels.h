@@ -155,6 +155,12 @@ struct SelectExtras {
     int64_t k_row_stride = 0;           // dense, generic: elements between consecutive keys of one head in k and v,
     int64_t k_head_stride = 0;          //        and between heads (0, 0: as q, see `in`)
     InStride in;                        // layout of q (generic kernels: of k and v too)
+    // dense, MFMA, blocks of 64 or 128 tokens: the key units are cut into n_split equal shares, each worked on
+    // by workgroups of its own; share i leaves its normalised result at out_f32 [i][n_tok][heads][64] and the
+    // base-2 logarithm of its sum of exponentials at part_lse [i][n_tok][heads] (launch_dense_combine adds
+    // the shares up).  For few query rows: more, shorter workgroups spread evenly over the CUs.
+    int n_split = 0;
+    float *part_lse = nullptr;
 };
 
 struct SelectArgs {
@@ -179,6 +185,11 @@ struct SelectArgs {
     bool is_bf16;
     SelectExtras x;
 };
+
+// out[qmap.row(t)][h][:] = sum_i w_i part_o[i][t][h][:], w_i = 2^(part_lse[i][t][h]) / sum_j 2^(part_lse[j][t][h]):
+// the softmax over all keys from its shares (out: bf16 [rows][heads][64]).
+hipError_t launch_dense_combine(const float *part_o, const float *part_lse, int n_split, int64_t n_tok, int heads,
+                                TokenMap qmap, void *out, hipStream_t stream);
 
 // One thread per query row, fp32 FMA; any dtype, any supported block size.
 hipError_t launch_select_generic(const SelectArgs &a, hipStream_t stream);

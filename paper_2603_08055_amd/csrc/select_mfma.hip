@@ -97,12 +97,19 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     int h;
-    int64_t set;  // query group (query block for selection) of this workgroup
+    int64_t set;    // query group (query block for selection) of this workgroup
+    int split = 0;  // dense attention in key splits: which share of the key units
     {
         const int64_t bid = blockIdx.x;
         if (map_mode == 0) {  // head fastest
             h = static_cast<int>(bid % heads);
             set = bid / heads;
+            if constexpr (EXTRA && DENSE) {  // then the key splits of a query group
+                if (x.n_split > 1) {
+                    split = static_cast<int>(set % x.n_split);
+                    set /= x.n_split;
+                }
+            }
         } else {  // head-major, each XCD (workgroup id mod 8) takes a contiguous range of sets
             const int64_t per = (n_sets + 7) / 8;
             h = static_cast<int>(bid / (8 * per));
@@ -174,9 +181,17 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
 
     // ---- the list of key blocks this workgroup visits ---------------------------------------
     int n_steps;  // units to process (host side keeps this below 2^31)
+    int u_begin = 0;  // dense attention: first unit
     const int32_t *sel = nullptr;
     if constexpr (DENSE) {
         n_steps = static_cast<int>(n_units1 + n_units2);
+        if constexpr (EXTRA && !SMALL) {  // key splits: units [u_begin, u_begin + n_steps)
+            if (x.n_split > 1) {
+                const int64_t u_all = n_units1 + n_units2;
+                u_begin = static_cast<int>(u_all * split / x.n_split);
+                n_steps = static_cast<int>(u_all * (split + 1) / x.n_split) - u_begin;
+            }
+        }
     } else {
         sel = idx + (static_cast<int64_t>(h) * n_blk + qgroup) * kk;
         n_steps = SMALL ? (kk + (1 << bpu_shift) - 1) >> bpu_shift : kk << upb_shift;
@@ -205,7 +220,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
 
     // step s -> key unit (global unit index); 32-bit arithmetic: these run once per step on the scalar unit
     auto unit_of = [&](int s) -> int {
-        if constexpr (DENSE) return s;
+        if constexpr (DENSE) return (EXTRA && !SMALL) ? s + u_begin : s;
         else return (sel[s >> upb_shift] << upb_shift) + (s & upb_mask);
     };
     // SMALL: the blocks a 64-key unit is put together from; missing ones (short last unit) point at the
@@ -396,14 +411,15 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
 
     if (!row_valid) return;
     const float l_tot = sum_with_other_half(l_run);
-    const float inv = 1.f / l_tot;
+    const float inv = (EXTRA && DENSE && l_tot == 0.f) ? 0.f : 1.f / l_tot;  // (a key split of empty units only)
     if (lse != nullptr && g == 0)
         lse[static_cast<int64_t>(h) * lse_stride + trow] = (m_run + __builtin_log2f(l_tot)) * kLn2;
     const int64_t o = (trow * heads + h) * 64;
     const float *oc = (o_comp != nullptr) ? o_comp + (static_cast<int64_t>(h) * n_blk + t / block) * 64 : nullptr;
     if constexpr (EXTRA)
         if (x.o_comp_tok != nullptr) oc = x.o_comp_tok + (t * heads + h) * 64;  // this query's own compressed output
-    if (EXTRA && DENSE && x.out_f32 != nullptr) {  // fp32, by query slot
+    if (EXTRA && DENSE && x.out_f32 != nullptr) {  // fp32, by (key split and) query slot
+        const int64_t slot = (static_cast<int64_t>(split) * n_tok + t) * heads + h;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
@@ -411,8 +427,10 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
                 floatx4 o4;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) o4[i] = oacc[dt][4 * r4 + i] * inv;
-                *reinterpret_cast<floatx4 *>(x.out_f32 + (t * heads + h) * 64 + 32 * dt + 8 * r4 + 4 * g) = o4;
+                *reinterpret_cast<floatx4 *>(x.out_f32 + slot * 64 + 32 * dt + 8 * r4 + 4 * g) = o4;
             }
+        // base-2 logarithm of the split's sum of exponentials: what weighs it against the other splits
+        if (x.part_lse != nullptr && g == 0) x.part_lse[slot] = l_tot > 0.f ? m_run + __builtin_log2f(l_tot) : -INFINITY;
         return;
     }
 #pragma unroll
@@ -461,11 +479,13 @@ static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
         if (per_launch < 1) per_launch = 1;
         if (per_launch > sets) per_launch = sets;
     }
-    if ((per_launch + 8) * a.heads > 0x7fffffffLL) return hipErrorInvalidValue;
+    if ((per_launch + 8) * a.heads * (a.x.n_split > 1 ? a.x.n_split : 1) > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (a.x.n_split > 1 && (!DENSE || SMALL || a.x.out_f32 == nullptr || a.x.part_lse == nullptr)) return hipErrorInvalidValue;
     const int map_mode = DENSE ? 0 : 2;
     for (int64_t s0 = 0; s0 < sets; s0 += per_launch) {
         const int64_t ns = (sets - s0 < per_launch) ? sets - s0 : per_launch;
-        const int64_t grid = (map_mode == 2) ? (ns + 7) / 8 * 8 * a.heads : ns * a.heads;
+        const int64_t n_split = (DENSE && a.x.n_split > 1) ? a.x.n_split : 1;
+        const int64_t grid = (map_mode == 2) ? (ns + 7) / 8 * 8 * a.heads : ns * n_split * a.heads;
         hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ>), dim3(static_cast<unsigned>(grid)),
                            dim3(QW * 64), 0, stream, static_cast<const bf16_t *>(a.q),
                            static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
@@ -515,6 +535,48 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
     if (a.block == 32) return run_select<1, false, 2, true, true>(a, stream);
     if (a.block == 16) return run_select<1, false, 2, true>(a, stream);
     return hipErrorInvalidValue;
+}
+
+// One thread per (query slot, head, 4 channels).
+__global__ __launch_bounds__(256) void dense_combine_kernel(const float *__restrict__ part_o,
+                                                            const float *__restrict__ part_lse, int n_split,
+                                                            int64_t n_tok, int heads, TokenMap qmap,
+                                                            bf16_t *__restrict__ out)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n_tok * heads * 16) return;
+    const int c4 = static_cast<int>(i & 15);
+    const int64_t th = i >> 4;  // t * heads + h
+    const int64_t share = n_tok * heads;
+    float top = -INFINITY;
+    for (int j = 0; j < n_split; ++j) top = fmaxf(top, part_lse[j * share + th]);
+    float den = 0.f;
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < n_split; ++j) {
+        const float l = part_lse[j * share + th];
+        if (l == -INFINITY) continue;  // a share without keys
+        const float w = exp2f(l - top);
+        const floatx4 o = *reinterpret_cast<const floatx4 *>(part_o + (j * share + th) * 64 + c4 * 4);
+        den += w;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] += w * o[c];
+    }
+    const int64_t t = th / heads;
+    const int h = static_cast<int>(th - t * heads);
+    bf16x4 r;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) r[c] = static_cast<bf16_t>(acc[c] / den);
+    *reinterpret_cast<bf16x4 *>(out + (qmap.row(t) * heads + h) * 64 + c4 * 4) = r;
+}
+
+hipError_t launch_dense_combine(const float *part_o, const float *part_lse, int n_split, int64_t n_tok, int heads,
+                                TokenMap qmap, void *out, hipStream_t stream)
+{
+    const int64_t threads = n_tok * heads * 16;
+    if (n_split < 1 || threads <= 0 || (threads + 255) / 256 > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dense_combine_kernel, dim3(static_cast<unsigned>((threads + 255) / 256)), dim3(256), 0, stream,
+                       part_o, part_lse, n_split, n_tok, heads, qmap, static_cast<bf16_t *>(out));
+    return hipGetLastError();
 }
 
 }  // namespace s3r

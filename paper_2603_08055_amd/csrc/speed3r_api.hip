@@ -43,6 +43,24 @@ int g_kernel_choice = 0;  // 0 auto, 1 generic attention kernels only, 2 TopK fr
 
 bool mfma_ok(s3r_dtype dtype, int block) { return g_kernel_choice != 1 && dtype == S3R_BF16; }  // any supported block
 
+// Dense attention of few query rows (the special tokens) in key splits: as many as make the workgroups fill
+// the CUs most evenly (MI355X: 256 CUs x 3 workgroups of the dense kernel each), at least 4 key units each.
+constexpr int kDenseSlots = 256 * 3;
+constexpr int kMaxDenseSplit = 8;
+int dense_splits(int64_t n_rows, int heads, int64_t n_units)
+{
+    const int64_t wgs = (n_rows + 127) / 128 * heads;
+    if (wgs >= 4 * kDenseSlots) return 1;
+    int best = 1;
+    double best_fill = 0.0;
+    for (int s = 1; s <= kMaxDenseSplit && (s == 1 || s * 4 <= n_units); ++s) {
+        const double rounds = static_cast<double>(wgs) * s / kDenseSlots;
+        const double fill = rounds / static_cast<double>(static_cast<int64_t>(rounds + 0.999999));
+        if (fill > best_fill + 1e-9) { best_fill = fill; best = s; }
+    }
+    return best;
+}
+
 constexpr int kCandCap = 256;  // candidate slots per list of the TopK-in-the-sweep path (two lists per row)
 
 s3r_status check_shape(int64_t n_tok, int heads, int head_dim, int block, int topk, int dtype)
@@ -67,7 +85,8 @@ struct Layout {
     int width;   // blocks attended per row: kk + n_forced
     int head_chunk;
     size_t qc, kc, vc, oc, tile[8], idx, idx_merged, forced_clean, forced_words, s, kb, vb, kb_spec, vb_spec;
-    size_t stat_slots, head_stats, thr, cand, cand_count, overflow, blk_len, oc_tok, total;
+    size_t stat_slots, head_stats, thr, cand, cand_count, overflow, blk_len, oc_tok, spec_part_o, spec_part_lse, total;
+    int spec_split;  // key splits of the special rows' dense attention (1: none)
 };
 
 // n_tok: tokens on the sparse path (the image tokens); n_spec: special tokens (dense rows).
@@ -116,6 +135,13 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, 
     L.blk_len = take(static_cast<size_t>(L.n_blk) * sizeof(int32_t));
     // compression branch with unpooled queries: fp32 compressed output per query slot
     L.oc_tok = take(token_queries ? static_cast<size_t>(L.n_blk) * block * heads * 64 * sizeof(float) : 0);
+    // special rows in key splits: normalised partial results and their log-sums
+    L.spec_split = 1;
+    if (n_spec > 0 && mfma_ok(dtype, block) && block >= 64)
+        L.spec_split = dense_splits(n_spec, heads, L.n_blk * (block / 64) + (n_spec + 63) / 64);
+    const size_t part_rows = L.spec_split > 1 ? static_cast<size_t>(L.spec_split) * n_spec * heads : 0;
+    L.spec_part_o = take(part_rows * 64 * sizeof(float));
+    L.spec_part_lse = take(part_rows * sizeof(float));
     L.total = off;
     return L;
 }
@@ -565,12 +591,21 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
             d.kb = kb; d.vb = vb; d.n_keys = sp.n_img; d.n_blk = L.n_blk;      // image keys, then special keys
             d.blk_len = blk_len;
             d.kb2 = kb_s; d.vb2 = vb_s; d.n_keys2 = sp.n_spec;
+            if (L.spec_split > 1) {
+                d.x.n_split = L.spec_split;
+                d.x.out_f32 = reinterpret_cast<float *>(at(ws, L.spec_part_o));
+                d.x.part_lse = reinterpret_cast<float *>(at(ws, L.spec_part_lse));
+            }
         } else {
             d.n_keys = p->n_tok; d.n_blk = (p->n_tok + p->block - 1) / p->block;  // every row, in place
         }
         StageTimer tm(S3R_STAGE_DENSE, stream);
         S3R_HIP(mfma ? s3r::launch_select_mfma(d, stream) : s3r::launch_select_generic(d, stream),
                 "dense kernel launch (special tokens)");
+        if (d.x.n_split > 1)
+            S3R_HIP(s3r::launch_dense_combine(d.x.out_f32, d.x.part_lse, d.x.n_split, sp.n_spec, p->heads, sp.spec,
+                                              p->out, stream),
+                    "dense combine kernel launch (special tokens)");
     }
     return S3R_OK;
 }
