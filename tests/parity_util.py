@@ -242,7 +242,8 @@ def compare_windows_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, topk, dtype
         s_free = ref["s"].copy()
         s_free[:, :, forced] = -np.inf
         dyn = gidx[~is_forced].reshape(gidx.shape[0], gidx.shape[1], k_dyn)
-        stats["topk_exact"], stats["topk_tie_resolved"] = check_topk_sets(s_free, dyn, k_dyn)
+        stats["topk_exact"], stats["topk_tie_resolved"] = (check_topk_sets(s_free, dyn, k_dyn) if k_dyn > 0
+                                                           else (0, 0))     # every block forced
     if stats["topk_tie_resolved"]:
         ref = oracle.gsa_forward_blocks(qf, kf, vf, blocks, topk, gate=gate_f, forced=forced, idx_override=gidx)
     img_rows = np.concatenate(blocks)

@@ -849,6 +849,65 @@ def test_strides_are_validated(s3r):
         s3r.speed3r_sparse_global_attn_ex(q, kt, q, out, 64, 2)
 
 
+# --------------------------------------------------- seeded sweep over randomly drawn shapes --
+
+def _random_case(seed):
+    """One small problem with every option drawn at random (seeded): shape, data type, block size,
+    special tokens, forced blocks, gate, query kind of the compression branch, input strides."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = "bf16" if rng.random() < 0.7 else "f32"
+    block = int(rng.choice([16, 32, 64, 128]))
+    heads = int(rng.integers(1, 4))
+    views = int(rng.integers(1, 5))
+    special = int(rng.choice([0, 0, 1, 3, 7]))
+    img = int(rng.integers(max(block // 2, 2), 5 * block))       # image rows per view
+    tpv = special + img
+    n_blk = (views * img + block - 1) // block
+    grid = None
+    if rng.random() < 0.25:                                      # blocks = spatial windows of a patch grid
+        window = int(rng.choice([4, 8]))
+        grid = (int(rng.integers(3, 21)), int(rng.integers(3, 21)), window)
+        block, img = window * window, grid[0] * grid[1]
+        tpv = special + img
+        n_blk = views * (-(-grid[0] // window)) * (-(-grid[1] // window))
+    topk = int(rng.integers(1, 7))
+    n_forced = int(rng.integers(0, min(3, n_blk) + 1)) if rng.random() < 0.4 else 0
+    forced = np.sort(rng.choice(n_blk, n_forced, replace=False)).astype(np.int32) if n_forced else None
+    return dict(dtype=dtype, block=block, heads=heads, views=views, special=special, tpv=tpv, topk=topk, grid=grid,
+                forced=forced, with_gate=bool(rng.random() < 0.6), token_queries=bool(rng.random() < 0.3),
+                strided=bool(rng.random() < 0.3), kind=str(rng.choice(["normal", "clustered", "outliers"])),
+                seed=200 + seed)
+
+
+@pytest.mark.parametrize("seed", range(160))
+def test_random_shapes(s3r, oracle, seed):
+    c = _random_case(seed)
+    wl = workloads.Workload(f"random{seed}", c["views"], c["tpv"], c["heads"], 64, c["dtype"], c["block"], c["topk"],
+                            c["seed"], c["kind"])
+    log(f"random case {seed}: { {k: (v.tolist() if isinstance(v, np.ndarray) else v) for k, v in c.items()} }")
+    q, k, v = workloads.make_inputs(wl)
+    gate = workloads.make_gate_logits(wl) if c["with_gate"] else None
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    if c["strided"]:                                   # slices of one packed [n_tok, 3, heads, 64] tensor
+        big = torch.stack([qd, kd, vd], dim=1).contiguous()
+        qd, kd, vd = big[:, 0], big[:, 1], big[:, 2]
+    res = run_device(s3r, qd, kd, vd, c["block"], c["topk"], gate=None if gate is None else gate.cuda(),
+                     forced=c["forced"], tokens_per_view=c["tpv"] if (c["special"] or c["grid"]) else 0,
+                     special_per_view=c["special"], grid=c["grid"], compress_queries=int(c["token_queries"]))
+    host = [to_host_f32(q), to_host_f32(k), to_host_f32(v), None if gate is None else to_host_f32(gate)]
+    if c["grid"]:
+        stats = compare_windows_with_oracle(oracle, res, *host, c["topk"], c["dtype"], c["views"], c["tpv"],
+                                            c["special"], c["grid"], forced=c["forced"], label=wl.name,
+                                            token_queries=c["token_queries"])
+    elif c["special"]:
+        stats = compare_layer_with_oracle(oracle, res, *host, c["block"], c["topk"], c["dtype"], c["tpv"], c["special"],
+                                          forced=c["forced"], label=wl.name, token_queries=c["token_queries"])
+    else:
+        stats = compare_with_oracle(oracle, res, *host, c["block"], c["topk"], c["dtype"], forced=c["forced"],
+                                    label=wl.name, token_queries=c["token_queries"])
+    log(f"random case {seed}: {stats}")
+
+
 # ------------------------------------------------------------------- HIP graph capture --
 
 def test_full_path_replays_from_a_hip_graph(s3r):
