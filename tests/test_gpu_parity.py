@@ -908,6 +908,47 @@ def test_random_shapes(s3r, oracle, seed):
     log(f"random case {seed}: {stats}")
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_medium_shapes_sampled_rows(s3r, oracle, seed):
+    """Hundreds to thousands of blocks (the TopK-in-the-sweep route with real candidate lists, several
+    key units per split, long index rows), 14 sampled query blocks each against the oracle."""
+    rng = np.random.default_rng(5000 + seed)
+    dtype = "bf16" if rng.random() < 0.8 else "f32"
+    block = int(rng.choice([16, 32, 64, 64, 128]))
+    heads = int(rng.integers(1, 5))
+    special = int(rng.choice([0, 0, 5]))
+    img = int(rng.integers(300, 1400))
+    views = int(rng.integers(6, 40)) * (2 if block >= 64 else 1)
+    if dtype == "f32":
+        views = max(views // 4, 2)                                  # the generic kernels are slow
+    tpv = special + img
+    n_blk = (views * img + block - 1) // block
+    topk = int(rng.choice([4, 16, 32, 64, 100]))
+    forced = None
+    if rng.random() < 0.35:
+        forced = np.sort(rng.choice(n_blk, int(rng.integers(1, 24)), replace=False)).astype(np.int32)
+    kind = str(rng.choice(["normal", "clustered", "outliers"]))
+    wl = workloads.Workload(f"medium{seed}", views, tpv, heads, 64, dtype, block, topk, 700 + seed, kind)
+    rows = np.unique(np.concatenate([[0, n_blk - 1], rng.choice(n_blk, 12, replace=False)]))
+    token_queries = bool(rng.random() < 0.25)
+    log(f"medium case {seed}: {dtype} block {block} heads {heads} views {views} x {tpv} ({special} special) "
+        f"n_blk {n_blk} topk {topk} forced {None if forced is None else forced.size} {kind} token_queries {token_queries}")
+    q, k, v = workloads.make_inputs(wl)
+    gate = workloads.make_gate_logits(wl)
+    res = run_device(s3r, q.cuda(), k.cuda(), v.cuda(), block, topk, gate=gate.cuda(), forced=forced,
+                     tokens_per_view=tpv if special else 0, special_per_view=special,
+                     compress_queries=int(token_queries))
+    host = [to_host_f32(q), to_host_f32(k), to_host_f32(v), to_host_f32(gate)]
+    if special:
+        spec = rng.choice(views * special, 8, replace=False)
+        stats = compare_layer_with_oracle(oracle, res, *host, block, topk, dtype, tpv, special, rows=rows,
+                                          spec_sample=spec, forced=forced, label=wl.name, token_queries=token_queries)
+    else:
+        stats = compare_with_oracle(oracle, res, *host, block, topk, dtype, rows=rows, forced=forced, label=wl.name,
+                                    token_queries=token_queries)
+    log(f"medium case {seed}: {stats}")
+
+
 # ------------------------------------------------------------------- HIP graph capture --
 
 def test_full_path_replays_from_a_hip_graph(s3r):
