@@ -4,7 +4,9 @@
 A "step" is one pass of the whole path (pool -> compressed attention with the TopK bounds ->
 TopK filter sweep + candidate TopK -> selection attention + merge) over one batch of synthetic Q/K/V that is already resident in HBM.
 Default workload: config 4, 1000 views x 1374 tokens, 16 heads, head_dim 64, bf16, block 64,
-top-64.  Prints ONE JSON line (see the design doc for the fields).  The in-house dense attention on the
+top-64.  Prints ONE JSON line: the metric (tokens/s of the whole path), the roofline of the selection
+kernel (executed FLOP/s against the bf16 MFMA peak, plus its memory side), per-stage times from HIP
+events, the dense denominator and the CPU baseline.  The in-house dense attention on the
 same inputs is timed once for the speed-up ratio, and the fp64 CPU oracle is timed on a bounded
 sample of the same workload as a reported baseline (cpu_baseline)."""
 from __future__ import annotations
