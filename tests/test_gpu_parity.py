@@ -849,6 +849,30 @@ def test_strides_are_validated(s3r):
         s3r.speed3r_sparse_global_attn_ex(q, kt, q, out, 64, 2)
 
 
+# ------------------------------------- the options at the benchmark's full size, sampled rows --
+
+@pytest.mark.timeout(600)
+def test_config4_full_size_forced_reference_views_sampled_rows(s3r, oracle):
+    """1000 views with the VGGT variant's fixed context (reference view + every 100th view: 224
+    forced blocks, 288 blocks per query block): the long-row selection kernel at full size."""
+    wl = workloads.config(4)
+    forced = workloads.vggt_forced_blocks(wl)
+    rng = np.random.default_rng(21)
+    rows = np.unique(np.concatenate([[0, int(forced[-1]), wl.n_blk - 1], rng.choice(wl.n_blk, 9, replace=False)]))
+    end_to_end(s3r, oracle, wl, rows=rows, forced=forced, device_gen="cuda", label="config4+reference views")
+
+
+@pytest.mark.timeout(600)
+def test_config4_full_size_token_queries_sampled_rows(s3r, oracle):
+    """1000 views with the unpooled-query compression branch: every one of the 1,374,000 rows
+    against 21,469 pooled keys; sampled query blocks against the oracle."""
+    wl = workloads.config(4)
+    rng = np.random.default_rng(22)
+    rows = np.unique(np.concatenate([[0, wl.n_blk - 1], rng.choice(wl.n_blk, 8, replace=False)]))
+    end_to_end(s3r, oracle, wl, rows=rows, with_gate=True, device_gen="cuda", token_queries=True,
+               label="config4 token queries")
+
+
 # --------------------------------------------------- seeded sweep over randomly drawn shapes --
 
 def _random_case(seed):
