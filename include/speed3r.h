@@ -20,14 +20,16 @@
  * and, as the comparison point, plain dense softmax attention (eq. 2 form).
  * Optional parts of the layer (fields of s3r_params): special tokens, which get
  * dense attention over all tokens (eqs. 1-2), a fixed set of key blocks every
- * query block attends besides its TopK (Sec. 3.3), spatial pooling windows.
+ * query block attends besides its TopK (Sec. 3.3), spatial pooling windows,
+ * unpooled queries in the compression branch.
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer unless stated otherwise; the
  *     caller owns all of them; the library never frees caller memory.
  *   - q, k, v, out, gate_logits, o_sel: layout [n_tok][heads][head_dim],
- *     contiguous, element type given by `dtype`, 16-byte aligned.  Inputs are
- *     read-only and must not alias outputs.
+ *     contiguous, element type given by `dtype`, 16-byte aligned (q, k, v of
+ *     speed3r_sparse_global_attn_ex may instead be strided, see stride_tok).
+ *     Inputs are read-only and must not alias outputs.
  *   - n_blk = ceil(n_tok / block).  head_dim must be 64, block one of
  *     16, 32, 64, 128 (else S3R_ERR_UNSUPPORTED).  topk > n_blk is clamped.
  *     n_tok need not be a multiple of block.
