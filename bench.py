@@ -200,8 +200,11 @@ def main():
     roofline["memory_side"] = {"algorithmic_bytes_per_launch": kv_bytes + qo_bytes,
                                "achieved_GBps": (kv_bytes + qo_bytes) / (sel_ms * 1e-3) / 1e9,
                                "hbm_peak_GBps": 8000.0,
-                               "note": "scattered 16 KiB K/V units; a load-only gather of such pieces measures "
-                                       "6.4-7.3 TB/s of L2-miss traffic on MI355X"}
+                               "measured_traffic_GBps": (None if roofline["traffic"] is None
+                                                         else roofline["traffic"] / (sel_ms * 1e-3) / 1e9),
+                               "note": "scattered 16 KiB K/V units; the measured L2-miss traffic per launch (rocprofv3 FETCH_SIZE, "
+                                       "profiles/) over the kernel time is what binds this kernel: a load-only gather of "
+                                       "such pieces measures 6.4-7.3 TB/s on MI355X"}
     # HBM-side figures of the two bandwidth-bound stages (algorithmic bytes / measured time)
     e = 2 if wl.dtype == "bf16" else 4
     pool_bytes = 3.0 * wl.n_tok * wl.heads * wl.head_dim * e + 3.0 * seq.n_blk * wl.heads * wl.head_dim * 4
