@@ -78,7 +78,12 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 // EXTRA : the rarely used arguments of SelectExtras are honoured (a second instantiation, so that the plain
 //         path carries none of their instructions: they cost the selection kernel 2.4 % when always compiled in)
 // ASMQ  : Q is loaded by inline asm after the first unit requests instead of by plain loads (see below)
-template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ>
+// PAIR  : selection with blocks of 64 tokens, QW = 4: one workgroup takes two neighbouring query blocks (two
+//         waves each) and walks the union of their two index lists, merged on the fly; a key block both
+//         lists hold is fetched into LDS once for both, and a pair of waves sits out the units only the
+//         other pair's list holds.  For long lists that are mostly common to all query blocks (forced
+//         blocks), where the traffic from the L2s into LDS is what binds.
+template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ, bool PAIR = false>
 __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ kb, const bf16_t *__restrict__ vb,
     const int32_t *__restrict__ idx, const float *__restrict__ o_comp, const bf16_t *__restrict__ gate,
@@ -129,7 +134,14 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         t = qgroup * block + (lane & 31);
         row_valid = (lane & 31) < block && t < n_tok;
     }
-    if (!DENSE && blk_len != nullptr) row_valid = wave * 32 + (lane & 31) < blk_len[qgroup];  // spatial windows
+    if (!DENSE && !PAIR && blk_len != nullptr) row_valid = wave * 32 + (lane & 31) < blk_len[qgroup];  // spatial windows
+    if constexpr (PAIR) {
+        static_assert(!PAIR || (QW == 4 && !DENSE && !SMALL && ASMQ), "two query blocks of 64 rows, two waves each");
+        const int64_t qblk = 2 * qgroup + (wave >> 1);
+        t = qblk * 64 + (wave & 1) * 32 + (lane & 31);
+        row_valid = t < n_tok;
+        if (blk_len != nullptr) row_valid = qblk < n_blk && (wave & 1) * 32 + (lane & 31) < blk_len[qblk];
+    }
     if constexpr (EXTRA && DENSE)
         if (x.q_blk_len != nullptr && row_valid) row_valid = t % x.q_block < x.q_blk_len[t / x.q_block];
     const int64_t trow = qmap.row(row_valid ? t : 0);  // the caller's row of this query
@@ -193,7 +205,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
             }
         }
     } else {
-        sel = idx + (static_cast<int64_t>(h) * n_blk + qgroup) * kk;
+        sel = idx + (static_cast<int64_t>(h) * n_blk + (PAIR ? 2 * qgroup : qgroup)) * kk;
         n_steps = SMALL ? (kk + (1 << bpu_shift) - 1) >> bpu_shift : kk << upb_shift;
     }
     // SMALL: the c-th key block of unit s, or -1 past the end of the list
@@ -390,6 +402,70 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
             }
     };
 
+    if constexpr (PAIR) {
+        // Two ascending lists -> their ascending union.  A cursor holds the position and the entry it looks
+        // at in either list; one cursor runs D units ahead and requests the loads, the other consumes.
+        constexpr int kEnd = 0x7fffffff;
+        const int32_t *sel_b = sel + kk;
+        const bool has_b = 2 * qgroup + 1 < n_blk;
+        struct Cursor { int ia, ib, ja, jb; };
+        auto start = [&]() -> Cursor {
+            return Cursor{0, 0, kk > 0 ? sel[0] : kEnd, (has_b && kk > 0) ? sel_b[0] : kEnd};
+        };
+        // next unit of the union (kEnd when done); ua / ub: list A / B holds it
+        auto next = [&](Cursor &c, bool &ua, bool &ub) -> int {
+            const int j = c.ja < c.jb ? c.ja : c.jb;
+            ua = c.ja == j;
+            ub = c.jb == j;
+            if (j == kEnd) return kEnd;
+            if (ua) { ++c.ia; c.ja = c.ia < kk ? sel[c.ia] : kEnd; }
+            if (ub) { ++c.ib; c.jb = c.ib < kk ? sel_b[c.ib] : kEnd; }
+            return j;
+        };
+        auto issue_unit = [&](int64_t w, int stage) {  // this wave's share of unit w -> LDS stage `stage`
+            const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (2 * kUnitElems * 2);
+            const bf16_t *unit = seg1 + w * kUnitElems;
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) {
+                const int chunk = wave * CPW + c;  // 0..7: K, 8..15: V
+                lds_dma_16(unit + (chunk & 7) * 512 + lane * 8, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
+            }
+        };
+        auto unit_mask_of = [&](int64_t w) -> unsigned long long {  // which of unit w's 64 keys exist
+            const int64_t left = blk_len != nullptr ? blk_len[w] : n_keys - w * kUnitKeys;
+            return left >= kUnitKeys ? ~0ull : left <= 0 ? 0ull : (1ull << left) - 1ull;
+        };
+        Cursor ahead = start(), here = start();
+        bool ua, ub;
+        int in_flight = 0;  // units requested and not yet consumed
+        for (int d = 0; d < D; ++d) {
+            const int j = next(ahead, ua, ub);
+            if (j == kEnd) break;
+            issue_unit(j, d);
+            ++in_flight;
+        }
+        load_q_dense();
+        int stage = NS - 1, stage_ahead = D - 1;
+        for (;;) {
+            const int j = next(here, ua, ub);
+            if (j == kEnd) break;
+            const bool mine = (wave >> 1) ? ub : ua;
+            stage = (stage + 1 == NS) ? 0 : stage + 1;
+            stage_ahead = (stage_ahead + 1 == NS) ? 0 : stage_ahead + 1;
+            // this unit's loads done (up to D - 1 later units may still be on their way), then everybody's
+            if (in_flight == D) wait_vmcnt<CPW *(D - 1)>(); else wait_vmcnt<0>();
+            lds_barrier();
+            bool ta, tb;
+            const int jn = next(ahead, ta, tb);
+            if (jn != kEnd) issue_unit(jn, stage_ahead); else --in_flight;
+            if (!mine) continue;
+            const unsigned long long vmask = unit_mask_of(j);
+            if (vmask == 0ull) continue;
+            scores(&ring[stage][0]);
+            softmax(vmask);
+            accumulate(&ring[stage][kUnitElems]);
+        }
+    } else {
     for (int s = 0; s < D && s < n_steps; ++s) issue(s, s);  // D < NS: stage = s
     if constexpr (kAsmQ) load_q_dense();
 
@@ -407,6 +483,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         scores(&ring[stage][0]);
         softmax(vmask);
         accumulate(&ring[stage][kUnitElems]);
+    }
     }
 
     if (!row_valid) return;
@@ -464,11 +541,11 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         }
 }
 
-template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ>
+template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ, bool PAIR>
 static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
 {
     const int64_t rows_per_group = 32 * QW;
-    const int64_t groups = DENSE ? (a.n_tok + rows_per_group - 1) / rows_per_group : a.n_blk;
+    const int64_t groups = DENSE ? (a.n_tok + rows_per_group - 1) / rows_per_group : PAIR ? (a.n_blk + 1) / 2 : a.n_blk;
     const int64_t sets = groups;
     // Dense attention is quadratic: keep each launch to roughly 2e14 FLOP (a fraction of a second)
     // so that no single kernel occupies the GPU for seconds.
@@ -486,7 +563,7 @@ static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
         const int64_t ns = (sets - s0 < per_launch) ? sets - s0 : per_launch;
         const int64_t n_split = (DENSE && a.x.n_split > 1) ? a.x.n_split : 1;
         const int64_t grid = (map_mode == 2) ? (ns + 7) / 8 * 8 * a.heads : ns * n_split * a.heads;
-        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ>), dim3(static_cast<unsigned>(grid)),
+        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ, PAIR>), dim3(static_cast<unsigned>(grid)),
                            dim3(QW * 64), 0, stream, static_cast<const bf16_t *>(a.q),
                            static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
                            a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
@@ -500,14 +577,14 @@ static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
     return hipSuccess;
 }
 
-template <int QW, bool DENSE, int NS, bool SMALL = false, bool ASMQ = DENSE>
+template <int QW, bool DENSE, int NS, bool SMALL = false, bool ASMQ = DENSE, bool PAIR = false>
 static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
 {
     const SelectExtras &x = a.x;
     const bool extra = x.o_comp_tok != nullptr || x.out_f32 != nullptr || x.kv_head_stride != 0 ||
                        x.q_blk_len != nullptr || x.in.tok != 0;
-    return extra ? run_select_x<QW, DENSE, NS, SMALL, true, ASMQ>(a, stream)
-                 : run_select_x<QW, DENSE, NS, SMALL, false, ASMQ>(a, stream);
+    return extra ? run_select_x<QW, DENSE, NS, SMALL, true, ASMQ, PAIR>(a, stream)
+                 : run_select_x<QW, DENSE, NS, SMALL, false, ASMQ, PAIR>(a, stream);
 }
 
 hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
@@ -525,11 +602,13 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
         return hipErrorInvalidValue;
     }
     if (a.n_keys != a.n_tok || a.n_keys2 != 0) return hipErrorInvalidValue;  // selection: keys = the query sequence
-    // Long index rows (forced blocks, which every query block shares and the L2 keeps) are bound by the loop
-    // itself rather than by the memory fabric; letting each unit's arithmetic overlap the next unit's loads
-    // (Q loaded by inline asm, see the kernel) is 3.5 % faster there and 1 % slower on short rows.
+    // Long index rows (forced blocks, which every query block shares and the L2s keep) are bound by the loop
+    // and by the traffic from the L2s into LDS rather than by the memory fabric: two neighbouring query blocks
+    // per workgroup, each common unit fetched once for both (PAIR), with each unit's arithmetic overlapping
+    // the next unit's loads (ASMQ): 135 against 149 ms with 224 forced + 64 selected blocks at 1000 views.  On
+    // short rows, where neighbours share a third of their blocks, the same kernel is 5 % slower.
     if (a.block == 64)
-        return a.kk > 96 ? run_select<2, false, 2, false, true>(a, stream) : run_select<2, false, 2>(a, stream);
+        return a.kk > 96 ? run_select<4, false, 2, false, true, true>(a, stream) : run_select<2, false, 2>(a, stream);
     // measured: the inline-asm Q load is 2 % faster for blocks of 128 and 32 tokens, 2 % slower for 16
     if (a.block == 128) return run_select<4, false, 2, false, true>(a, stream);
     if (a.block == 32) return run_select<1, false, 2, true, true>(a, stream);

@@ -849,6 +849,39 @@ def test_strides_are_validated(s3r):
         s3r.speed3r_sparse_global_attn_ex(q, kt, q, out, 64, 2)
 
 
+# --------------------- long index rows: two query blocks per workgroup on the merged list --
+
+@pytest.mark.parametrize("n_tok,topk,n_forced,with_gate", [
+    (64 * 202 + 17, 120, 0, True),       # 203 blocks (odd: the last workgroup holds one query block), ragged tail
+    (64 * 150, 16, 100, False),          # mostly forced blocks, common to every query block
+    (64 * 129 + 1, 200, 0, False),       # topk > n_blk: every block selected by every query block
+    (64 * 140 + 40, 60, 45, True),       # forced and selected interleaved
+])
+def test_long_index_rows_pair_kernel(s3r, oracle, n_tok, topk, n_forced, with_gate):
+    """Rows of more than 96 blocks of 64 tokens run two query blocks per workgroup on the union of
+    their lists; every output against the oracle."""
+    wl = workloads.Workload(f"longrows_{n_tok}_{topk}_{n_forced}", 1, n_tok, 2, 64, "bf16", 64, topk, 111, "clustered")
+    forced = None
+    if n_forced:
+        forced = np.sort(np.random.default_rng(112).choice(wl.n_blk, n_forced, replace=False)).astype(np.int32)
+    end_to_end(s3r, oracle, wl, with_gate=with_gate, forced=forced)
+
+
+def test_long_index_rows_spatial_windows(s3r, oracle):
+    """The same kernel with 8 x 8 windows (per-block lengths, cut edge windows): 9 views of 37 x 37
+    patches = 225 blocks, 110 selected."""
+    views, special, grid = 9, 5, (37, 37, 8)
+    tpv = special + 37 * 37
+    wl = workloads.Workload("longrows_windows", views, tpv, 2, 64, "bf16", 64, 110, 113, "normal")
+    q, k, v = workloads.make_inputs(wl)
+    gate = workloads.make_gate_logits(wl)
+    res = run_device(s3r, q.cuda(), k.cuda(), v.cuda(), 64, 110, gate=gate.cuda(), tokens_per_view=tpv,
+                     special_per_view=special, grid=grid)
+    stats = compare_windows_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v),
+                                        to_host_f32(gate), 110, "bf16", views, tpv, special, grid, label=wl.name)
+    log(f"{wl.name}: {stats}")
+
+
 # ------------------------------------- the options at the benchmark's full size, sampled rows --
 
 @pytest.mark.timeout(600)
