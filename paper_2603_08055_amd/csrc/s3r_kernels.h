@@ -181,6 +181,7 @@ struct SelectArgs {
     TokenMap qmap, kmap;
     const int32_t *blk_len = nullptr;  // tokens per block of the kb/vb (or kmap) sequence; null: full blocks and a short last one
     int heads, block, kk;
+    int n_common = 0;          // selection: entries of every index row known to be the same in all rows (forced blocks)
     float scale;
     bool is_bf16;
     SelectExtras x;

@@ -606,9 +606,12 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
     // and by the traffic from the L2s into LDS rather than by the memory fabric: two neighbouring query blocks
     // per workgroup, each common unit fetched once for both (PAIR), with each unit's arithmetic overlapping
     // the next unit's loads (ASMQ): 135 against 149 ms with 224 forced + 64 selected blocks at 1000 views.  On
-    // short rows, where neighbours share a third of their blocks, the same kernel is 5 % slower.
+    // rows without common blocks, where neighbours share a third of their blocks, PAIR is 5 % slower; long
+    // ones still gain from ASMQ alone.
     if (a.block == 64)
-        return a.kk > 96 ? run_select<4, false, 2, false, true, true>(a, stream) : run_select<2, false, 2>(a, stream);
+        return (a.kk > 96 && 2 * a.n_common >= a.kk) ? run_select<4, false, 2, false, true, true>(a, stream)
+               : a.kk > 96                            ? run_select<2, false, 2, false, true>(a, stream)
+                                                      : run_select<2, false, 2>(a, stream);
     // measured: the inline-asm Q load is 2 % faster for blocks of 128 and 32 tokens, 2 % slower for 16
     if (a.block == 128) return run_select<4, false, 2, false, true>(a, stream);
     if (a.block == 32) return run_select<1, false, 2, true, true>(a, stream);

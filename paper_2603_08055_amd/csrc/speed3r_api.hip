@@ -561,6 +561,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
 
     s3r::SelectArgs a{};
     a.x.o_comp_tok = oc_tok; a.x.in = in;
+    a.n_common = n_forced;
     a.q = p->q; a.k = p->k; a.v = p->v; a.kb = kb; a.vb = vb; a.idx = idx_sel; a.o_comp = oc;
     a.gate = p->gate_logits; a.out = p->out; a.o_sel = p->o_sel; a.lse = p->lse_sel;
     a.n_tok = sp.n_img; a.n_keys = sp.n_img; a.n_blk = L.n_blk; a.lse_stride = p->n_tok;

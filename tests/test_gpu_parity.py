@@ -852,14 +852,17 @@ def test_strides_are_validated(s3r):
 # --------------------- long index rows: two query blocks per workgroup on the merged list --
 
 @pytest.mark.parametrize("n_tok,topk,n_forced,with_gate", [
-    (64 * 202 + 17, 120, 0, True),       # 203 blocks (odd: the last workgroup holds one query block), ragged tail
+    (64 * 202 + 17, 30, 100, True),      # 203 blocks (odd: the last workgroup holds one query block), ragged tail
     (64 * 150, 16, 100, False),          # mostly forced blocks, common to every query block
+    (64 * 140 + 40, 50, 55, True),       # forced and selected interleaved, about half and half
+    (64 * 130, 1, 129, False),           # all blocks but one forced
+    (64 * 202 + 17, 120, 0, True),       # long rows without forced blocks: one query block per workgroup
     (64 * 129 + 1, 200, 0, False),       # topk > n_blk: every block selected by every query block
-    (64 * 140 + 40, 60, 45, True),       # forced and selected interleaved
+    (64 * 140 + 40, 60, 45, True),       # forced blocks the smaller part of a long row
 ])
 def test_long_index_rows_pair_kernel(s3r, oracle, n_tok, topk, n_forced, with_gate):
-    """Rows of more than 96 blocks of 64 tokens run two query blocks per workgroup on the union of
-    their lists; every output against the oracle."""
+    """Rows of more than 96 blocks of 64 tokens, at least half of them forced, run two query blocks
+    per workgroup on the union of their lists; other long rows one; every output against the oracle."""
     wl = workloads.Workload(f"longrows_{n_tok}_{topk}_{n_forced}", 1, n_tok, 2, 64, "bf16", 64, topk, 111, "clustered")
     forced = None
     if n_forced:
@@ -869,16 +872,19 @@ def test_long_index_rows_pair_kernel(s3r, oracle, n_tok, topk, n_forced, with_ga
 
 def test_long_index_rows_spatial_windows(s3r, oracle):
     """The same kernel with 8 x 8 windows (per-block lengths, cut edge windows): 9 views of 37 x 37
-    patches = 225 blocks, 110 selected."""
+    patches = 225 blocks (odd), 60 of them forced (the corner windows among them), 50 selected."""
     views, special, grid = 9, 5, (37, 37, 8)
     tpv = special + 37 * 37
-    wl = workloads.Workload("longrows_windows", views, tpv, 2, 64, "bf16", 64, 110, 113, "normal")
+    wl = workloads.Workload("longrows_windows", views, tpv, 2, 64, "bf16", 64, 50, 113, "normal")
     q, k, v = workloads.make_inputs(wl)
     gate = workloads.make_gate_logits(wl)
-    res = run_device(s3r, q.cuda(), k.cuda(), v.cuda(), 64, 110, gate=gate.cuda(), tokens_per_view=tpv,
+    forced = np.unique(np.concatenate([[4, 20, 24, 224], np.random.default_rng(114).choice(225, 56, replace=False)]))
+    forced = forced.astype(np.int32)
+    res = run_device(s3r, q.cuda(), k.cuda(), v.cuda(), 64, 50, gate=gate.cuda(), forced=forced, tokens_per_view=tpv,
                      special_per_view=special, grid=grid)
     stats = compare_windows_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v),
-                                        to_host_f32(gate), 110, "bf16", views, tpv, special, grid, label=wl.name)
+                                        to_host_f32(gate), 50, "bf16", views, tpv, special, grid, forced=forced,
+                                        label=wl.name)
     log(f"{wl.name}: {stats}")
 
 
