@@ -44,10 +44,41 @@ def rel_errors(gpu, ref):
     return elem, glob
 
 
+def strict_errors(gpu, ref):
+    """The element-wise relative error with the denominator floored at 1e-2 * rms(ref) instead of rms(ref):
+    (max, 99.9th percentile).  Reported beside the gated figure, never gated on: an element a hundred
+    times smaller than the tensor's RMS carries the same absolute rounding error as any other (the error
+    of a softmax average scales with the RMS of the values averaged), so its ratio is up to 100 times
+    the gated one by construction."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0, 0.0
+    rms = math.sqrt(float(np.mean(ref * ref)))
+    r = np.abs(gpu - ref) / np.maximum(np.abs(ref), max(1e-2 * rms, 1e-30))
+    return float(np.max(r)), float(np.quantile(r, 0.999))
+
+
 def assert_close(gpu, ref, tol, what):
     elem, glob = rel_errors(gpu, ref)
     assert elem <= tol and glob <= tol, f"{what}: rel err elem {elem:.3e} glob {glob:.3e} > {tol:.1e}"
     return elem
+
+
+def check_topk_sets_fast(s_rows, gpu_idx, k):
+    """check_topk_sets for many rows: rows whose device set equals the oracle's own choice (stable sort:
+    equal scores go to the smaller index) are counted at once, the others go through the near-tie rule
+    one by one.  Returns (n_exact, n_tie_resolved)."""
+    H, R, n_blk = s_rows.shape
+    assert gpu_idx.shape == (H, R, k), (gpu_idx.shape, (H, R, k))
+    want = np.sort(np.argsort(-s_rows, axis=-1, kind="stable")[..., :k], axis=-1)
+    same = (want == gpu_idx).all(axis=-1)
+    n_tie = 0
+    for h, r in zip(*np.nonzero(~same)):
+        e, t = check_topk_sets(s_rows[h:h + 1, r:r + 1], gpu_idx[h:h + 1, r:r + 1], k)
+        assert e == 0 and t == 1
+        n_tie += 1
+    return int(same.sum()), n_tie
 
 
 def check_topk_sets(s_rows, gpu_idx, k):
@@ -191,7 +222,9 @@ def compare_with_oracle(oracle, dev_res, qf, kf, vf, gate_f, block, topk, dtype,
         tok = tok[tok < n_tok]
         oc_tok = oracle.compressed_attn_tokens(qf, kc, vc, scale, tok)
         out_v = oracle.merge_tokens(oc_tok, o_sel_v, None if gate_f is None else gate_f[tok])
-    stats["out"] = assert_close(tok_sel(dev_res["out"]), out_v, tol, f"{label} out")
+    got_out = tok_sel(dev_res["out"])
+    stats["out"] = assert_close(got_out, out_v, tol, f"{label} out")
+    stats["out_strict_max"], stats["out_strict_p999"] = strict_errors(got_out, out_v)
     return stats
 
 

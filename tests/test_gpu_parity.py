@@ -195,6 +195,34 @@ def test_dense_attn(s3r, oracle, dtype, n_tok, choice):
         s3r.speed3r_set_kernel_choice(0)
 
 
+@pytest.mark.timeout(600)
+def test_dense_attn_in_several_bounded_launches(s3r, oracle):
+    """Large problems run the dense kernel (the speed-up denominator, eq. 2 form) as several launches of
+    about 2e14 FLOP, each starting at a query-group offset.  250 037 tokens x 16 heads take two launches,
+    the second starting at query group 1525 (row 195 200): rows at both ends, either side of that
+    boundary and at random against the oracle."""
+    n_tok, heads = 250_037, 16
+    per_launch = int(2e14 / (4.0 * 64.0 * 128 * n_tok * heads))
+    groups = (n_tok + 127) // 128
+    assert 1 <= per_launch < groups <= 2 * per_launch          # exactly two launches
+    edge = per_launch * 128
+    g = torch.Generator(device="cuda").manual_seed(4242)
+    q, k, v = (torch.randn((n_tok, heads, 64), generator=g, device="cuda").to(torch.bfloat16) for _ in range(3))
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((heads, n_tok), float("nan"), device="cuda")
+    s3r.speed3r_dense_attn(q, k, v, out, lse)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()      # every row was written
+    rng = np.random.default_rng(17)
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, edge - 129, edge - 128, edge - 1, edge, edge + 1, edge + 127,
+                                      edge + 128, n_tok - 38, n_tok - 37, n_tok - 2, n_tok - 1],
+                                     rng.choice(n_tok, 49, replace=False)]))
+    ref, ref_lse = oracle.dense_attn(to_host_f32(q), to_host_f32(k), to_host_f32(v), 0.125, q_tok=rows, want_lse=True)
+    take = torch.from_numpy(rows).cuda()
+    assert_close(to_host_f32(out.index_select(0, take)), ref, TOL["bf16"], "dense, two launches")
+    assert float(np.max(np.abs(lse.index_select(1, take).cpu().numpy() - ref_lse))) <= TOL["bf16"]
+
+
 # ------------------------------------------------------------------------------- end to end --
 
 def end_to_end(s3r, oracle, wl, rows=None, with_gate=False, device_gen="cpu", label=None, forced=None,
@@ -257,6 +285,17 @@ def test_config5_pi3_300_views_full_size_sampled_rows(s3r, oracle, topk):
     wl = workloads.config(5, topk=topk)
     rng = np.random.default_rng(9)
     rows = np.unique(np.concatenate([[0, wl.n_blk - 1], rng.choice(wl.n_blk, 14, replace=False)]))
+    end_to_end(s3r, oracle, wl, rows=rows, device_gen="cuda")
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("topk", [16, 128])
+def test_config5_pi3_300_views_full_size_sampled_rows_top16_top128(s3r, oracle, topk):
+    """The two ends of config 5's top-k sweep at full size: 16 (TopK inside the sweep) and 128 (TopK from
+    scores written to memory, 16 384 selected keys per query)."""
+    wl = workloads.config(5, topk=topk)
+    rng = np.random.default_rng(19 + topk)
+    rows = np.unique(np.concatenate([[0, wl.n_blk - 1], rng.choice(wl.n_blk, 10, replace=False)]))
     end_to_end(s3r, oracle, wl, rows=rows, device_gen="cuda")
 
 
