@@ -152,6 +152,21 @@ int speed3r_sparse_global_attn(const void *q, const void *k, const void *v, void
                                int64_t n_tok, int heads, int head_dim, int block, int topk,
                                void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the short form above with its scratch in a fixed device array of
+ * S3R_STATIC_SCRATCH_BYTES that is part of the library's code object, so the call performs no hipMalloc,
+ * hipFree, event creation or any other allocating call; every GPU the library runs on holds its own copy of
+ * that array until the process ends.  Same arguments, same kernels and bit-identical results as
+ * speed3r_sparse_global_attn.  Problems whose speed3r_workspace_bytes(..., n_forced = 0, S3R_BF16) exceeds
+ * S3R_STATIC_SCRATCH_BYTES are refused with S3R_ERR_WORKSPACE before anything is enqueued (8 views x 1374
+ * tokens x 16 heads, block 64, top-16 needs 57 MiB and fits).  All calls on one GPU share that GPU's array:
+ * calls that overlap in time on one GPU (different streams or threads) race; calls ordered on one stream are
+ * fine, and no call depends on what an earlier one left in the array. */
+#define S3R_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int speed3r_sparse_global_attn_noalloc(const void *q, const void *k, const void *v, void *out,
+                                       int64_t n_tok, int heads, int head_dim, int block, int topk,
+                                       void *stream);
+
 /* Dense softmax attention over all n_tok keys (eq. 2 form): out[t,h] = softmax_u(scale q.k) v.
  * The speed-up denominator.  lse (optional) is [heads][n_tok].  Library-held scratch. */
 s3r_status speed3r_dense_attn(const void *q, const void *k, const void *v, void *out, float *lse,

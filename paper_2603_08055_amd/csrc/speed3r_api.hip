@@ -9,9 +9,16 @@
 #include <mutex>
 #include <vector>
 
+// Scratch of speed3r_sparse_global_attn_noalloc: device memory that exists from the moment the code object
+// is loaded, one copy per GPU, so that entry point never allocates.  In host code this name only stands for
+// the symbol; the device address comes from hipGetSymbolAddress (static_scratch below).
+constexpr size_t kStaticScratchBytes = S3R_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local char g_err[512] = "no error";
+thread_local bool t_no_events = false;  // set while an entry point that must not create HIP events runs
 
 s3r_status fail(s3r_status st, const char *fmt, ...)
 {
@@ -175,6 +182,26 @@ s3r_status scratch_get(size_t bytes, void **out)
     return S3R_OK;
 }
 
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+void *g_static_ptr[kMaxDevices] = {};
+
+s3r_status static_scratch(void **out)
+{
+    int dev = 0;
+    S3R_HIP(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(S3R_ERR_UNSUPPORTED, "device ordinal %d unsupported", dev);
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (g_static_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        S3R_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (ptr == nullptr || (reinterpret_cast<uintptr_t>(ptr) & (kAlign - 1)) != 0)
+            return fail(S3R_ERR_HIP, "static scratch has no usable device address (%p)", ptr);
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return S3R_OK;
+}
+
 // ---- per-stage event timing ------------------------------------------------------------------
 bool g_profiling = false;
 struct Span { int stage; hipEvent_t start, stop; };
@@ -195,7 +222,7 @@ struct StageTimer {
     bool on = false;
     StageTimer(int stage, hipStream_t st) : stream(st)
     {
-        if (!g_profiling) return;
+        if (!g_profiling || t_no_events) return;
         std::lock_guard<std::mutex> lock(g_mu);
         span.stage = stage;
         span.start = event_take();
@@ -624,6 +651,32 @@ int speed3r_sparse_global_attn(const void *q, const void *k, const void *v, void
     st = scratch_get(p.workspace_bytes, &p.workspace);
     if (st != S3R_OK) return st;
     return speed3r_sparse_global_attn_ex(&p);
+}
+
+int speed3r_sparse_global_attn_noalloc(const void *q, const void *k, const void *v, void *out, int64_t n_tok,
+                                       int heads, int head_dim, int block, int topk, void *stream)
+{
+    s3r_status st = check_shape(n_tok, heads, head_dim, block, topk, S3R_BF16);
+    if (st != S3R_OK) return st;
+    const size_t need = speed3r_workspace_bytes(n_tok, heads, head_dim, block, topk, 0, S3R_BF16);
+    if (need == 0 || need > kStaticScratchBytes)
+        return fail(S3R_ERR_WORKSPACE,
+                    "problem needs %zu bytes of scratch, the static scratch of this entry point holds %zu: "
+                    "use speed3r_sparse_global_attn_ex with a caller workspace",
+                    need, kStaticScratchBytes);
+    s3r_params p{};
+    p.q = q; p.k = k; p.v = v; p.out = out;
+    p.n_tok = n_tok; p.heads = heads; p.head_dim = head_dim; p.block = block; p.topk = topk;
+    p.dtype = S3R_BF16; p.softmax_scale = 0.f; p.stream = stream;
+    p.workspace_bytes = kStaticScratchBytes;
+    st = static_scratch(&p.workspace);
+    if (st != S3R_OK) return st;
+    // nothing of the previous call's scratch contents is relied on: every flag and counter the kernels
+    // read is cleared by a kernel of this call
+    t_no_events = true;
+    st = speed3r_sparse_global_attn_ex(&p);
+    t_no_events = false;
+    return st;
 }
 
 s3r_status speed3r_pool_blocks(const void *q, const void *k, const void *v, float *qc, float *kc, float *vc,

@@ -41,6 +41,7 @@ EXPORTS = {
     "speed3r_selected_per_row": (_int, [_i64, _int, _int, _int]),
     "speed3r_sparse_global_attn_ex": (_int, [ctypes.POINTER(s3r_params)]),
     "speed3r_sparse_global_attn": (_int, [_vp, _vp, _vp, _vp, _i64, _int, _int, _int, _int, _vp]),
+    "speed3r_sparse_global_attn_noalloc": (_int, [_vp, _vp, _vp, _vp, _i64, _int, _int, _int, _int, _vp]),
     "speed3r_dense_attn": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _int, _flt, _vp]),
     "speed3r_pool_blocks": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _int, _int, _vp]),
     "speed3r_compress_attn_scores": (_int, [_vp, _vp, _vp, _vp, _i64, _vp, _i64, _int, _int, _flt,
@@ -223,6 +224,19 @@ def speed3r_sparse_global_attn(q, k, v, out, block, topk, stream=None):
     _check(load().speed3r_sparse_global_attn(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
                                              _dev(out, "out", q.dtype), n_tok, heads, head_dim,
                                              block, topk, _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def speed3r_sparse_global_attn_noalloc(q, k, v, out, block, topk, stream=None):
+    """The short form on the library's fixed device scratch: the call allocates nothing."""
+    n_tok, heads, head_dim, dt = _qkv(q, k, v)
+    if dt != S3R_BF16:
+        raise TypeError("the short forms are bf16 only; use speed3r_sparse_global_attn_ex")
+    _check(load().speed3r_sparse_global_attn_noalloc(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
+                                                     _dev(out, "out", q.dtype), n_tok, heads, head_dim,
+                                                     block, topk, _stream(stream)))
 
 
 def speed3r_dense_attn(q, k, v, out, lse=None, softmax_scale=0.0, stream=None):

@@ -146,6 +146,21 @@ def test_workspace_bytes_and_shape_validation(s3r):
     assert lib.speed3r_set_kernel_choice(0) == s3r.S3R_OK
 
 
+def test_noalloc_entry_refuses_oversized_problems_on_the_host(s3r):
+    """The entry point for callers that cannot allocate checks the size against its fixed scratch before any
+    device work (the pointers are never dereferenced)."""
+    lib = s3r.load()
+    text = open(HEADER).read()
+    assert re.search(r"#define\s+S3R_STATIC_SCRATCH_BYTES\s+\(\(size_t\)64 << 20\)", text)
+    assert s3r.STATIC_SCRATCH_BYTES == 64 << 20
+    assert s3r.speed3r_workspace_bytes(8 * 1374, 16, 64, 64, 16, s3r.S3R_BF16) <= s3r.STATIC_SCRATCH_BYTES
+    assert lib.speed3r_sparse_global_attn_noalloc(0x1000, 0x1000, 0x1000, 0x2000, 100 * 1374, 16, 64, 64, 32,
+                                                  None) == s3r.S3R_ERR_WORKSPACE
+    assert "static scratch" in s3r.speed3r_last_error()
+    assert lib.speed3r_sparse_global_attn_noalloc(0x1000, 0x1000, 0x1000, 0x2000, 1374, 16, 32, 64, 32,
+                                                  None) == s3r.S3R_ERR_UNSUPPORTED
+
+
 def test_binding_rejects_cpu_tensors(s3r):
     import torch
     q = torch.zeros((64, 1, 64), dtype=torch.bfloat16)
