@@ -297,8 +297,11 @@ __device__ __forceinline__ void compress_block(
                     oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, p[w], oacc[dt], 0, 0, 0);
                 }
         };
-        // before the overlapped region: keys that do not exist, the running maximum (rarely raised)
-        auto soft_pre = [&](int kt, int mt, floatx16 &acc) __attribute__((always_inline)) {
+        // before the overlapped region: keys that do not exist, the running maximum (rarely raised).
+        // p_pending: the probabilities of the half step before, whose P.V product has not been issued yet (it
+        // runs inside the half step that follows): they were formed against the old maximum, so a raise
+        // rescales them together with the accumulators (Alg. 1's rescaling applies to everything summed so far).
+        auto soft_pre = [&](int kt, int mt, floatx16 &acc, bf16x8 (&p_pending)[2]) __attribute__((always_inline)) {
             if (kt * 64 + mt * 32 + 32 > n_blk) {
                 asm volatile("" ::: "memory");  // keep this rare path a real branch
 #pragma unroll
@@ -319,6 +322,10 @@ __device__ __forceinline__ void compress_block(
                 for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+#pragma unroll
+                for (int w = 0; w < 2; ++w)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) p_pending[w][e] = static_cast<bf16_t>(static_cast<float>(p_pending[w][e]) * alpha);
             }
         };
         // One half step, written out as 16 slots of vector work on one score register each, every other
@@ -398,12 +405,12 @@ __device__ __forceinline__ void compress_block(
             const unsigned long long fw = decltype(forced_tag)::value ? forced_words[kt] : 0ull;  // wave-uniform
             const int knext = (kst + 1 == 3) ? 0 : kst + 1;
             // half step 0: softmax here; P.V of the previous half step and scores of half step 1 on the matrix pipe
-            soft_pre(kt, 0, sacc0);
+            soft_pre(kt, 0, sacc0, p1);
             half_step(forced_tag, fw, 0, sacc0, bmax[PAR], p0, vprev, 1, p1, kst, 1, sacc1);
             publish(kt + 1);  // group kt + 1: keys of step kt + 1, values of step kt
             // half step 1: softmax here; P.V of half step 0 and the first scores of the next step on the matrix pipe
             // (after the last step: a copy of its keys, result unused)
-            soft_pre(kt, 1, sacc1);
+            soft_pre(kt, 1, sacc1, p0);
             half_step(forced_tag, fw, 1, sacc1, bmax[PAR], p1, kst, 0, p0, knext, 0, sacc0);
             vprev = kst;
             kst = knext;

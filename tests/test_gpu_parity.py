@@ -350,6 +350,69 @@ def test_compress_attn_topk_random(s3r, oracle, n_blk, heads, k, accurate):
     assert_close(o_comp, ref, TOL["f32"] if accurate else TOL["bf16"], "o_comp")
 
 
+@pytest.mark.parametrize("accurate", [False, True])
+@pytest.mark.parametrize("route", ["in_sweep", "stored"])
+@pytest.mark.parametrize("step", [0.25, 0.5, -0.25])
+def test_compress_attn_running_maximum_rises_along_the_keys(s3r, oracle, route, accurate, step):
+    """Logits that grow steadily with the key index (by `step` per key, i.e. by 8 or 16 per 32 keys): the
+    online softmax has to raise its running maximum over and over while earlier partial sums are still
+    being accumulated (eq. 3, Alg. 1's rescaling of O and l).  A negative step puts the maximum first.
+    The dominant components are multiples of 0.25, exact in every operand format the sweeps use, so that
+    what is tested is the rescaling and not the rounding of logits of size 75 to 150."""
+    n_blk, heads = 300, 2
+    rng = np.random.default_rng(int(abs(step) * 100) + 3)
+    qc = np.zeros((heads, n_blk, 64), dtype=np.float32)
+    kc = np.zeros((heads, n_blk, 64), dtype=np.float32)
+    qc[:, :, 0] = 8.0
+    kc[:, :, 0] = step * np.arange(n_blk, dtype=np.float32)          # logit_j = 0.125 * 8 * step * j
+    qc[:, :, 1:] = 0.01 * rng.standard_normal((heads, n_blk, 63)).astype(np.float32)
+    kc[:, :, 1:] = 0.01 * rng.standard_normal((heads, n_blk, 63)).astype(np.float32)
+    vc = rng.standard_normal((heads, n_blk, 64)).astype(np.float32)
+    s64 = oracle.scores(qc.astype(np.float64), kc.astype(np.float64))
+    ref = oracle.compressed_attn(s64, vc.astype(np.float64), 0.125)
+    if route == "in_sweep":
+        o_comp, idx = compress_topk_case(s3r, qc, kc, vc, 16, accurate, scale=0.125)
+        check_topk_sets(s64, idx, 16)
+    else:
+        s_dev = torch.full((heads, n_blk, n_blk), float("nan"), device="cuda")
+        oc_dev = torch.full((heads, n_blk, 64), float("nan"), device="cuda")
+        s3r.speed3r_compress_attn_scores(torch.from_numpy(qc).cuda(), torch.from_numpy(kc).cuda(),
+                                         torch.from_numpy(vc).cuda(), s_dev, oc_dev, 0.125, accurate)
+        torch.cuda.synchronize()
+        o_comp = oc_dev.cpu().numpy()
+    # fp32-grade route: scores from bf16 hi/lo operand pairs are good to 4e-5 |qc||kc| (the bound the score
+    # test holds them to), which at logits of up to 135 is what limits the output
+    tol_f32 = max(TOL["f32"], 4e-5 * 8.0 * abs(step) * n_blk * 0.125)
+    assert_close(o_comp, ref, tol_f32 if accurate else TOL["bf16"], f"o_comp, {route}, step {step}")
+
+
+@pytest.mark.parametrize("block,kk", [(64, 40), (128, 20), (32, 60), (16, 100), (64, 120)])
+def test_select_attn_running_maximum_rises_along_the_keys(s3r, oracle, block, kk):
+    """The same for the selection branch (eq. 6, Alg. 2's rescaling): keys whose logits grow by 0.25 per
+    token along the sequence, every block selected in ascending order."""
+    n_tok, heads = kk * block, 2
+    g = torch.Generator().manual_seed(block + kk)
+    q = 0.05 * torch.randn((n_tok, heads, 64), generator=g)
+    k = 0.05 * torch.randn((n_tok, heads, 64), generator=g)
+    v = torch.randn((n_tok, heads, 64), generator=g)
+    q[:, :, 0] = 4.0
+    k[:, :, 0] = 0.5 * torch.arange(n_tok, dtype=torch.float32)[:, None] / (block / 16)   # logit step 0.25 * 16 / block per token
+    q, k, v = (x.to(torch.bfloat16) for x in (q, k, v))
+    n_blk = n_tok // block
+    idx = torch.arange(kk, dtype=torch.int32).expand(heads, n_blk, kk).contiguous()
+    out = torch.full(q.shape, float("nan"), dtype=q.dtype, device="cuda")
+    lse = torch.full((heads, n_tok), float("nan"), device="cuda")
+    s3r.speed3r_select_attn(q.cuda(), k.cuda(), v.cuda(), idx.cuda(), out, block, lse=lse)
+    torch.cuda.synchronize()
+    rows = np.array([0, n_blk // 2, n_blk - 1])
+    o_ref, l_ref = oracle.select_attn(to_host_f32(q), to_host_f32(k), to_host_f32(v), block, idx.numpy()[:, rows], 0.125, rows)
+    tok = (rows[:, None] * block + np.arange(block)[None, :]).reshape(-1)
+    got = to_host_f32(out.index_select(0, torch.from_numpy(tok).cuda()))
+    assert_close(got, o_ref.reshape(-1, heads, 64), TOL["bf16"], f"o_sel rising maximum B={block}")
+    got_l = lse.index_select(1, torch.from_numpy(tok).cuda()).cpu().numpy()
+    assert float(np.max(np.abs(got_l - l_ref.reshape(heads, -1)))) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("n_blk,k,offset,noise", [(1000, 16, 0.5, 0.05), (1500, 64, 0.5, 0.05), (700, 8, 0.25, 0.2)])
 def test_compress_attn_topk_large_common_component(s3r, oracle, n_blk, k, offset, noise):
     """Pooled keys that share a large common vector: all scores of a row sit within a narrow band on
