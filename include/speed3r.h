@@ -229,6 +229,22 @@ s3r_status speed3r_select_attn(const void *q, const void *k, const void *v, cons
 
 /* ---- utilities ------------------------------------------------------------------------------ */
 
+/* Measurement of what the data movement of the selection stage (eq. 6 / Alg. 2) costs by itself: the
+ * selection kernel for bf16 blocks of 64 or 128 tokens with its arithmetic taken out.  It walks idx
+ * ([heads][n_blk][kk], as in speed3r_select_attn) with the same work mapping, brings every selected K/V
+ * unit into LDS through the same ring with the same waits and barriers, reads Q and writes `out` (which
+ * receives a copy of q).  Time it with speed3r_set_profiling / speed3r_get_stage_ms (stage SELECT): the
+ * real kernel cannot be faster than this on the same index lists.
+ *   ring_stages: 0 or 2 = the real kernels' two-stage LDS ring; 3, 4 = deeper rings (more units on their
+ *                way per workgroup);
+ *   wg_per_cu  : 0 = as many workgroups per CU as fit (the real kernels' five); 1..5 = at most that many
+ *                (fewer query blocks in progress per XCD: more of the units neighbouring query blocks share
+ *                are still in that XCD's L2 when the second one asks).
+ * Library-held scratch. */
+s3r_status speed3r_probe_select_loads(const void *q, const void *k, const void *v, const int32_t *idx,
+                                      void *out, int64_t n_tok, int heads, int head_dim, int block, int kk,
+                                      int ring_stages, int wg_per_cu, void *stream);
+
 /* When enabled, every entry point brackets each kernel launch with HIP events on the call's own
  * stream and keeps them until speed3r_get_stage_ms reads them (process-wide switch; default off). */
 s3r_status speed3r_set_profiling(int enable);

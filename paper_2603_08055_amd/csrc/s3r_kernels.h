@@ -184,6 +184,10 @@ struct SelectArgs {
     int n_common = 0;          // selection: entries of every index row known to be the same in all rows (forced blocks)
     float scale;
     bool is_bf16;
+    bool loads_only = false;   // MFMA selection, blocks of 64 / 128 tokens: move the K/V units, skip the arithmetic
+                               // (a measurement of the stage's data movement; `out` receives the Q rows)
+    int probe_stages = 0;      // loads_only: LDS ring stages, 2 (the real kernels', also 0), 3 or 4
+    int probe_wg_per_cu = 0;   // loads_only: at most this many workgroups per CU (0: as many as fit)
     SelectExtras x;
 };
 
@@ -197,5 +201,6 @@ hipError_t launch_select_generic(const SelectArgs &a, hipStream_t stream);
 
 // bf16 MFMA kernels (any supported block size).
 hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream);
+
 
 }  // namespace s3r

@@ -29,42 +29,10 @@
 // unit; probabilities then range up to 2^kRescaleSlack, which fp32 sums and bf16 operands carry as
 // well as values below 1, and the final normalisation uses the same maximum: plain softmax.
 #include "s3r_device.h"
+#include "s3r_attn_device.h"
 #include "s3r_kernels.h"
 
 namespace s3r {
-
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-constexpr float kRescaleSlack = 8.0f;
-constexpr int kUnitKeys = 64;
-constexpr int kUnitElems = kUnitKeys * 64;  // bf16 elements of one K (or V) unit: 8 KiB
-
-__device__ __forceinline__ float max_with_other_half(float x)
-{
-    // v_permlane32_swap exchanges the two half-waves: one VALU instruction, no LDS traffic
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-
-__device__ __forceinline__ float sum_with_other_half(float x)
-{
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// One LDS-direct load: 64 lanes x 16 bytes from `src` (per-lane address) to LDS byte address
-// `lds_byte` (wave-uniform) + 16 * lane.  Counted by vmcnt like any vector memory load.
-__device__ __forceinline__ void lds_dma_16(const void *src, unsigned lds_byte)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_byte)
-                 : "memory", "m0");
-}
-
-template <int N> __device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
 
 // QW    : waves per workgroup = query rows / 32 (block / 32 for selection: one query block)
 // DENSE : every key unit instead of an index list
@@ -83,7 +51,11 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 //         lists hold is fetched into LDS once for both, and a pair of waves sits out the units only the
 //         other pair's list holds.  For long lists that are mostly common to all query blocks (forced
 //         blocks), where the traffic from the L2s into LDS is what binds.
-template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ, bool PAIR = false>
+// PROBE : measurement only.  The kernel walks its index list and moves every K/V unit into LDS exactly as the
+//         real one does (same work mapping, ring, waits and barriers) but does no arithmetic on them; it
+//         writes its Q rows to `out`, so Q is read and `out` written as well.  Its run time is what the data
+//         movement of the selection stage costs by itself.
+template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ, bool PAIR = false, bool PROBE = false>
 __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ kb, const bf16_t *__restrict__ vb,
     const int32_t *__restrict__ idx, const float *__restrict__ o_comp, const bf16_t *__restrict__ gate,
@@ -478,6 +450,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         if (s + D <= n_steps) wait_vmcnt<CPW *(D - 1)>(); else wait_vmcnt<0>();
         lds_barrier();
         if (s + D < n_steps) issue(s + D, stage_ahead);
+        if constexpr (PROBE) continue;
         const unsigned long long vmask = unit_mask(s);
         if (vmask == 0ull) continue;  // second half of a short last block
         scores(&ring[stage][0]);
@@ -487,6 +460,12 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     }
 
     if (!row_valid) return;
+    if constexpr (PROBE) {
+        static_assert(!PROBE || (!DENSE && !PAIR && !SMALL && !EXTRA), "probe of the plain selection kernels only");
+#pragma unroll
+        for (int s = 0; s < 4; ++s) *reinterpret_cast<bf16x8 *>(out + (trow * heads + h) * 64 + 16 * s + 8 * g) = qb[s];
+        return;
+    }
     const float l_tot = sum_with_other_half(l_run);
     const float inv = (EXTRA && DENSE && l_tot == 0.f) ? 0.f : 1.f / l_tot;  // (a key split of empty units only)
     if (lse != nullptr && g == 0)
@@ -541,9 +520,21 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         }
 }
 
-template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ, bool PAIR>
+template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ, bool PAIR, bool PROBE = false>
 static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
 {
+    // The load probe can hold the number of workgroups per CU down: unused dynamic LDS on top of the ring makes
+    // each workgroup take 1 / probe_wg_per_cu of a CU's 160 KiB.
+    unsigned pad_bytes = 0;
+    if (PROBE && a.probe_wg_per_cu > 0) {
+        const int ring = NS * 2 * kUnitElems * 2, share = (160 * 1024 / a.probe_wg_per_cu) & ~1023;
+        if (share < ring) return hipErrorInvalidValue;
+        pad_bytes = static_cast<unsigned>(share - ring);
+        const hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void *>(&select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ, PAIR, PROBE>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(pad_bytes));
+        if (e != hipSuccess) return e;
+    }
     const int64_t rows_per_group = 32 * QW;
     const int64_t groups = DENSE ? (a.n_tok + rows_per_group - 1) / rows_per_group : PAIR ? (a.n_blk + 1) / 2 : a.n_blk;
     const int64_t sets = groups;
@@ -563,8 +554,8 @@ static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
         const int64_t ns = (sets - s0 < per_launch) ? sets - s0 : per_launch;
         const int64_t n_split = (DENSE && a.x.n_split > 1) ? a.x.n_split : 1;
         const int64_t grid = (map_mode == 2) ? (ns + 7) / 8 * 8 * a.heads : ns * n_split * a.heads;
-        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ, PAIR>), dim3(static_cast<unsigned>(grid)),
-                           dim3(QW * 64), 0, stream, static_cast<const bf16_t *>(a.q),
+        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ, PAIR, PROBE>), dim3(static_cast<unsigned>(grid)),
+                           dim3(QW * 64), pad_bytes, stream, static_cast<const bf16_t *>(a.q),
                            static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
                            a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
                            static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.block,
@@ -602,6 +593,21 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
         return hipErrorInvalidValue;
     }
     if (a.n_keys != a.n_tok || a.n_keys2 != 0) return hipErrorInvalidValue;  // selection: keys = the query sequence
+    if (a.loads_only) {  // the data movement of the plain kernels for blocks of 64 and 128 tokens, no arithmetic
+        if (a.x.o_comp_tok != nullptr || a.x.in.tok != 0 || a.qmap.period != 0 || a.blk_len != nullptr) return hipErrorInvalidValue;
+        const int ns = a.probe_stages == 0 ? 2 : a.probe_stages;
+        if (a.block == 64) {
+            if (ns == 2) return run_select_x<2, false, 2, false, false, false, false, true>(a, stream);
+            if (ns == 3) return run_select_x<2, false, 3, false, false, false, false, true>(a, stream);
+            if (ns == 4) return run_select_x<2, false, 4, false, false, false, false, true>(a, stream);
+        }
+        if (a.block == 128) {
+            if (ns == 2) return run_select_x<4, false, 2, false, false, true, false, true>(a, stream);
+            if (ns == 3) return run_select_x<4, false, 3, false, false, true, false, true>(a, stream);
+            if (ns == 4) return run_select_x<4, false, 4, false, false, true, false, true>(a, stream);
+        }
+        return hipErrorInvalidValue;
+    }
     // Long index rows (forced blocks, which every query block shares and the L2s keep) are bound by the loop
     // and by the traffic from the L2s into LDS rather than by the memory fabric: two neighbouring query blocks
     // per workgroup, each common unit fetched once for both (PAIR), with each unit's arithmetic overlapping

@@ -815,6 +815,46 @@ s3r_status speed3r_select_attn(const void *q, const void *k, const void *v, cons
     return S3R_OK;
 }
 
+s3r_status speed3r_probe_select_loads(const void *q, const void *k, const void *v, const int32_t *idx, void *out,
+                                      int64_t n_tok, int heads, int head_dim, int block, int kk, int ring_stages,
+                                      int wg_per_cu, void *stream)
+{
+    s3r_status st = check_shape(n_tok, heads, head_dim, block, kk, S3R_BF16);
+    if (st != S3R_OK) return st;
+    if (block != 64 && block != 128) return fail(S3R_ERR_UNSUPPORTED, "the load probe covers blocks of 64 and 128 tokens");
+    if (ring_stages != 0 && (ring_stages < 2 || ring_stages > 4))
+        return fail(S3R_ERR_INVALID_ARG, "ring_stages (%d) must be 0 or 2..4", ring_stages);
+    if (wg_per_cu < 0 || wg_per_cu > 5 || (wg_per_cu > 0 && 160 / wg_per_cu < 16 * (ring_stages ? ring_stages : 2)))
+        return fail(S3R_ERR_INVALID_ARG, "wg_per_cu (%d) must be 0 or 1..5 and leave each workgroup room for a ring of %d stages of 16 KiB",
+                    wg_per_cu, ring_stages ? ring_stages : 2);
+    if (!q || !k || !v || !idx || !out) return fail(S3R_ERR_INVALID_ARG, "q, k, v, idx and out must be non-null");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+        return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    const int64_t n_blk = (n_tok + block - 1) / block;
+    if (kk > n_blk) return fail(S3R_ERR_INVALID_ARG, "k (%d) exceeds the number of blocks (%lld)", kk, static_cast<long long>(n_blk));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t blocked = align_up(static_cast<size_t>(heads) * n_blk * block * 64 * 2);
+    void *ws = nullptr;
+    st = scratch_get(2 * blocked, &ws);
+    if (st != S3R_OK) return st;
+    s3r::SelectArgs a{};
+    a.kb = ws;
+    a.vb = at(ws, blocked);
+    {
+        StageTimer tm(S3R_STAGE_POOL, s);
+        S3R_HIP(s3r::launch_pool(q, k, v, nullptr, nullptr, nullptr, const_cast<void *>(a.kb), const_cast<void *>(a.vb),
+                                 n_tok, heads, block, true, s3r::TokenMap{}, s3r::InStride{}, s),
+                "pool kernel launch");
+    }
+    a.q = q; a.k = k; a.v = v; a.idx = idx; a.out = out;
+    a.n_tok = n_tok; a.n_keys = n_tok; a.lse_stride = n_tok; a.n_blk = n_blk;
+    a.heads = heads; a.block = block; a.kk = kk; a.scale = 1.f; a.is_bf16 = true; a.loads_only = true;
+    a.probe_stages = ring_stages; a.probe_wg_per_cu = wg_per_cu;
+    StageTimer tm(S3R_STAGE_SELECT, s);
+    S3R_HIP(s3r::launch_select_mfma(a, s), "select (loads only) kernel launch");
+    return S3R_OK;
+}
+
 s3r_status speed3r_dense_attn(const void *q, const void *k, const void *v, void *out, float *lse, int64_t n_tok,
                               int heads, int head_dim, s3r_dtype dtype, float softmax_scale, void *stream)
 {

@@ -50,6 +50,7 @@ EXPORTS = {
     "speed3r_topk_blocks": (_int, [_vp, _i64, _vp, _i64, _int, _int, _vp]),
     "speed3r_select_attn": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _int, _int,
                                    _int, _int, _int, _flt, _vp]),
+    "speed3r_probe_select_loads": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _int, _int, _int, _int, _int, _int, _vp]),
     "speed3r_set_profiling": (_int, [_int]),
     "speed3r_get_stage_ms": (_int, [ctypes.POINTER(_flt), ctypes.POINTER(_int)]),
     "speed3r_set_kernel_choice": (_int, [_int]),
@@ -297,6 +298,17 @@ def speed3r_select_attn(q, k, v, idx, out, block, *, o_comp=None, gate_logits=No
                                       _dev(out, "out", q.dtype), _dev(o_sel, "o_sel", q.dtype),
                                       _dev(lse, "lse", torch.float32), n_tok, heads, head_dim, block,
                                       idx.shape[2], dt, float(softmax_scale), _stream(stream)))
+
+
+def speed3r_probe_select_loads(q, k, v, idx, out, block, ring_stages=0, wg_per_cu=0, stream=None):
+    """The selection kernel's data movement without its arithmetic (measurement utility); out receives q.
+    ring_stages 0/2..4 and wg_per_cu 0/1..5 vary the LDS ring depth and the workgroups per CU."""
+    n_tok, heads, head_dim, dt = _qkv(q, k, v)
+    if dt != S3R_BF16 or idx.dim() != 3 or idx.shape[0] != heads:
+        raise ValueError("bf16 q, k, v and idx [heads, n_blk, kk] expected")
+    _check(load().speed3r_probe_select_loads(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(idx, "idx", torch.int32),
+                                             _dev(out, "out", q.dtype), n_tok, heads, head_dim, block, idx.shape[2],
+                                             int(ring_stages), int(wg_per_cu), _stream(stream)))
 
 
 def speed3r_set_profiling(enable: bool):

@@ -765,6 +765,26 @@ def test_full_topk_equals_dense_kernel(s3r, oracle):
     assert_close(to_host_f32(dense), ref, TOL["bf16"], "dense kernel vs dense oracle")
 
 
+@pytest.mark.parametrize("block,stages,wg", [(64, 0, 0), (64, 3, 2), (64, 4, 1), (128, 0, 0), (128, 2, 2), (128, 4, 1)])
+def test_load_probe_moves_data_and_leaves_q(s3r, block, stages, wg):
+    """The measurement kernel (the selection kernel without its arithmetic) must run its whole index walk with
+    every ring depth and occupancy limit, write a copy of q, and refuse what it does not cover."""
+    n_tok, heads, kk = 37 * block + 11, 3, 9
+    g = torch.Generator().manual_seed(block + stages)
+    q, k, v = (torch.randn((n_tok, heads, 64), generator=g).to(torch.bfloat16).cuda() for _ in range(3))
+    n_blk = (n_tok + block - 1) // block
+    idx = torch.stack([torch.stack([torch.sort(torch.randperm(n_blk, generator=g)[:kk]).values for _ in range(n_blk)])
+                       for _ in range(heads)]).to(torch.int32).cuda()
+    out = torch.full_like(q, float("nan"))
+    s3r.speed3r_probe_select_loads(q, k, v, idx, out, block, stages, wg)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), q.view(torch.int16))
+    with pytest.raises(s3r.Speed3rError):
+        s3r.speed3r_probe_select_loads(q, k, v, idx, out, block, 5, 0)
+    with pytest.raises(s3r.Speed3rError):
+        s3r.speed3r_probe_select_loads(q, k, v, idx, out, block, 4, 3)          # three rings of 64 KiB do not fit a CU's 160 KiB
+
+
 def test_deterministic_and_stream(s3r):
     wl = workloads.config(2, views=2)
     q, k, v = (x.cuda() for x in workloads.make_inputs(wl))
