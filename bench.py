@@ -265,7 +265,10 @@ def main():
             s3r.speed3r_set_profiling(False)
             return p_ms["select"] / max(p_n["select"], 1)
 
-        probe_ms = time_probe(0, 0)
+        # the probe at the occupancy of the kernel that ran: long rows on long sequences run two workgroups per
+        # CU (64 query blocks in progress per XCD), everything else as many as fit
+        probe_wg = 2 if (wl.block == 64 and kk >= 40 and seq.n_blk >= 3000) else 0
+        probe_ms = time_probe(0, probe_wg)
         assert torch.equal(probe_out, q), "the load probe must leave a copy of q in its output"
         sweep = None
         if args.probe_sweep:
@@ -278,8 +281,10 @@ def main():
         del probe_out
         s3r.speed3r_release_scratch()
         roofline["data_movement_bound"] = {
-            "bound": "fabric", "what": "select_mfma_kernel<PROBE>: same index lists, work mapping, LDS ring, waits and "
-                                       "barriers, Q read and out written, no MFMA / softmax",
+            "bound": "fabric", "what": "select_mfma_kernel<PROBE>: the same index lists walked with the same work mapping, "
+                                       "K/V units moved into LDS through a two-stage ring, Q read and out written, "
+                                       "no MFMA / softmax; " + (f"{probe_wg} workgroups per CU like the kernel that ran"
+                                                                if probe_wg else "as many workgroups per CU as fit"),
             "loads_only_ms": probe_ms, "kernel_ms": sel_ms, "frac": probe_ms / sel_ms,
             "loads_only_GBps": (kv_bytes + qo_bytes) / (probe_ms * 1e-3) / 1e9,
             "mfma_frac_if_arithmetic_were_free": sel_flops / (probe_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}

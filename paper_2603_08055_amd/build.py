@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspeed3r.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["pool.hip", "split.hip", "compress.hip", "topk.hip", "select_generic.hip",
-           "select_mfma.hip", "speed3r_api.hip"]
+           "select_mfma.hip", "select_pipe.hip", "speed3r_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed-fp32 VALU instructions

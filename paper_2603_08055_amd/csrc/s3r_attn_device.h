@@ -32,6 +32,21 @@ __device__ __forceinline__ void lds_dma_16(const void *src, unsigned lds_byte)
                  : "memory", "m0");
 }
 
+// Four consecutive 1 KiB chunks of a contiguous run with a wave-uniform start address: lane L's 16 bytes of chunk
+// c come from base + voff + c KiB (voff = 16 L, or 16 L + 4096 for the second half of an 8 KiB run: the
+// constant offset of the instruction reaches 4095 bytes) and land at LDS byte lds_byte + c KiB + 16 L: the
+// instruction's constant offset moves the LDS address along with the global one, so M0 is set once.
+__device__ __forceinline__ void lds_dma_16_x4(const void *base, unsigned voff, unsigned lds_byte)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, %1\n\t"
+                 "global_load_lds_dwordx4 %0, %1 offset:1024\n\t"
+                 "global_load_lds_dwordx4 %0, %1 offset:2048\n\t"
+                 "global_load_lds_dwordx4 %0, %1 offset:3072"
+                 ::"v"(voff), "s"(base), "s"(lds_byte)
+                 : "memory", "m0");
+}
+
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");

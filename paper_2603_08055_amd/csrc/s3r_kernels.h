@@ -202,5 +202,9 @@ hipError_t launch_select_generic(const SelectArgs &a, hipStream_t stream);
 // bf16 MFMA kernels (any supported block size).
 hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream);
 
+// bf16 MFMA selection for plain index rows (at most 128 blocks of 64 tokens each, packed q, per-block compressed
+// outputs): few workgroups per CU, each wave software-pipelined (launch_select_mfma routes here).
+hipError_t launch_select_pipe(const SelectArgs &a, hipStream_t stream);
+
 
 }  // namespace s3r

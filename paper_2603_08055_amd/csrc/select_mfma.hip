@@ -593,6 +593,11 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
         return hipErrorInvalidValue;
     }
     if (a.n_keys != a.n_tok || a.n_keys2 != 0) return hipErrorInvalidValue;  // selection: keys = the query sequence
+    // plain rows of at most 128 blocks of 64 tokens: the software-pipelined kernel of select_pipe.hip (rows that
+    // are mostly forced blocks stay with the PAIR variant below)
+    if (a.block == 64 && !a.loads_only && a.kk <= 128 && !(a.kk > 96 && 2 * a.n_common >= a.kk) &&
+        a.x.o_comp_tok == nullptr && a.x.in.tok == 0)
+        return launch_select_pipe(a, stream);
     if (a.loads_only) {  // the data movement of the plain kernels for blocks of 64 and 128 tokens, no arithmetic
         if (a.x.o_comp_tok != nullptr || a.x.in.tok != 0 || a.qmap.period != 0 || a.blk_len != nullptr) return hipErrorInvalidValue;
         const int ns = a.probe_stages == 0 ? 2 : a.probe_stages;

@@ -169,6 +169,52 @@ def test_select_attn_mfma_bf16(s3r, oracle, block, n_tok, kk, with_gate):
     select_case(s3r, oracle, "bf16", n_tok, 3, block, kk, 0, with_gate, 1000 + n_tok)
 
 
+@pytest.mark.parametrize("kk,rising", [(41, False), (64, False), (40, True), (97, False), (128, True)])
+def test_select_attn_long_rows_on_long_sequences(s3r, oracle, kk, rising):
+    """Rows of 40 or more blocks on sequences of 3000 or more blocks of 64 tokens run with two pairs of waves
+    per query block, each pair on every second unit of the list, their two partial softmaxes combined at
+    the end (eq. 6 over all selected keys): odd and even row lengths, a ragged last block, gate and merge,
+    and (rising) logits that grow along the list so that both pairs keep raising their running maxima.
+    Sampled query blocks against the oracle."""
+    block, heads = 64, 2
+    n_blk = 3001
+    n_tok = n_blk * block - 17
+    g = torch.Generator().manual_seed(1000 + kk)
+    q, k, v = (torch.randn((n_tok, heads, 64), generator=g) for _ in range(3))
+    if rising:
+        q, k = 0.05 * q, 0.05 * k
+        q[:, :, 0] = 4.0
+        k[:, :, 0] = torch.arange(n_tok, dtype=torch.float32)[:, None] / 256.0       # logits grow by 8 per 64 x 64 keys
+    q, k, v = (x.to(torch.bfloat16) for x in (q, k, v))
+    gate = torch.randn((n_tok, heads, 64), generator=g).to(torch.bfloat16)
+    oc = torch.randn((heads, n_blk, 64), generator=g)
+    rows = np.array([0, 1, 1500, n_blk - 2, n_blk - 1])
+    rng = np.random.default_rng(kk)
+    idx = np.zeros((heads, n_blk, kk), dtype=np.int32)
+    idx[:] = np.sort(rng.choice(n_blk, kk, replace=False))[None, None, :]
+    for h in range(heads):
+        for r in rows:
+            pick = np.sort(rng.choice(n_blk - 1, kk - 1, replace=False))
+            idx[h, r] = np.sort(np.concatenate([pick, [n_blk - 1]]))          # the ragged last block in every sampled row
+    out = torch.full(q.shape, float("nan"), dtype=q.dtype, device="cuda")
+    o_sel = torch.full(q.shape, float("nan"), dtype=q.dtype, device="cuda")
+    lse = torch.full((heads, n_tok), float("nan"), device="cuda")
+    s3r.speed3r_select_attn(q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(idx).cuda(), out, block, o_comp=oc.cuda(),
+                            gate_logits=gate.cuda(), o_sel=o_sel, lse=lse)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    qf, kf, vf = (to_host_f32(x) for x in (q, k, v))
+    ref_sel, ref_lse = oracle.select_attn(qf, kf, vf, block, idx[:, rows], 0.125, rows)
+    ref_out = oracle.merge(oc.numpy().astype(np.float64)[:, rows], ref_sel, to_host_f32(gate), n_tok, block, rows)
+    tok, sel_v = oracle.rows_to_tokens(ref_sel, rows, n_tok, block)
+    _, out_v = oracle.rows_to_tokens(ref_out, rows, n_tok, block)
+    _, lse_v = oracle.rows_to_tokens(ref_lse.transpose(1, 2, 0), rows, n_tok, block)
+    take = torch.from_numpy(np.asarray(tok)).cuda()
+    assert_close(to_host_f32(o_sel.index_select(0, take)), sel_v, TOL["bf16"], f"o_sel k={kk}")
+    assert_close(to_host_f32(out.index_select(0, take)), out_v, TOL["bf16"], f"out k={kk}")
+    assert float(np.max(np.abs(lse.index_select(1, take).cpu().numpy().T - lse_v))) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("block,n_tok,kk", [(16, 200, 5), (32, 333, 4), (64, 1000, 5), (128, 700, 3)])
 def test_select_attn_generic(s3r, oracle, dtype, block, n_tok, kk):
