@@ -61,6 +61,9 @@ typedef enum {
 
 typedef enum { S3R_F32 = 0, S3R_BF16 = 1 } s3r_dtype;
 
+/* Bits of the device status word (s3r_params.status). */
+enum { S3R_DIAG_FORCED_RANGE = 1, S3R_DIAG_FORCED_ORDER = 2 };
+
 /* Stages of the path, for speed3r_get_stage_ms(). */
 enum {
     S3R_STAGE_POOL = 0,     /* block pooling (+ K/V tile re-layout for the MFMA path) */
@@ -78,10 +81,17 @@ typedef struct s3r_params {
     const void *gate_logits; /* in, optional (NULL: g = 1/2), same layout and dtype as q        */
     /* Forced blocks (Sec. 3.3: the fixed global context of the VGGT variant, e.g. all blocks of the
      * reference view): n_forced block indices in DEVICE memory that every query block attends in
-     * addition to its TopK, which then runs over the other blocks only.  The list must be
-     * ascending, distinct and within [0, n_blk); out-of-range entries are clamped, not diagnosed. */
+     * addition to its TopK, which then runs over the other blocks only.  The list must be strictly
+     * ascending and within [0, n_blk).  The library cannot look at device memory without a host
+     * synchronisation, which it never does: a list that breaks this is reported through `status`
+     * below; the call itself then runs on the list with its entries clamped into range (memory-safe;
+     * a block listed twice is attended twice, so the result is not the paper's). */
     const int32_t *forced_blocks; /* in, optional (NULL: none)                                   */
     int n_forced;            /* 0 when forced_blocks is NULL                                    */
+    /* out, optional: one device word, written by the call (stream-ordered like every output): 0, or
+     * S3R_DIAG_FORCED_RANGE | S3R_DIAG_FORCED_ORDER for a forced_blocks list with an entry outside
+     * [0, n_blk) / not strictly ascending.  4-byte aligned. */
+    int32_t *status;
     /* Special tokens (Sec. 3.2 eqs. 1-2 and "Final Output"): the n_tok rows come in views of
      * tokens_per_view rows, the first special_per_view of each being special (camera / register)
      * tokens.  Those rows get plain softmax attention over ALL n_tok rows; the remaining image rows,

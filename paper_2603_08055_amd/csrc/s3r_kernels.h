@@ -131,9 +131,10 @@ hipError_t launch_topk_candidates(const float *qc, const float *kc, const int32_
                                   int cap, int32_t *idx, int64_t n_blk, int heads, int k, hipStream_t stream);
 
 // Forced (always attended) blocks: clamp the caller's list into `forced_clean` and build the
-// 64-key bit words for the compression kernel.
+// 64-key bit words for the compression kernel.  status (optional, device): receives 0, or bit 0 = an entry
+// out of range, bit 1 = list not strictly ascending.  With n_forced == 0 only *status is written.
 hipError_t launch_forced_prepare(const int32_t *forced, int n_forced, int64_t n_blk, int32_t *forced_clean,
-                                 unsigned long long *forced_words, hipStream_t stream);
+                                 unsigned long long *forced_words, int32_t *status, hipStream_t stream);
 
 // out[r][0 .. k_dyn + n_forced) = ascending merge of dyn[r][0 .. k_dyn) and forced_clean[0 .. n_forced).
 hipError_t launch_merge_forced(const int32_t *dyn, int k_dyn, const int32_t *forced_clean, int n_forced,

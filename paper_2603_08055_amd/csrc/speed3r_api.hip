@@ -476,7 +476,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     if (!p->q || !p->k || !p->v || !p->out) return fail(S3R_ERR_INVALID_ARG, "q, k, v and out must be non-null");
     if (!aligned16(p->q) || !aligned16(p->k) || !aligned16(p->v) || !aligned16(p->out) ||
         !aligned16(p->gate_logits) || !aligned16(p->o_sel) || !aligned16(p->o_comp) ||
-        !aligned16(p->topk_idx) || !aligned16(p->lse_sel))
+        !aligned16(p->topk_idx) || !aligned16(p->lse_sel) || (reinterpret_cast<uintptr_t>(p->status) & 3u) != 0)
         return fail(S3R_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     if (p->out == p->q || p->out == p->k || p->out == p->v) return fail(S3R_ERR_INVALID_ARG, "out must not alias an input");
     // 16-byte vector loads: rows and heads of q, k, v must start on 16-byte boundaries
@@ -547,9 +547,9 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     fb.cand = reinterpret_cast<int32_t *>(at(ws, L.cand));
     fb.cand_count = reinterpret_cast<int *>(at(ws, L.cand_count));
     fb.overflow = reinterpret_cast<int *>(at(ws, L.overflow));
-    if (n_forced > 0) {
+    if (n_forced > 0 || p->status != nullptr) {
         StageTimer tm(S3R_STAGE_TOPK, stream);
-        S3R_HIP(s3r::launch_forced_prepare(p->forced_blocks, n_forced, L.n_blk, forced_clean, forced_words, stream),
+        S3R_HIP(s3r::launch_forced_prepare(p->forced_blocks, n_forced, L.n_blk, forced_clean, forced_words, p->status, stream),
                 "forced-block prepare kernel launch");
     }
     st = run_compress_topk(qc, kc, vc, tile, reinterpret_cast<float *>(at(ws, L.s)), L.ld_s, L.head_chunk, oc,

@@ -461,18 +461,65 @@ hipError_t launch_topk_candidates(const float *qc, const float *kc, const int32_
     return hipGetLastError();
 }
 
-// Forced blocks (Sec. 3.3): one workgroup clamps the caller's list and sets the per-64-key bit words.
+// Forced blocks (Sec. 3.3): one workgroup turns the caller's list into the per-64-key bit words and into
+// forced_clean, the list every later kernel works with: n_forced entries in [0, n_blk), ascending.  For a list
+// that keeps its contract (in range, strictly ascending) that is the list itself.  Whatever else the caller
+// passes is made safe rather than trusted, because an index row with a hole or an out-of-range entry would send
+// the attention kernels to memory that is not theirs: entries are clamped into range, put in ascending order
+// (read back from the bit words), and what duplicates leave over is filled with the last block, which is then
+// simply attended more than once.  What was wrong is left in *status (when given): bit 0 = an entry outside
+// [0, n_blk), bit 1 = entries not strictly ascending; 0 = fine.  The library never synchronises the host, so
+// this word is how a broken list is reported.
 __global__ __launch_bounds__(256) void forced_prepare_kernel(const int32_t *__restrict__ forced, int n_forced,
                                                              int n_blk, int32_t *__restrict__ forced_clean,
-                                                             unsigned long long *__restrict__ words, int n_words)
+                                                             unsigned long long *__restrict__ words, int n_words,
+                                                             int32_t *__restrict__ status)
 {
-    for (int w = threadIdx.x; w < n_words; w += 256) words[w] = 0ull;
+    __shared__ int flags;
+    __shared__ int part[256];   // set bits in each thread's run of words, then their exclusive prefix sums
+    const int tid = threadIdx.x;
+    if (tid == 0) flags = 0;
+    for (int w = tid; w < n_words; w += 256) words[w] = 0ull;
     __syncthreads();
-    for (int a = threadIdx.x; a < n_forced; a += 256) {
+    int mine = 0;
+    for (int a = tid; a < n_forced; a += 256) {
         int j = forced[a];
+        if (j < 0 || j >= n_blk) mine |= 1;
+        if (a > 0 && forced[a - 1] >= j) mine |= 2;
         j = j < 0 ? 0 : (j >= n_blk ? n_blk - 1 : j);
-        forced_clean[a] = j;
         atomicOr(&words[j >> 6], 1ull << (j & 63));
+    }
+    if (mine != 0) atomicOr(&flags, mine);
+    __syncthreads();
+    if (tid == 0 && status != nullptr) *status = flags;
+    // the ascending list of distinct blocks, read back from the bit words: thread t owns words [t * run, (t + 1) * run)
+    const int run = (n_words + 255) / 256;
+    const int w0 = tid * run, w1 = (w0 + run < n_words) ? w0 + run : n_words;
+    int cnt = 0;
+    for (int w = w0; w < w1; ++w) cnt += __popcll(words[w]);
+    part[tid] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+        int acc = 0;
+        for (int t = 0; t < 256; ++t) { const int c = part[t]; part[t] = acc; acc += c; }
+        flags = acc;   // number of distinct blocks (the status word has been written)
+    }
+    __syncthreads();
+    int pos = part[tid];
+    for (int w = w0; w < w1; ++w) {
+        unsigned long long bits = words[w];
+        while (bits != 0ull) {
+            const int b = __ffsll(static_cast<long long>(bits)) - 1;
+            bits &= bits - 1ull;
+            if (pos < n_forced) forced_clean[pos] = w * 64 + b;
+            ++pos;
+        }
+    }
+    __syncthreads();
+    const int n_distinct = flags;
+    if (n_distinct > 0 && n_distinct < n_forced) {
+        const int last = forced_clean[n_distinct - 1];
+        for (int a = n_distinct + tid; a < n_forced; a += 256) forced_clean[a] = last;
     }
 }
 
@@ -507,11 +554,11 @@ __global__ __launch_bounds__(256) void merge_forced_kernel(const int32_t *__rest
 }
 
 hipError_t launch_forced_prepare(const int32_t *forced, int n_forced, int64_t n_blk, int32_t *forced_clean,
-                                 unsigned long long *forced_words, hipStream_t stream)
+                                 unsigned long long *forced_words, int32_t *status, hipStream_t stream)
 {
-    const int n_words = static_cast<int>((n_blk + 63) / 64);
+    const int n_words = n_forced > 0 ? static_cast<int>((n_blk + 63) / 64) : 0;
     hipLaunchKernelGGL(forced_prepare_kernel, dim3(1), dim3(256), 0, stream, forced, n_forced,
-                       static_cast<int>(n_blk), forced_clean, forced_words, n_words);
+                       static_cast<int>(n_blk), forced_clean, forced_words, n_words, status);
     return hipGetLastError();
 }
 

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libspeed3r.so")
 
 S3R_OK, S3R_ERR_INVALID_ARG, S3R_ERR_UNSUPPORTED, S3R_ERR_WORKSPACE, S3R_ERR_HIP = range(5)
 S3R_F32, S3R_BF16 = 0, 1
+S3R_DIAG_FORCED_RANGE, S3R_DIAG_FORCED_ORDER = 1, 2
 STAGES = ("pool", "split", "compress", "topk", "select", "dense")
 HEAD_DIM = 64
 
@@ -25,7 +26,7 @@ _flt = ctypes.c_float
 
 class s3r_params(ctypes.Structure):
     _fields_ = [("q", _vp), ("k", _vp), ("v", _vp), ("out", _vp), ("gate_logits", _vp),
-                ("forced_blocks", _vp), ("n_forced", _int),
+                ("forced_blocks", _vp), ("n_forced", _int), ("status", _vp),
                 ("tokens_per_view", _int), ("special_per_view", _int),
                 ("grid_h", _int), ("grid_w", _int), ("window", _int), ("compress_queries", _int),
                 ("n_tok", _i64), ("stride_tok", _i64), ("stride_head", _i64), ("heads", _int), ("head_dim", _int), ("block", _int),
@@ -180,7 +181,7 @@ def speed3r_selected_per_row(n_tok, block, topk, n_forced=0) -> int:
 def speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, *, gate_logits=None, softmax_scale=0.0,
                                   topk_idx=None, lse_sel=None, o_comp=None, o_sel=None,
                                   forced_blocks=None, tokens_per_view=0, special_per_view=0, grid=None,
-                                  compress_queries=0, workspace=None, stream=None):
+                                  compress_queries=0, workspace=None, status=None, stream=None):
     """The whole path on caller-provided buffers.  `workspace` is a uint8 CUDA tensor of at least
     speed3r_workspace_bytes(...) bytes (allocated here when None).  `forced_blocks` is an int32
     CUDA tensor of ascending distinct block indices attended by every query block.  With
@@ -188,7 +189,8 @@ def speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, *, gate_logits=None
     (dense attention over all rows); the other rows form the sequence of the sparse path.
     grid = (grid_h, grid_w, window) makes the blocks spatial windows of each view's patch grid.
     compress_queries = 1: every row's own query (instead of its block's pooled query) attends the
-    pooled keys in the compression branch.  q, k, v may be strided views with contiguous channels
+    pooled keys in the compression branch.  `status`: an int32 CUDA tensor of one element that receives
+    0 or the S3R_DIAG_* bits for a forced_blocks list that is out of range or not strictly ascending.  q, k, v may be strided views with contiguous channels
     and common strides (slices of one packed tensor).  Returns the workspace used."""
     n_tok, heads, head_dim, dt = _qkv(q, k, v)
     n_forced = 0 if forced_blocks is None else int(forced_blocks.numel())
@@ -202,6 +204,7 @@ def speed3r_sparse_global_attn_ex(q, k, v, out, block, topk, *, gate_logits=None
     p.gate_logits = _dev(gate_logits, "gate_logits", q.dtype)
     p.forced_blocks = _dev(forced_blocks, "forced_blocks", torch.int32) if n_forced else None
     p.n_forced = n_forced
+    p.status = _dev(status, "status", torch.int32)
     p.tokens_per_view, p.special_per_view = int(tokens_per_view), int(special_per_view)
     p.grid_h, p.grid_w, p.window = grid if grid else (0, 0, 0)
     p.compress_queries = int(compress_queries)

@@ -635,6 +635,23 @@ def test_forced_blocks_edge_cases(s3r, oracle, dtype, block, n_tok, topk, forced
     end_to_end(s3r, oracle, wl, with_gate=True, forced=np.asarray(forced, dtype=np.int32))
 
 
+def test_forced_blocks_list_is_diagnosed_through_the_status_word(s3r):
+    """A forced-block list that is out of range or not strictly ascending cannot be refused on the host (it is
+    device memory and no call synchronises): the device status word says so, and the call stays memory-safe."""
+    q, k, v = (draw(40 * 64, 2, "bf16", 7700 + i).cuda() for i in range(3))
+    out = torch.empty_like(q)
+    cases = [([1, 5, 9], 0), ([1, 5, 40], s3r.S3R_DIAG_FORCED_RANGE), ([-2, 5, 9], s3r.S3R_DIAG_FORCED_RANGE),
+             ([5, 1, 9], s3r.S3R_DIAG_FORCED_ORDER), ([1, 5, 5], s3r.S3R_DIAG_FORCED_ORDER),
+             ([9, 5, 77], s3r.S3R_DIAG_FORCED_RANGE | s3r.S3R_DIAG_FORCED_ORDER), (None, 0)]
+    for forced, want in cases:
+        status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        f = None if forced is None else torch.tensor(forced, dtype=torch.int32, device="cuda")
+        s3r.speed3r_sparse_global_attn_ex(q, k, v, out, 64, 4, forced_blocks=f, status=status)
+        torch.cuda.synchronize()
+        assert int(status.item()) == want, (forced, int(status.item()), want)
+        assert torch.isfinite(out.float()).all()
+
+
 def test_forced_blocks_leave_compressed_branch_unchanged(s3r):
     """The forced list only changes the selection set: Oc' is bit-identical with and without it."""
     wl = workloads.config(2, views=4)
