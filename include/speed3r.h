@@ -229,6 +229,8 @@ s3r_status speed3r_topk_blocks(const float *s_guide, int64_t ld_s, int32_t *idx,
 
 /* Steps 5-6 (eq. 6 / Alg. 2, then eqs. 5, 7, 8) with a given index tensor.
  *   idx     : in  [heads][n_blk][kk] block indices in [0, n_blk), distinct per row; 1 <= kk <= n_blk
+ *             (entries outside the range are held into it, so that a broken list stays memory-safe; a
+ *             block listed twice is attended twice)
  *   o_comp  : in, optional fp32 [heads][n_blk][head_dim]; NULL: `out` receives O_sel unmerged
  *   gate_logits, o_sel, lse: as in s3r_params (all optional)
  * Library-held scratch. */

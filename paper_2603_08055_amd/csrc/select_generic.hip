@@ -50,7 +50,8 @@ __global__ void select_generic_kernel(const T *__restrict__ q, const T *__restri
     const int32_t *sel = (idx != nullptr) ? idx + (static_cast<int64_t>(h) * n_qblk + i) * kk : nullptr;
 
     for (int64_t a = 0; a < n_sel; ++a) {
-        const int64_t j = (sel != nullptr) ? sel[a] : a;
+        int64_t j = (sel != nullptr) ? sel[a] : a;
+        j = j < 0 ? 0 : (j >= n_kblk ? n_kblk - 1 : j);   // a caller's list is not trusted with the address arithmetic
         const int64_t u0 = j * block;
         const int len = (blk_len != nullptr) ? blk_len[j] : static_cast<int>((n_keys - u0 < block) ? (n_keys - u0) : block);
         for (int c0 = 0; c0 < len; c0 += kChunk) {

@@ -180,11 +180,17 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         sel = idx + (static_cast<int64_t>(h) * n_blk + (PAIR ? 2 * qgroup : qgroup)) * kk;
         n_steps = SMALL ? (kk + (1 << bpu_shift) - 1) >> bpu_shift : kk << upb_shift;
     }
+    // An entry of the index list, held into [0, n_blk): the lists of the library's own TopK are always in range,
+    // a caller's (speed3r_select_attn) are not trusted with the address arithmetic.
+    auto sel_at = [&](const int32_t *list, int pos) -> int {
+        const int j = list[pos];
+        return j < 0 ? 0 : (j >= static_cast<int>(n_blk) ? static_cast<int>(n_blk) - 1 : j);
+    };
     // SMALL: the c-th key block of unit s, or -1 past the end of the list
     auto block_at = [&](int s, int c) -> int {
         const int pos = (s << bpu_shift) + c;
         if constexpr (DENSE) return pos < n_blk ? pos : -1;
-        else return pos < kk ? sel[pos] : -1;
+        else return pos < kk ? sel_at(sel, pos) : -1;
     };
     auto block_tokens = [&](int j) -> int {  // tokens of key block j (j >= 0)
         if (blk_len != nullptr) return blk_len[j];
@@ -205,7 +211,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     // step s -> key unit (global unit index); 32-bit arithmetic: these run once per step on the scalar unit
     auto unit_of = [&](int s) -> int {
         if constexpr (DENSE) return (EXTRA && !SMALL) ? s + u_begin : s;
-        else return (sel[s >> upb_shift] << upb_shift) + (s & upb_mask);
+        else return (sel_at(sel, s >> upb_shift) << upb_shift) + (s & upb_mask);
     };
     // SMALL: the blocks a 64-key unit is put together from; missing ones (short last unit) point at the
     // first, and are masked
@@ -382,7 +388,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         const bool has_b = 2 * qgroup + 1 < n_blk;
         struct Cursor { int ia, ib, ja, jb; };
         auto start = [&]() -> Cursor {
-            return Cursor{0, 0, kk > 0 ? sel[0] : kEnd, (has_b && kk > 0) ? sel_b[0] : kEnd};
+            return Cursor{0, 0, kk > 0 ? sel_at(sel, 0) : kEnd, (has_b && kk > 0) ? sel_at(sel_b, 0) : kEnd};
         };
         // next unit of the union (kEnd when done); ua / ub: list A / B holds it
         auto next = [&](Cursor &c, bool &ua, bool &ub) -> int {
@@ -390,8 +396,8 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
             ua = c.ja == j;
             ub = c.jb == j;
             if (j == kEnd) return kEnd;
-            if (ua) { ++c.ia; c.ja = c.ia < kk ? sel[c.ia] : kEnd; }
-            if (ub) { ++c.ib; c.jb = c.ib < kk ? sel_b[c.ib] : kEnd; }
+            if (ua) { ++c.ia; c.ja = c.ia < kk ? sel_at(sel, c.ia) : kEnd; }
+            if (ub) { ++c.ib; c.jb = c.ib < kk ? sel_at(sel_b, c.ib) : kEnd; }
             return j;
         };
         auto issue_unit = [&](int64_t w, int stage) {  // this wave's share of unit w -> LDS stage `stage`

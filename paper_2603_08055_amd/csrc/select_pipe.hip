@@ -95,6 +95,9 @@ __global__ __launch_bounds__(128 * P, 2) void select_pipe_kernel(
                      : "v"(a_lo), "v"(a_hi)
                      : "memory");
     }
+    // (held into [0, n_blk): a caller's list is not trusted with the address arithmetic)
+    sel_lo = sel_lo < 0 ? 0 : (sel_lo >= static_cast<int>(n_blk) ? static_cast<int>(n_blk) - 1 : sel_lo);
+    sel_hi = sel_hi < 0 ? 0 : (sel_hi >= static_cast<int>(n_blk) ? static_cast<int>(n_blk) - 1 : sel_hi);
     auto unit_of = [&](int u) -> int { return __builtin_amdgcn_readlane(u < 64 ? sel_lo : sel_hi, u & 63); };
 
     // ---- loads: of its pair's units the first wave moves the K part, the second the V part (eight 1 KiB chunks)

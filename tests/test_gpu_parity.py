@@ -215,6 +215,30 @@ def test_select_attn_long_rows_on_long_sequences(s3r, oracle, kk, rising):
     assert float(np.max(np.abs(lse.index_select(1, take).cpu().numpy().T - lse_v))) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("dtype,block", [("bf16", 64), ("bf16", 128), ("bf16", 16), ("bf16", 32), ("f32", 64)])
+def test_select_attn_holds_out_of_range_indices_in_range(s3r, dtype, block):
+    """A caller's index tensor is device memory the library cannot inspect: entries outside [0, n_blk) are held
+    into the range by the kernels (the documented behaviour), so the result equals that of the clamped list."""
+    n_tok, heads, kk = 21 * block + 5, 2, 6
+    n_blk = 22
+    q, k, v = (draw(n_tok, heads, dtype, 8800 + i).cuda() for i in range(3))
+    rng = np.random.default_rng(block)
+    idx = np.stack([[np.sort(rng.choice(n_blk, kk, replace=False)) for _ in range(n_blk)] for _ in range(heads)]).astype(np.int32)
+    bad = idx.copy()
+    bad[:, ::3, 0] = -7
+    bad[:, 1::3, kk - 1] = n_blk + 1000
+    bad[0, 5, kk - 1] = 2 ** 30
+    good = np.clip(bad, 0, n_blk - 1)
+    outs = []
+    for lists in (bad, good):
+        out = torch.full_like(q, float("nan"))
+        s3r.speed3r_select_attn(q, k, v, torch.from_numpy(lists).cuda(), out, block)
+        torch.cuda.synchronize()
+        outs.append(out)
+    assert torch.isfinite(outs[0].float()).all()
+    assert torch.equal(outs[0], outs[1])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("block,n_tok,kk", [(16, 200, 5), (32, 333, 4), (64, 1000, 5), (128, 700, 3)])
 def test_select_attn_generic(s3r, oracle, dtype, block, n_tok, kk):
