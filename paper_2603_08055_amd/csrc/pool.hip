@@ -23,9 +23,31 @@ template <> struct Load8<float> {
         const floatx4 b = *reinterpret_cast<const floatx4 *>(p + 4);
 #pragma unroll
         for (int i = 0; i < 4; ++i) { f[i] = a[i]; f[4 + i] = b[i]; }
-        (void)raw;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) raw[i] = static_cast<bf16_t>(f[i]);   // the hi part of the operand pair
     }
 };
+
+// x = hi + lo + O(2^-17 |x|) with hi = bf16(x), lo = bf16(x - hi): an operand pair; with the third part
+// lo2 = bf16(x - hi - lo) the sum is x itself (each residual has 8 significant bits fewer than the one before).
+// V goes to the matrix pipe as a pair (its products with probabilities in [0, 1] need no more), K as a triple:
+// the error of a logit enters the result through an exponential, in absolute terms, so the scores must keep
+// all 24 bits of K and Q however large their entries are.
+__device__ __forceinline__ bf16x8 lo_parts(const float (&f)[8], const bf16x8 &hi)
+{
+    bf16x8 lo;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) lo[i] = static_cast<bf16_t>(f[i] - static_cast<float>(hi[i]));
+    return lo;
+}
+__device__ __forceinline__ bf16x8 lo2_parts(const float (&f)[8], const bf16x8 &hi, const bf16x8 &lo)
+{
+    bf16x8 lo2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        lo2[i] = static_cast<bf16_t>((f[i] - static_cast<float>(hi[i])) - static_cast<float>(lo[i]));
+    return lo2;
+}
 
 // grid: one workgroup per (block j, head h), head fastest; 256 threads.
 // Thread (r0 = tid / 8, c = tid % 8) handles channels 8c..8c+7 of rows r0, r0 + 32, ...
@@ -35,11 +57,15 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ q, cons
                                                    float *__restrict__ kc, float *__restrict__ vc,
                                                    bf16_t *__restrict__ kb, bf16_t *__restrict__ vb,
                                                    int64_t n_tok, int heads, int64_t n_blk, TokenMap map,
-                                                   InStride in)
+                                                   InStride in, int64_t lo_off)
 {
+    // fp32 inputs are re-laid-out as bf16 operand parts: the lo tiles lie lo_off elements after the hi ones, K's
+    // third part another lo_off elements on
+    constexpr bool PAIRS = REPACK && sizeof(T) == 4;
     constexpr int VS_STRIDE = 72;  // bf16 elements per staged V row (64 + pad: conflict-free columns)
     __shared__ float red[3][32][65];
     __shared__ bf16_t vs[REPACK ? B : 1][VS_STRIDE];
+    __shared__ bf16_t vs_lo[PAIRS ? B : 1][VS_STRIDE];
 
     const int64_t bid = blockIdx.x;
     const int h = static_cast<int>(bid % heads);
@@ -71,14 +97,20 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ q, cons
             for (int i = 0; i < 8; ++i) acc[1][i] += f[i];
         }
         if constexpr (REPACK) {
-            if (!valid)
+            if (!valid) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) raw[i] = static_cast<bf16_t>(0.f);
+                for (int i = 0; i < 8; ++i) { raw[i] = static_cast<bf16_t>(0.f); f[i] = 0.f; }
+            }
             // 32-row tiles in operand order; a block of 16 rows is stored as the 16-row half of such a
             // tile, column chunk by column chunk, so that two of them interleave into one tile
             bf16_t *dst = (B >= 32) ? kb + tile_base + (r >> 5) * kRowTileElems + row_tile_chunk_offset(r & 31, c)
                                     : kb + tile_base + (c * 16 + r) * 8;
             *reinterpret_cast<bf16x8 *>(dst) = raw;
+            if constexpr (PAIRS) {
+                const bf16x8 lo = lo_parts(f, raw);
+                *reinterpret_cast<bf16x8 *>(dst + lo_off) = lo;
+                *reinterpret_cast<bf16x8 *>(dst + 2 * lo_off) = lo2_parts(f, raw, lo);
+            }
         }
         if (valid) {
             Load8<T>::run(v + off, f, raw);
@@ -86,10 +118,12 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ q, cons
             for (int i = 0; i < 8; ++i) acc[2][i] += f[i];
         }
         if constexpr (REPACK) {
-            if (!valid)
+            if (!valid) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) raw[i] = static_cast<bf16_t>(0.f);
+                for (int i = 0; i < 8; ++i) { raw[i] = static_cast<bf16_t>(0.f); f[i] = 0.f; }
+            }
             *reinterpret_cast<bf16x8 *>(&vs[r][c * 8]) = raw;
+            if constexpr (PAIRS) *reinterpret_cast<bf16x8 *>(&vs_lo[r][c * 8]) = lo_parts(f, raw);
         }
     }
 #pragma unroll
@@ -116,6 +150,11 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ q, cons
 #pragma unroll
             for (int i = 0; i < 8; ++i) o[i] = vs[tr_tile_key(u, l, i)][d];
             *reinterpret_cast<bf16x8 *>(vb + tile_base + static_cast<int64_t>(ci) * 8) = o;
+            if constexpr (PAIRS) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o[i] = vs_lo[tr_tile_key(u, l, i)][d];
+                *reinterpret_cast<bf16x8 *>(vb + lo_off + tile_base + static_cast<int64_t>(ci) * 8) = o;
+            }
         }
     }
 }
@@ -126,10 +165,11 @@ static hipError_t run_pool(const void *q, const void *k, const void *v, float *q
                            TokenMap map, InStride in, hipStream_t stream)
 {
     const int64_t grid = n_blk * heads;
+    const int64_t lo_off = static_cast<int64_t>(heads) * n_blk * B * 64;   // fp32 inputs: [hi tiles | lo tiles | K: lo2 tiles]
     hipLaunchKernelGGL((pool_kernel<T, B, REPACK>), dim3(static_cast<unsigned>(grid)), dim3(256), 0,
                        stream, static_cast<const T *>(q), static_cast<const T *>(k),
                        static_cast<const T *>(v), qc, kc, vc, static_cast<bf16_t *>(kb),
-                       static_cast<bf16_t *>(vb), n_tok, heads, n_blk, map, in);
+                       static_cast<bf16_t *>(vb), n_tok, heads, n_blk, map, in, lo_off);
     return hipGetLastError();
 }
 
@@ -158,7 +198,7 @@ hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, f
     if (n_blk * heads > 0x7fffffffLL) return hipErrorInvalidValue;
     if (map.period != 0 && n_tok > 0x7fffffffLL) return hipErrorInvalidValue;
     const bool repack = kb != nullptr;
-    if (repack && !is_bf16) return hipErrorInvalidValue;
+    if (repack && !is_bf16 && block < 64) return hipErrorInvalidValue;  // operand pairs: blocks of 64 and 128 tokens
 #define S3R_POOL_CASE(TT, BB, RR) \
     return run_pool<TT, BB, RR>(q, k, v, qc, kc, vc, kb, vb, n_tok, heads, n_blk, map, in, stream)
     if (is_bf16) {
@@ -172,8 +212,8 @@ hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, f
         switch (block) {
         case 16: S3R_POOL_CASE(float, 16, false);
         case 32: S3R_POOL_CASE(float, 32, false);
-        case 64: S3R_POOL_CASE(float, 64, false);
-        case 128: S3R_POOL_CASE(float, 128, false);
+        case 64: if (repack) S3R_POOL_CASE(float, 64, true); else S3R_POOL_CASE(float, 64, false);
+        case 128: if (repack) S3R_POOL_CASE(float, 128, true); else S3R_POOL_CASE(float, 128, false);
         }
     }
 #undef S3R_POOL_CASE

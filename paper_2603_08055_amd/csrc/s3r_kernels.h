@@ -72,7 +72,9 @@ hipError_t launch_block_lens(TokenMap map, int block, int64_t n_tok, int64_t n_b
 
 // Block means of q, k, v (fp32 [heads][n_blk][64]; any of qc/kc/vc may be null together) and,
 // when kb/vb are given (bf16 input), the per-(head, block) K and V tiles in MFMA operand order:
-// kb, vb are bf16 [heads][n_blk][block * 64] (blocks of 16 rows: half tiles, see pool.hip).  n_tok counts the tokens of the
+// kb, vb are bf16 [heads][n_blk][block * 64] (blocks of 16 rows: half tiles, see pool.hip).  fp32 input (blocks of
+// 64 and 128 tokens only): kb, vb are [2][heads][n_blk][block * 64], the bf16 hi parts followed by the lo parts
+// (x - hi rounded to bf16).  n_tok counts the tokens of the
 // sub-sequence `map` picks out of q, k, v; blocks are runs of that sub-sequence.
 hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, float *kc, float *vc,
                        void *kb, void *vb, int64_t n_tok, int heads, int block, bool is_bf16,
@@ -168,6 +170,8 @@ struct SelectArgs {
     const void *q, *k, *v;     // the caller's layout: [rows][heads][64], or the strides x.in
     const void *kb, *vb;       // operand-order tiles of the keys (MFMA path only)
     const void *kb2 = nullptr, *vb2 = nullptr;  // MFMA dense only: a second key segment, 64-key tiles
+    int64_t lo_off = 0, lo_off2 = 0;  // fp32 problems on the MFMA path: kb, vb (kb2, vb2) hold [hi tiles | lo tiles],
+                                      // the lo tiles this many elements after the hi ones
     const int32_t *idx;        // [heads][n_blk][kk]; null = every key (dense attention)
     const float *o_comp;       // [heads][n_blk][64] or null (no merge)
     const void *gate;          // [rows][heads][64] or null
@@ -195,7 +199,7 @@ struct SelectArgs {
 // out[qmap.row(t)][h][:] = sum_i w_i part_o[i][t][h][:], w_i = 2^(part_lse[i][t][h]) / sum_j 2^(part_lse[j][t][h]):
 // the softmax over all keys from its shares (out: bf16 [rows][heads][64]).
 hipError_t launch_dense_combine(const float *part_o, const float *part_lse, int n_split, int64_t n_tok, int heads,
-                                TokenMap qmap, void *out, hipStream_t stream);
+                                TokenMap qmap, void *out, bool is_bf16, hipStream_t stream);
 
 // One thread per query row, fp32 FMA; any dtype, any supported block size.
 hipError_t launch_select_generic(const SelectArgs &a, hipStream_t stream);

@@ -55,21 +55,34 @@ namespace s3r {
 //         real one does (same work mapping, ring, waits and barriers) but does no arithmetic on them; it
 //         writes its Q rows to `out`, so Q is read and `out` written as well.  Its run time is what the data
 //         movement of the selection stage costs by itself.
-template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ, bool PAIR = false, bool PROBE = false>
+// F32   : fp32 q, gate, out and o_sel (the pointers below are then float pointers in disguise), K/V tiles in bf16
+//         parts ([hi tiles | lo tiles | K only: lo2 tiles], lo_off elements apart), x = hi + lo (+ lo2).  Scores
+//         take Q and K in three parts each and the six products whose weight is above 2^-24 (a logit's error
+//         enters the result in absolute terms, so it must not grow with the size of the entries); P.V takes
+//         two parts each, hi.hi + hi.lo + lo.hi (2^-17 relative, of values in [0, 1] times V).  All on the
+//         bf16 matrix pipe with fp32 accumulation: fp32-grade results at nine MFMAs per tile step in place of two.
+template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ, bool PAIR = false, bool PROBE = false,
+          bool F32 = false>
 __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     const bf16_t *__restrict__ q, const bf16_t *__restrict__ kb, const bf16_t *__restrict__ vb,
     const int32_t *__restrict__ idx, const float *__restrict__ o_comp, const bf16_t *__restrict__ gate,
     bf16_t *__restrict__ out, bf16_t *__restrict__ o_sel, float *__restrict__ lse, int64_t n_tok,
     int64_t n_blk, int heads, int block, int kk, float scale_log2, int64_t set_offset, int64_t n_sets,
     int map_mode, TokenMap qmap, int64_t n_keys, int64_t lse_stride, const bf16_t *__restrict__ kb2,
-    const bf16_t *__restrict__ vb2, int64_t n_keys2, const int32_t *__restrict__ blk_len, SelectExtras x)
+    const bf16_t *__restrict__ vb2, int64_t n_keys2, const int32_t *__restrict__ blk_len, SelectExtras x,
+    int64_t lo_off, int64_t lo_off2)
 {
     constexpr int NW = QW;             // waves per workgroup
-    constexpr int CPW = 16 / NW;       // 1 KiB chunks of a unit (8 K + 8 V) issued by each wave
+    constexpr int NCH = F32 ? 40 : 16; // 1 KiB chunks of a unit: 8 K + 8 V (F32: then 8 K lo + 8 V lo + 8 K lo2)
+    constexpr int CPW = NCH / NW;      // ... issued by each wave
     constexpr int D = NS - 1;          // units in flight
-    static_assert(16 % NW == 0 && NW <= 16, "waves must split the 16 chunks of a unit evenly");
+    static_assert(NCH % NW == 0 && 16 % NW == 0, "waves must split the chunks of a unit evenly");
     static_assert(CPW * D < 64, "vmcnt budget");
-    __shared__ __attribute__((aligned(1024))) bf16_t ring[NS][2 * kUnitElems];  // [stage][K 8 KiB | V 8 KiB]
+    static_assert(!F32 || (!SMALL && !PAIR && !PROBE), "operand pairs: blocks of 64 and 128 tokens, plain and dense kernels");
+    // [stage][K 8 KiB | V 8 KiB] (F32: then [K lo 8 KiB | V lo 8 KiB | K lo2 8 KiB])
+    constexpr int kStageParts = F32 ? 5 : 2;
+    __shared__ __attribute__((aligned(1024))) bf16_t ring[NS][kStageParts * kUnitElems];
+    constexpr int kLoElems = 2 * kUnitElems;  // from a hi part of a stage to its lo part, and on to K's lo2 part
 
     const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -127,8 +140,32 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     // each step anyway (two stages), and a plain early load of Q is 1 % faster there, except on long index
     // rows (ASMQ chooses).
     bf16x8 qb[4];
-    constexpr bool kAsmQ = ASMQ;
-    if constexpr (!kAsmQ) {
+    bf16x8 ql[F32 ? 4 : 1], ql2[F32 ? 4 : 1];   // F32: the lo and lo2 parts of Q
+    constexpr bool kAsmQ = ASMQ && !F32;
+    if constexpr (F32) {
+        const float *qf = reinterpret_cast<const float *>(q);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            float f[8];
+            if (row_valid) {
+                const int64_t qo = EXTRA ? x.in.at(trow, h, heads) : (trow * heads + h) * 64;
+                const floatx4 a = *reinterpret_cast<const floatx4 *>(qf + qo + 16 * s + 8 * g);
+                const floatx4 b = *reinterpret_cast<const floatx4 *>(qf + qo + 16 * s + 8 * g + 4);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { f[i] = a[i]; f[4 + i] = b[i]; }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) f[i] = 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                qb[s][i] = static_cast<bf16_t>(f[i]);
+                const float r1 = f[i] - static_cast<float>(qb[s][i]);
+                ql[s][i] = static_cast<bf16_t>(r1);
+                ql2[s][i] = static_cast<bf16_t>(r1 - static_cast<float>(ql[s][i]));
+            }
+        }
+    } else if constexpr (!kAsmQ) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             if (row_valid) {
@@ -223,7 +260,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         return UnitBlocks{f0, b1 >= 0 ? b1 : f0, b2 >= 0 ? b2 : f0, b3 >= 0 ? b3 : f0};
     };
     auto issue = [&](int s, int stage) {  // this wave's share of unit s -> LDS stage `stage`
-        const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (2 * kUnitElems * 2);
+        const unsigned stage_byte = ring_base + static_cast<unsigned>(stage) * (kStageParts * kUnitElems * 2);
         if constexpr (SMALL) {
             // (dense: the second key segment is stored as plain 64-key units)
             const bool small = !(DENSE && s >= n_units1);
@@ -264,9 +301,22 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
             }
             return;
         }
-        // all chunks of a wave are of one kind (K or V) here
-        static_assert(SMALL || CPW <= 8, "a wave's chunks must be all K or all V");
         const int64_t w = unit_of(s);
+        if constexpr (F32) {  // chunk = 16 * part + (0..7: K, 8..15: V), part 0 = hi, 1 = lo, 2 = lo2 (K only)
+            const bool second = DENSE && w >= n_units1;
+            const int64_t wu = second ? w - n_units1 : w;
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) {
+                const int chunk = wave * CPW + c;
+                const bf16_t *arr = (chunk & 8) ? (second ? vb2_h : vb_h) : (second ? kb2_h : kb_h);
+                const int64_t part = (chunk >> 4) * (second ? lo_off2 : lo_off);
+                lds_dma_16(arr + part + wu * kUnitElems + (chunk & 7) * 512 + lane * 8,
+                           __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
+            }
+            return;
+        }
+        // all chunks of a wave are of one kind (K or V) here
+        static_assert(SMALL || F32 || CPW <= 8, "a wave's chunks must be all K or all V");
         const bf16_t *unit = (DENSE && w >= n_units1) ? seg2 + (w - n_units1) * kUnitElems : seg1 + w * kUnitElems;
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
@@ -305,6 +355,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
 
     floatx16 sacc[2];
     bf16x8 pb[4];  // probabilities of one unit as MFMA operands
+    bf16x8 pl[F32 ? 4 : 1];  // F32: their lo parts
     const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     // S^T = K Q^T of the unit whose K sits in `ks`.  Selection: the two 32-key tiles take turns, so that
     // no MFMA waits for the one issued just before it (3 % faster at 64 blocks per row, 7 % at 288).
@@ -316,6 +367,15 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
             const int mt = DENSE ? i >> 2 : i & 1, c = DENSE ? i & 3 : i >> 1;
             const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(ks + ((mt * 4 + c) * 64 + lane) * 8);
             sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qb[c], c == 0 ? zero16 : sacc[mt], 0, 0, 0);
+            if constexpr (F32) {
+                const bf16x8 kl = *reinterpret_cast<const bf16x8 *>(ks + kLoElems + ((mt * 4 + c) * 64 + lane) * 8);
+                const bf16x8 kl2 = *reinterpret_cast<const bf16x8 *>(ks + 2 * kLoElems + ((mt * 4 + c) * 64 + lane) * 8);
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql[c], sacc[mt], 0, 0, 0);
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl, qb[c], sacc[mt], 0, 0, 0);
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql2[c], sacc[mt], 0, 0, 0);
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl, ql[c], sacc[mt], 0, 0, 0);
+                sacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kl2, qb[c], sacc[mt], 0, 0, 0);
+            }
         }
     };
     // keys past the end of a block or of the sequence do not exist
@@ -354,8 +414,22 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
         // The row sum adds the probabilities as the MFMA will see them (rounded to bf16), two per
         // v_dot2_f32_bf16 with a vector of ones: half the instructions of fp32 adds, and numerator and
         // denominator of the softmax then carry the same rounding.
-        const bf16x2 ones = {static_cast<bf16_t>(1.f), static_cast<bf16_t>(1.f)};
         float lsum[4] = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (F32) {  // probabilities in fp32, split into operand pairs; the row sum adds the fp32 values
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int mt = v >> 1, r = 8 * (v & 1) + i;
+                    const float p = fast_exp2(sacc[mt][r] * scale_log2 - m_run);
+                    lsum[i & 3] += p;
+                    pb[v][i] = static_cast<bf16_t>(p);
+                    pl[v][i] = static_cast<bf16_t>(p - static_cast<float>(pb[v][i]));
+                }
+            l_run += (lsum[0] + lsum[1]) + (lsum[2] + lsum[3]);
+            return;
+        }
+        const bf16x2 ones = {static_cast<bf16_t>(1.f), static_cast<bf16_t>(1.f)};
 #pragma unroll
         for (int v = 0; v < 4; ++v)
 #pragma unroll
@@ -377,6 +451,11 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
             for (int dt = 0; dt < 2; ++dt) {
                 const bf16x8 va = *reinterpret_cast<const bf16x8 *>(vs + ((v * 2 + dt) * 64 + lane) * 8);
                 oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[v], oacc[dt], 0, 0, 0);
+                if constexpr (F32) {
+                    const bf16x8 vl = *reinterpret_cast<const bf16x8 *>(vs + kLoElems + ((v * 2 + dt) * 64 + lane) * 8);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pl[v], oacc[dt], 0, 0, 0);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vl, pb[v], oacc[dt], 0, 0, 0);
+                }
             }
     };
 
@@ -507,26 +586,41 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
                 const floatx4 c4 = *reinterpret_cast<const floatx4 *>(oc + d0);
                 float gt[4] = {0.5f, 0.5f, 0.5f, 0.5f};
                 if (gate != nullptr) {
-                    const bf16x4 gl = *reinterpret_cast<const bf16x4 *>(gate + o + d0);
+                    float gl[4];
+                    if constexpr (F32) {
+                        const floatx4 g4 = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const float *>(gate) + o + d0);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) gt[i] = 1.f / (1.f + __expf(-static_cast<float>(gl[i])));
+                        for (int i = 0; i < 4; ++i) gl[i] = g4[i];
+                    } else {
+                        const bf16x4 g4 = *reinterpret_cast<const bf16x4 *>(gate + o + d0);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) gl[i] = static_cast<float>(g4[i]);
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) gt[i] = 1.f / (1.f + __expf(-gl[i]));
                 }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) res[i] = gt[i] * c4[i] + (1.f - gt[i]) * os[i];
             }
-            bf16x4 ro;
+            if constexpr (F32) {
+                *reinterpret_cast<floatx4 *>(reinterpret_cast<float *>(out) + o + d0) = floatx4{res[0], res[1], res[2], res[3]};
+                if (o_sel != nullptr)
+                    *reinterpret_cast<floatx4 *>(reinterpret_cast<float *>(o_sel) + o + d0) = floatx4{os[0], os[1], os[2], os[3]};
+            } else {
+                bf16x4 ro;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) ro[i] = static_cast<bf16_t>(res[i]);
-            *reinterpret_cast<bf16x4 *>(out + o + d0) = ro;
-            if (o_sel != nullptr) {
+                for (int i = 0; i < 4; ++i) ro[i] = static_cast<bf16_t>(res[i]);
+                *reinterpret_cast<bf16x4 *>(out + o + d0) = ro;
+                if (o_sel != nullptr) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) ro[i] = static_cast<bf16_t>(os[i]);
-                *reinterpret_cast<bf16x4 *>(o_sel + o + d0) = ro;
+                    for (int i = 0; i < 4; ++i) ro[i] = static_cast<bf16_t>(os[i]);
+                    *reinterpret_cast<bf16x4 *>(o_sel + o + d0) = ro;
+                }
             }
         }
 }
 
-template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ, bool PAIR, bool PROBE = false>
+template <int QW, bool DENSE, int NS, bool SMALL, bool EXTRA, bool ASMQ, bool PAIR, bool PROBE = false, bool F32 = false>
 static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
 {
     // The load probe can hold the number of workgroups per CU down: unused dynamic LDS on top of the ring makes
@@ -537,7 +631,7 @@ static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
         if (share < ring) return hipErrorInvalidValue;
         pad_bytes = static_cast<unsigned>(share - ring);
         const hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(&select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ, PAIR, PROBE>),
+            reinterpret_cast<const void *>(&select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ, PAIR, PROBE, F32>),
             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(pad_bytes));
         if (e != hipSuccess) return e;
     }
@@ -560,33 +654,45 @@ static hipError_t run_select_x(const SelectArgs &a, hipStream_t stream)
         const int64_t ns = (sets - s0 < per_launch) ? sets - s0 : per_launch;
         const int64_t n_split = (DENSE && a.x.n_split > 1) ? a.x.n_split : 1;
         const int64_t grid = (map_mode == 2) ? (ns + 7) / 8 * 8 * a.heads : ns * n_split * a.heads;
-        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ, PAIR, PROBE>), dim3(static_cast<unsigned>(grid)),
+        hipLaunchKernelGGL((select_mfma_kernel<QW, DENSE, NS, SMALL, EXTRA, ASMQ, PAIR, PROBE, F32>), dim3(static_cast<unsigned>(grid)),
                            dim3(QW * 64), pad_bytes, stream, static_cast<const bf16_t *>(a.q),
                            static_cast<const bf16_t *>(a.kb), static_cast<const bf16_t *>(a.vb), a.idx,
                            a.o_comp, static_cast<const bf16_t *>(a.gate), static_cast<bf16_t *>(a.out),
                            static_cast<bf16_t *>(a.o_sel), a.lse, a.n_tok, a.n_blk, a.heads, a.block,
                            a.kk, a.scale * kLog2e, s0, ns, map_mode, a.qmap, a.n_keys, a.lse_stride,
                            static_cast<const bf16_t *>(a.kb2), static_cast<const bf16_t *>(a.vb2), a.n_keys2,
-                           a.blk_len, a.x);
+                           a.blk_len, a.x, a.lo_off, a.lo_off2);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-template <int QW, bool DENSE, int NS, bool SMALL = false, bool ASMQ = DENSE, bool PAIR = false>
+template <int QW, bool DENSE, int NS, bool SMALL = false, bool ASMQ = DENSE, bool PAIR = false, bool F32 = false>
 static hipError_t run_select(const SelectArgs &a, hipStream_t stream)
 {
     const SelectExtras &x = a.x;
     const bool extra = x.o_comp_tok != nullptr || x.out_f32 != nullptr || x.kv_head_stride != 0 ||
                        x.q_blk_len != nullptr || x.in.tok != 0;
-    return extra ? run_select_x<QW, DENSE, NS, SMALL, true, ASMQ, PAIR>(a, stream)
-                 : run_select_x<QW, DENSE, NS, SMALL, false, ASMQ, PAIR>(a, stream);
+    return extra ? run_select_x<QW, DENSE, NS, SMALL, true, ASMQ, PAIR, false, F32>(a, stream)
+                 : run_select_x<QW, DENSE, NS, SMALL, false, ASMQ, PAIR, false, F32>(a, stream);
 }
 
 hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
 {
-    if (!a.is_bf16 || a.kb == nullptr || a.vb == nullptr) return hipErrorInvalidValue;
+    if (a.kb == nullptr || a.vb == nullptr) return hipErrorInvalidValue;
+    if (!a.is_bf16) {
+        // fp32 problems: K/V tiles as bf16 hi/lo operand pairs, blocks of 64 and 128 tokens
+        if (a.lo_off <= 0 || a.loads_only || (a.block != 64 && a.block != 128)) return hipErrorInvalidValue;
+        if (a.qmap.period != 0 && a.n_tok > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (a.idx == nullptr) {
+            if (a.n_keys2 > 0 && (a.kb2 == nullptr || a.vb2 == nullptr || a.lo_off2 <= 0)) return hipErrorInvalidValue;
+            return run_select<4, true, 3, false, true, false, true>(a, stream);
+        }
+        if (a.n_keys != a.n_tok || a.n_keys2 != 0) return hipErrorInvalidValue;
+        return a.block == 64 ? run_select<2, false, 2, false, false, false, true>(a, stream)
+                             : run_select<4, false, 2, false, false, false, true>(a, stream);
+    }
     // One query block per workgroup, two LDS stages: measured best on MI355X.  A third stage is slower even
     // where it costs no occupancy (blocks of 128 tokens: 18.2 against 16.8 ms on 300 views, top-64): the fabric
     // is saturated already, and the units on their way (3 workgroups x 2 units x 16 KiB on each of an XCD's 32
@@ -637,10 +743,11 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
 }
 
 // One thread per (query slot, head, 4 channels).
+template <typename T>
 __global__ __launch_bounds__(256) void dense_combine_kernel(const float *__restrict__ part_o,
                                                             const float *__restrict__ part_lse, int n_split,
                                                             int64_t n_tok, int heads, TokenMap qmap,
-                                                            bf16_t *__restrict__ out)
+                                                            T *__restrict__ out)
 {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (i >= n_tok * heads * 16) return;
@@ -662,19 +769,32 @@ __global__ __launch_bounds__(256) void dense_combine_kernel(const float *__restr
     }
     const int64_t t = th / heads;
     const int h = static_cast<int>(th - t * heads);
-    bf16x4 r;
+    T *dst = out + (qmap.row(t) * heads + h) * 64 + c4 * 4;
+    if constexpr (sizeof(T) == 4) {
+        floatx4 r;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) r[c] = static_cast<bf16_t>(acc[c] / den);
-    *reinterpret_cast<bf16x4 *>(out + (qmap.row(t) * heads + h) * 64 + c4 * 4) = r;
+        for (int c = 0; c < 4; ++c) r[c] = acc[c] / den;
+        *reinterpret_cast<floatx4 *>(dst) = r;
+    } else {
+        bf16x4 r;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) r[c] = static_cast<bf16_t>(acc[c] / den);
+        *reinterpret_cast<bf16x4 *>(dst) = r;
+    }
 }
 
 hipError_t launch_dense_combine(const float *part_o, const float *part_lse, int n_split, int64_t n_tok, int heads,
-                                TokenMap qmap, void *out, hipStream_t stream)
+                                TokenMap qmap, void *out, bool is_bf16, hipStream_t stream)
 {
     const int64_t threads = n_tok * heads * 16;
     if (n_split < 1 || threads <= 0 || (threads + 255) / 256 > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(dense_combine_kernel, dim3(static_cast<unsigned>((threads + 255) / 256)), dim3(256), 0, stream,
-                       part_o, part_lse, n_split, n_tok, heads, qmap, static_cast<bf16_t *>(out));
+    const dim3 grid(static_cast<unsigned>((threads + 255) / 256));
+    if (is_bf16)
+        hipLaunchKernelGGL(dense_combine_kernel<bf16_t>, grid, dim3(256), 0, stream, part_o, part_lse, n_split, n_tok,
+                           heads, qmap, static_cast<bf16_t *>(out));
+    else
+        hipLaunchKernelGGL(dense_combine_kernel<float>, grid, dim3(256), 0, stream, part_o, part_lse, n_split, n_tok,
+                           heads, qmap, static_cast<float *>(out));
     return hipGetLastError();
 }
 

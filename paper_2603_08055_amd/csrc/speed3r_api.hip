@@ -48,7 +48,10 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int g_kernel_choice = 0;  // 0 auto, 1 generic attention kernels only, 2 TopK from scores written to memory
 
-bool mfma_ok(s3r_dtype dtype, int block) { return g_kernel_choice != 1 && dtype == S3R_BF16; }  // any supported block
+// bf16: every supported block size; fp32: blocks of 64 and 128 tokens (K/V as bf16 hi/lo operand pairs)
+bool mfma_ok(s3r_dtype dtype, int block) { return g_kernel_choice != 1 && (dtype == S3R_BF16 || block >= 64); }
+// copies of a K (or V) tile array the MFMA kernels read: fp32 problems keep bf16 parts hi, lo and (K) lo2
+size_t tile_parts(s3r_dtype dtype) { return dtype == S3R_BF16 ? 1 : 3; }
 
 // Dense attention of few query rows (the special tokens) in key splits: as many as make the workgroups fill
 // the CUs most evenly (MI355X: 256 CUs x 3 workgroups of the dense kernel each), at least 4 key units each.
@@ -125,10 +128,10 @@ Layout make_layout(int64_t n_tok, int heads, int block, int topk, int n_forced, 
     L.forced_clean = take(static_cast<size_t>(n_forced) * sizeof(int32_t));
     L.forced_words = take(n_forced > 0 ? static_cast<size_t>((L.n_blk + 63) / 64) * sizeof(unsigned long long) : 0);
     L.s = take(per_head_s * L.head_chunk);
-    const size_t blocked = mfma_ok(dtype, block) ? static_cast<size_t>(heads) * L.n_blk * block * 64 * 2 : 0;
+    const size_t blocked = mfma_ok(dtype, block) ? static_cast<size_t>(heads) * L.n_blk * block * 64 * 2 * tile_parts(dtype) : 0;
     L.kb = take(blocked);
     L.vb = take(blocked);
-    const size_t spec_tiles = mfma_ok(dtype, block) ? static_cast<size_t>(heads) * ((n_spec + 63) / 64) * 64 * 64 * 2 : 0;
+    const size_t spec_tiles = mfma_ok(dtype, block) ? static_cast<size_t>(heads) * ((n_spec + 63) / 64) * 64 * 64 * 2 * tile_parts(dtype) : 0;
     L.kb_spec = take(spec_tiles);
     L.vb_spec = take(spec_tiles);
     // TopK-in-the-sweep buffers, for all heads at once (the sweeps are not chunked)
@@ -575,7 +578,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
         c.scale = scale; c.is_bf16 = is_bf16;
         c.x.out_f32 = oc_tok; c.x.q_blk_len = blk_len; c.x.q_block = p->block; c.x.in = in;
         StageTimer tm(S3R_STAGE_COMPRESS, stream);
-        if (mfma) {
+        if (mfma && is_bf16) {
             c.kb = tile[2]; c.vb = tile[4];
             c.x.kv_head_stride = L.tiles * 32 * 64;
             S3R_HIP(s3r::launch_select_mfma(c, stream), "compression branch (unpooled queries) kernel launch");
@@ -595,6 +598,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
     a.qmap = sp.img; a.kmap = sp.img; a.blk_len = blk_len;
     a.heads = p->heads; a.block = p->block; a.kk = L.width;
     a.scale = scale; a.is_bf16 = is_bf16;
+    a.lo_off = (mfma && !is_bf16) ? static_cast<int64_t>(p->heads) * L.n_blk * p->block * 64 : 0;
     {
         StageTimer tm(S3R_STAGE_SELECT, stream);
         S3R_HIP(mfma ? s3r::launch_select_mfma(a, stream) : s3r::launch_select_generic(a, stream),
@@ -613,12 +617,16 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
             {
                 StageTimer tm(S3R_STAGE_POOL, stream);
                 S3R_HIP(s3r::launch_pool(p->q, p->k, p->v, nullptr, nullptr, nullptr, kb_s, vb_s, sp.n_spec, p->heads,
-                                         64, true, sp.spec, in, stream),
+                                         64, is_bf16, sp.spec, in, stream),
                         "pool kernel launch (special tokens)");
             }
             d.kb = kb; d.vb = vb; d.n_keys = sp.n_img; d.n_blk = L.n_blk;      // image keys, then special keys
             d.blk_len = blk_len;
             d.kb2 = kb_s; d.vb2 = vb_s; d.n_keys2 = sp.n_spec;
+            if (!is_bf16) {
+                d.lo_off = a.lo_off;
+                d.lo_off2 = static_cast<int64_t>(p->heads) * ((sp.n_spec + 63) / 64) * 64 * 64;
+            }
             if (L.spec_split > 1) {
                 d.x.n_split = L.spec_split;
                 d.x.out_f32 = reinterpret_cast<float *>(at(ws, L.spec_part_o));
@@ -632,7 +640,7 @@ s3r_status speed3r_sparse_global_attn_ex(const s3r_params *p)
                 "dense kernel launch (special tokens)");
         if (d.x.n_split > 1)
             S3R_HIP(s3r::launch_dense_combine(d.x.out_f32, d.x.part_lse, d.x.n_split, sp.n_spec, p->heads, sp.spec,
-                                              p->out, stream),
+                                              p->out, is_bf16, stream),
                     "dense combine kernel launch (special tokens)");
     }
     return S3R_OK;
@@ -795,15 +803,17 @@ s3r_status speed3r_select_attn(const void *q, const void *k, const void *v, cons
     const bool mfma = mfma_ok(dtype, block);
     s3r::SelectArgs a{};
     if (mfma) {
-        const size_t blocked = align_up(static_cast<size_t>(heads) * n_blk * block * 64 * 2);
+        const size_t blocked = align_up(static_cast<size_t>(heads) * n_blk * block * 64 * 2 * tile_parts(dtype));
         void *ws = nullptr;
         st = scratch_get(2 * blocked, &ws);
         if (st != S3R_OK) return st;
         a.kb = ws;
         a.vb = at(ws, blocked);
+        a.lo_off = dtype == S3R_BF16 ? 0 : static_cast<int64_t>(heads) * n_blk * block * 64;
         StageTimer tm(S3R_STAGE_POOL, s);
         S3R_HIP(s3r::launch_pool(q, k, v, nullptr, nullptr, nullptr, const_cast<void *>(a.kb),
-                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s3r::TokenMap{}, s3r::InStride{}, s),
+                                 const_cast<void *>(a.vb), n_tok, heads, block, dtype == S3R_BF16, s3r::TokenMap{},
+                                 s3r::InStride{}, s),
                 "pool kernel launch");
     }
     a.q = q; a.k = k; a.v = v; a.idx = idx; a.o_comp = o_comp; a.gate = gate_logits; a.out = out;
@@ -869,15 +879,17 @@ s3r_status speed3r_dense_attn(const void *q, const void *k, const void *v, void 
     const bool mfma = mfma_ok(dtype, block);
     s3r::SelectArgs a{};
     if (mfma) {
-        const size_t blocked = align_up(static_cast<size_t>(heads) * n_blk * block * 64 * 2);
+        const size_t blocked = align_up(static_cast<size_t>(heads) * n_blk * block * 64 * 2 * tile_parts(dtype));
         void *ws = nullptr;
         st = scratch_get(2 * blocked, &ws);
         if (st != S3R_OK) return st;
         a.kb = ws;
         a.vb = at(ws, blocked);
+        a.lo_off = dtype == S3R_BF16 ? 0 : static_cast<int64_t>(heads) * n_blk * block * 64;
         StageTimer tm(S3R_STAGE_POOL, s);
         S3R_HIP(s3r::launch_pool(q, k, v, nullptr, nullptr, nullptr, const_cast<void *>(a.kb),
-                                 const_cast<void *>(a.vb), n_tok, heads, block, true, s3r::TokenMap{}, s3r::InStride{}, s),
+                                 const_cast<void *>(a.vb), n_tok, heads, block, dtype == S3R_BF16, s3r::TokenMap{},
+                                 s3r::InStride{}, s),
                 "pool kernel launch");
     }
     a.q = q; a.k = k; a.v = v; a.idx = nullptr; a.o_comp = nullptr; a.gate = nullptr; a.out = out;

@@ -169,6 +169,15 @@ def test_select_attn_mfma_bf16(s3r, oracle, block, n_tok, kk, with_gate):
     select_case(s3r, oracle, "bf16", n_tok, 3, block, kk, 0, with_gate, 1000 + n_tok)
 
 
+@pytest.mark.parametrize("block,n_tok,kk", [(64, 1024, 4), (64, 1000, 5), (128, 1100, 3), (64, 64, 1),
+                                            (128, 2000, 16), (64, 2500, 40)])
+@pytest.mark.parametrize("with_gate", [False, True])
+def test_select_attn_mfma_f32(s3r, oracle, block, n_tok, kk, with_gate):
+    """fp32 problems with blocks of 64 and 128 tokens run on the matrix cores with bf16 hi/lo operand pairs and
+    must stay within the fp32 tolerance."""
+    select_case(s3r, oracle, "f32", n_tok, 3, block, kk, 0, with_gate, 1000 + n_tok)
+
+
 @pytest.mark.parametrize("kk,rising", [(41, False), (64, False), (40, True), (97, False), (128, True)])
 def test_select_attn_long_rows_on_long_sequences(s3r, oracle, kk, rising):
     """Rows of 40 or more blocks on sequences of 3000 or more blocks of 64 tokens run with two pairs of waves
@@ -248,7 +257,7 @@ def test_select_attn_generic(s3r, oracle, dtype, block, n_tok, kk):
 # ------------------------------------------------------------------------------ stage: dense --
 
 @pytest.mark.parametrize("dtype,n_tok,choice", [("bf16", 1024, 0), ("bf16", 1000, 0), ("bf16", 300, 0),
-                                                ("bf16", 777, 1), ("f32", 1024, 0), ("f32", 500, 0)])
+                                                ("bf16", 777, 1), ("f32", 1024, 0), ("f32", 500, 0), ("f32", 777, 1)])
 def test_dense_attn(s3r, oracle, dtype, n_tok, choice):
     s3r.speed3r_set_kernel_choice(choice)
     try:
@@ -645,6 +654,7 @@ def test_forced_blocks_view_stride_sampled_rows(s3r, oracle):
 @pytest.mark.parametrize("dtype,block,n_tok,topk,forced", [
     ("f32", 16, 333, 4, [0, 1, 20]),                 # generic kernels, ragged tail, last block forced
     ("f32", 64, 1000, 3, [5]),
+    ("f32", 128, 1100, 2, [0, 8]),                   # fp32 on the matrix cores, two units per block, ragged tail
     ("bf16", 64, 1000, 5, [0, 3, 4, 15]),            # 16 blocks; last (ragged) one forced
     ("bf16", 64, 1000, 14, [1, 2]),                  # topk + forced = n_blk: every block attended
     ("bf16", 64, 1000, 64, [0, 7, 9]),               # topk > free blocks: k_dyn clamps to 13
@@ -717,6 +727,8 @@ def test_special_tokens_vggt_8_views(s3r, oracle):
 @pytest.mark.parametrize("dtype,block,views,tpv,special,topk", [
     ("f32", 16, 3, 111, 2, 3),           # generic kernels, blocks straddle views, ragged tail
     ("f32", 64, 2, 300, 7, 2),
+    ("f32", 64, 1, 1000, 100, 3),        # fp32 operand pairs: special rows over two key segments, two special units
+    ("f32", 128, 3, 700, 5, 2),
     ("bf16", 64, 4, 333, 5, 4),          # image sequence 1312 = 20.5 blocks; 20 special rows (< one unit)
     ("bf16", 64, 1, 1000, 100, 3),       # the paper's [spec; img] arrangement, 100 special rows (two units)
     ("bf16", 128, 3, 700, 5, 2),         # block 128: dense rows walk half-block units, odd unit count
@@ -783,6 +795,7 @@ def test_special_tokens_untouched_outputs_and_zero_special(s3r):
     ("bf16", 2, 5, 37, 37, 8, 5, [0, 4, 24]),  # forced windows incl. the corner one of view 0
     ("f32", 2, 2, 9, 10, 4, 3, None),          # 4 x 4 windows (block 16): generic kernels
     ("f32", 3, 0, 8, 8, 4, 2, [1]),
+    ("f32", 2, 5, 37, 37, 8, 5, [0, 4, 24]),   # fp32 on the matrix cores: cut windows, special rows, forced windows
     ("bf16", 2, 3, 11, 13, 4, 4, None),        # block 16 in bf16: generic kernels
     ("bf16", 1, 0, 5, 5, 8, 1, None),          # a single cut window
 ])
