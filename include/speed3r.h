@@ -266,8 +266,8 @@ s3r_status speed3r_set_profiling(int enable);
  * switched on); the record is cleared.  Waits for the recorded events, so call it after the work. */
 s3r_status speed3r_get_stage_ms(float *ms, int *launches);
 
-/* Selects kernel families, process-wide.  0 = automatic: MFMA attention kernels for bf16 and, with blocks
- * of 64 and 128 tokens, for fp32 (bf16 operand parts; the generic kernel for fp32 otherwise), and for up to 64 TopK blocks per row the TopK that runs
+/* Selects kernel families, process-wide.  0 = automatic: MFMA attention kernels (fp32 problems in bf16
+ * operand parts), and for up to 64 TopK blocks per row the TopK that runs
  * inside the compression sweep without writing S_guide to memory (supplementary Sec. 1).  1 = always
  * the generic attention kernel.  2 = like 0 but TopK always from S_guide written to memory. */
 s3r_status speed3r_set_kernel_choice(int choice);

@@ -198,7 +198,6 @@ hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, f
     if (n_blk * heads > 0x7fffffffLL) return hipErrorInvalidValue;
     if (map.period != 0 && n_tok > 0x7fffffffLL) return hipErrorInvalidValue;
     const bool repack = kb != nullptr;
-    if (repack && !is_bf16 && block < 64) return hipErrorInvalidValue;  // operand pairs: blocks of 64 and 128 tokens
 #define S3R_POOL_CASE(TT, BB, RR) \
     return run_pool<TT, BB, RR>(q, k, v, qc, kc, vc, kb, vb, n_tok, heads, n_blk, map, in, stream)
     if (is_bf16) {
@@ -210,8 +209,8 @@ hipError_t launch_pool(const void *q, const void *k, const void *v, float *qc, f
         }
     } else {
         switch (block) {
-        case 16: S3R_POOL_CASE(float, 16, false);
-        case 32: S3R_POOL_CASE(float, 32, false);
+        case 16: if (repack) S3R_POOL_CASE(float, 16, true); else S3R_POOL_CASE(float, 16, false);
+        case 32: if (repack) S3R_POOL_CASE(float, 32, true); else S3R_POOL_CASE(float, 32, false);
         case 64: if (repack) S3R_POOL_CASE(float, 64, true); else S3R_POOL_CASE(float, 64, false);
         case 128: if (repack) S3R_POOL_CASE(float, 128, true); else S3R_POOL_CASE(float, 128, false);
         }

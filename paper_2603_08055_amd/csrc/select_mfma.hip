@@ -78,7 +78,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
     constexpr int D = NS - 1;          // units in flight
     static_assert(NCH % NW == 0 && 16 % NW == 0, "waves must split the chunks of a unit evenly");
     static_assert(CPW * D < 64, "vmcnt budget");
-    static_assert(!F32 || (!SMALL && !PAIR && !PROBE), "operand pairs: blocks of 64 and 128 tokens, plain and dense kernels");
+    static_assert(!F32 || (!PAIR && !PROBE), "operand parts: the plain and the dense kernels");
     // [stage][K 8 KiB | V 8 KiB] (F32: then [K lo 8 KiB | V lo 8 KiB | K lo2 8 KiB])
     constexpr int kStageParts = F32 ? 5 : 2;
     __shared__ __attribute__((aligned(1024))) bf16_t ring[NS][kStageParts * kUnitElems];
@@ -275,7 +275,8 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
                 const int base = c * QW;                 // compile time
                 const int chunk = base + wave;           // base .. base + QW - 1, all in the same mt
                 const int mt = (base & 7) >> 2;          // compile time
-                const bool is_k = base < 8;              // compile time
+                const bool is_k = (base & 15) < 8;       // compile time (F32: 16 chunks per operand part, K only in the third)
+                const int64_t part = F32 ? (base >> 4) * (small ? lo_off : lo_off2) : 0;
                 const bf16_t *src;
                 if (small) {
                     const int lo = mt == 0 ? b.b0 : (bpu_shift == 2 ? b.b2 : b.b1);   // first block of tile half mt
@@ -297,7 +298,7 @@ __global__ __launch_bounds__(QW * 64, 2) void select_mfma_kernel(
                     const int64_t w2 = s - n_units1;
                     src = (is_k ? kb2_h : vb2_h) + w2 * kUnitElems + (chunk & 7) * 512 + lane * 8;
                 }
-                lds_dma_16(src, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
+                lds_dma_16(src + part, __builtin_amdgcn_readfirstlane(stage_byte + chunk * 1024));
             }
             return;
         }
@@ -682,16 +683,20 @@ hipError_t launch_select_mfma(const SelectArgs &a, hipStream_t stream)
 {
     if (a.kb == nullptr || a.vb == nullptr) return hipErrorInvalidValue;
     if (!a.is_bf16) {
-        // fp32 problems: K/V tiles as bf16 hi/lo operand pairs, blocks of 64 and 128 tokens
-        if (a.lo_off <= 0 || a.loads_only || (a.block != 64 && a.block != 128)) return hipErrorInvalidValue;
+        // fp32 problems: K/V tiles in bf16 operand parts
+        if (a.lo_off <= 0 || a.loads_only) return hipErrorInvalidValue;
+        const bool small = a.block == 16 || a.block == 32;
+        if (!small && a.block != 64 && a.block != 128) return hipErrorInvalidValue;
         if (a.qmap.period != 0 && a.n_tok > 0x7fffffffLL) return hipErrorInvalidValue;
         if (a.idx == nullptr) {
             if (a.n_keys2 > 0 && (a.kb2 == nullptr || a.vb2 == nullptr || a.lo_off2 <= 0)) return hipErrorInvalidValue;
-            return run_select<4, true, 3, false, true, false, true>(a, stream);
+            return small ? run_select<4, true, 3, true, true, false, true>(a, stream)
+                         : run_select<4, true, 3, false, true, false, true>(a, stream);
         }
         if (a.n_keys != a.n_tok || a.n_keys2 != 0) return hipErrorInvalidValue;
-        return a.block == 64 ? run_select<2, false, 2, false, false, false, true>(a, stream)
-                             : run_select<4, false, 2, false, false, false, true>(a, stream);
+        return small          ? run_select<1, false, 2, true, false, false, true>(a, stream)
+               : a.block == 64 ? run_select<2, false, 2, false, false, false, true>(a, stream)
+                               : run_select<4, false, 2, false, false, false, true>(a, stream);
     }
     // One query block per workgroup, two LDS stages: measured best on MI355X.  A third stage is slower even
     // where it costs no occupancy (blocks of 128 tokens: 18.2 against 16.8 ms on 300 views, top-64): the fabric

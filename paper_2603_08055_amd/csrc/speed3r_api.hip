@@ -48,8 +48,8 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int g_kernel_choice = 0;  // 0 auto, 1 generic attention kernels only, 2 TopK from scores written to memory
 
-// bf16: every supported block size; fp32: blocks of 64 and 128 tokens (K/V as bf16 hi/lo operand pairs)
-bool mfma_ok(s3r_dtype dtype, int block) { return g_kernel_choice != 1 && (dtype == S3R_BF16 || block >= 64); }
+// every supported block size, bf16 and fp32 (the latter with K/V in bf16 operand parts)
+bool mfma_ok(s3r_dtype dtype, int block) { (void)dtype; (void)block; return g_kernel_choice != 1; }
 // copies of a K (or V) tile array the MFMA kernels read: fp32 problems keep bf16 parts hi, lo and (K) lo2
 size_t tile_parts(s3r_dtype dtype) { return dtype == S3R_BF16 ? 1 : 3; }
 

@@ -170,11 +170,12 @@ def test_select_attn_mfma_bf16(s3r, oracle, block, n_tok, kk, with_gate):
 
 
 @pytest.mark.parametrize("block,n_tok,kk", [(64, 1024, 4), (64, 1000, 5), (128, 1100, 3), (64, 64, 1),
-                                            (128, 2000, 16), (64, 2500, 40)])
+                                            (128, 2000, 16), (64, 2500, 40),
+                                            (16, 1000, 7), (16, 37, 3), (32, 333, 4), (32, 1024, 6)])
 @pytest.mark.parametrize("with_gate", [False, True])
 def test_select_attn_mfma_f32(s3r, oracle, block, n_tok, kk, with_gate):
-    """fp32 problems with blocks of 64 and 128 tokens run on the matrix cores with bf16 hi/lo operand pairs and
-    must stay within the fp32 tolerance."""
+    """fp32 problems run on the matrix cores with K, V, Q and P in bf16 operand parts and must stay within the
+    fp32 tolerance."""
     select_case(s3r, oracle, "f32", n_tok, 3, block, kk, 0, with_gate, 1000 + n_tok)
 
 
@@ -224,7 +225,7 @@ def test_select_attn_long_rows_on_long_sequences(s3r, oracle, kk, rising):
     assert float(np.max(np.abs(lse.index_select(1, take).cpu().numpy().T - lse_v))) <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("dtype,block", [("bf16", 64), ("bf16", 128), ("bf16", 16), ("bf16", 32), ("f32", 64)])
+@pytest.mark.parametrize("dtype,block", [("bf16", 64), ("bf16", 128), ("bf16", 16), ("bf16", 32), ("f32", 64), ("f32", 16)])
 def test_select_attn_holds_out_of_range_indices_in_range(s3r, dtype, block):
     """A caller's index tensor is device memory the library cannot inspect: entries outside [0, n_blk) are held
     into the range by the kernels (the documented behaviour), so the result equals that of the clamped list."""
@@ -257,7 +258,7 @@ def test_select_attn_generic(s3r, oracle, dtype, block, n_tok, kk):
 # ------------------------------------------------------------------------------ stage: dense --
 
 @pytest.mark.parametrize("dtype,n_tok,choice", [("bf16", 1024, 0), ("bf16", 1000, 0), ("bf16", 300, 0),
-                                                ("bf16", 777, 1), ("f32", 1024, 0), ("f32", 500, 0), ("f32", 777, 1)])
+                                                ("bf16", 777, 1), ("f32", 1024, 0), ("f32", 500, 0), ("f32", 777, 1)])   # (dense attention has no block size: 64-key units)
 def test_dense_attn(s3r, oracle, dtype, n_tok, choice):
     s3r.speed3r_set_kernel_choice(choice)
     try:
