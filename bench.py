@@ -299,19 +299,43 @@ def main():
     # one roofline fraction per stage: algorithmic bytes (HBM-bound stages) or executed matrix FLOPs over the stage's time
     def stage_s(name):
         return stage_ms[name] / args.steps * 1e-3
-    tiles_bytes = (2.0 * seq.n_blk * wl.block * wl.heads * wl.head_dim * 2) if wl.dtype == "bf16" else 0.0
+    # K and V tiles in operand order: one bf16 copy each (fp32 problems: K in three bf16 parts, V in two)
+    tiles_bytes = (2.0 if wl.dtype == "bf16" else 5.0) * seq.n_blk * wl.block * wl.heads * wl.head_dim * 2
+
+    def device_copy_gbps(moved):
+        """What a plain device-to-device copy (torch's copy kernel) moving the same number of bytes, half read and
+        half written, sustains on this GPU: the practical reference beside the 8 TB/s of the data sheet."""
+        n = int(moved // 2) // 16 * 16
+        src = torch.empty(n, dtype=torch.uint8, device="cuda")
+        src.zero_()
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        return 2.0 * n / (e0.elapsed_time(e1) / 5 * 1e-3) / 1e9
     sweep_flops = 2.0 * wl.head_dim * float(seq.n_blk) * float(seq.n_blk) * wl.heads     # one N_b x N_b x d product
     in_sweep = kk - n_forced <= 64
     stages = {
         "pool": {"bound": "hbm", "unit": "GB/s", "peak": 8000.0, "achieved": pool_bytes / stage_s("pool") / 1e9,
                  "frac": pool_bytes / stage_s("pool") / 1e9 / 8000.0, "algorithmic_bytes": pool_bytes,
                  "moved_bytes": pool_bytes + tiles_bytes,
+                 "moved_GBps": (pool_bytes + tiles_bytes) / stage_s("pool") / 1e9,
                  "note": "moved = algorithmic + the K/V operand-order tiles this design writes for the selection kernel"},
         "compress": {"bound": "mfma", "unit": "TFLOP/s", "peak": MFMA_BF16_PEAK_TFLOPS,
                      "achieved": 2.0 * sweep_flops / stage_s("compress") / 1e12,
                      "frac": 2.0 * sweep_flops / stage_s("compress") / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                      "flops": 2.0 * sweep_flops, "note": "Qc Kc^T and P Vc, 4 d N_b^2 H FLOP (eqs. 3-4), counted once each"},
     }
+    if not args.no_probe:
+        copy_gbps = device_copy_gbps(pool_bytes + tiles_bytes)
+        stages["pool"]["device_copy_GBps"] = copy_gbps
+        stages["pool"]["moved_over_device_copy"] = stages["pool"]["moved_GBps"] / copy_gbps
+        say(f"pool stage moves {stages['pool']['moved_GBps']:.0f} GB/s; a plain device copy of as many bytes {copy_gbps:.0f} GB/s")
     if in_sweep:
         stages["topk"] = {"bound": "mfma", "unit": "TFLOP/s", "peak": MFMA_BF16_PEAK_TFLOPS,
                           "achieved": sweep_flops / stage_s("topk") / 1e12,
