@@ -59,7 +59,8 @@ def measured_traffic(wl):
     this run: only quoted for exactly the workload it was measured on (config 4 as BASELINE states it)."""
     path = os.path.join(ROOT, TRAFFIC_FILE)
     ref = CONFIG4
-    if (wl.name, wl.views, wl.block, wl.topk) != (ref.name, ref.views, ref.block, ref.topk) or not os.path.exists(path):
+    if ((wl.name, wl.views, wl.block, wl.topk, wl.dtype) != (ref.name, ref.views, ref.block, ref.topk, ref.dtype)
+            or not os.path.exists(path)):
         return None
     for line in open(path):
         if line.startswith("traffic_bytes_per_launch_select_kernel:"):
@@ -135,6 +136,11 @@ def main():
     ap.add_argument("--views", type=int, default=None, help="override the number of views")
     ap.add_argument("--topk", type=int, default=None)
     ap.add_argument("--block", type=int, default=None, help="override the pooling block (16, 32, 64, 128)")
+    ap.add_argument("--dtype", choices=("bf16", "f32"), default=None,
+                    help="override the I/O type of the workload (f32: the matrix-core kernels on bf16 operand parts)")
+    ap.add_argument("--kernel-choice", type=int, default=0, choices=(0, 1, 2),
+                    help="speed3r_set_kernel_choice: 0 automatic, 1 the generic one-thread-per-row attention kernel, "
+                         "2 TopK always from stored scores; not the headline metric unless 0")
     ap.add_argument("--special", type=int, default=0,
                     help="treat the first N tokens of every view as special tokens (dense rows); not the headline metric")
     ap.add_argument("--forced-vggt", action="store_true",
@@ -166,6 +172,9 @@ def main():
         over["topk"] = args.topk
     if args.block is not None:
         over["block"] = args.block
+    if args.dtype is not None:
+        over["dtype"] = args.dtype
+    s3r.speed3r_set_kernel_choice(args.kernel_choice)
     global CONFIG4
     CONFIG4 = workloads.config(4)
     wl = workloads.config(args.config, **over)
@@ -230,8 +239,11 @@ def main():
     sel_flops = 4.0 * wl.head_dim * pairs
     sel_ms = stage_ms["select"] / max(stage_n["select"], 1)
     achieved = sel_flops / (sel_ms * 1e-3) / 1e12
-    traffic = None if (args.special or n_forced or args.compress_queries) else measured_traffic(wl)
-    roofline = {"kernel": "select_mfma_kernel" if wl.dtype == "bf16" else "select_generic_kernel",
+    traffic = None if (args.special or n_forced or args.compress_queries or args.kernel_choice) else measured_traffic(wl)
+    pipe = (args.kernel_choice != 1 and wl.dtype == "bf16" and wl.block == 64 and kk <= 128 and not args.special
+            and not args.compress_queries and not (kk > 96 and 2 * n_forced >= kk))
+    roofline = {"kernel": ("select_generic_kernel" if args.kernel_choice == 1 else
+                           "select_pipe_kernel" if pipe else "select_mfma_kernel"),
                 "bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": traffic,
@@ -301,6 +313,8 @@ def main():
         return stage_ms[name] / args.steps * 1e-3
     # K and V tiles in operand order: one bf16 copy each (fp32 problems: K in three bf16 parts, V in two)
     tiles_bytes = (2.0 if wl.dtype == "bf16" else 5.0) * seq.n_blk * wl.block * wl.heads * wl.head_dim * 2
+    if args.kernel_choice == 1:
+        tiles_bytes = 0.0   # the generic kernel reads K and V in place
 
     def device_copy_gbps(moved):
         """What a plain device-to-device copy (torch's copy kernel) moving the same number of bytes, half read and
@@ -363,7 +377,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "views": wl.views, "tokens_per_view": wl.tokens_per_view,
                    "n_tok": wl.n_tok, "heads": wl.heads, "head_dim": wl.head_dim, "block": wl.block,
-                   "topk": wl.topk, "kind": wl.kind, "seed": wl.seed,
+                   "topk": wl.topk, "kind": wl.kind, "seed": wl.seed, "kernel_choice": args.kernel_choice,
                    "generator": "torch.Generator(device='cuda'), one view at a time (the tests' small cases draw on the CPU generator)"},
         "roofline": roofline,
         "stages": stages,
