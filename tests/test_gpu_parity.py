@@ -333,6 +333,19 @@ def test_config2_vggt_8_views(s3r, oracle):
     end_to_end(s3r, oracle, workloads.config(2), with_gate=True)
 
 
+@pytest.mark.parametrize("dtype,block,prescale", [
+    ("bf16", 64, 16.0), ("bf16", 64, 1e-3), ("bf16", 128, 16.0), ("bf16", 16, 16.0),
+    ("f32", 64, 16.0), ("f32", 64, 1e-3), ("f32", 32, 16.0),
+])
+def test_peaked_and_flat_softmax(s3r, oracle, dtype, block, prescale):
+    """Queries 16 times larger (logits of standard deviation 16: nearly all the weight on one or two keys, exponents
+    far below the running maximum everywhere else, maxima that rise by tens from unit to unit) and a thousand
+    times smaller (all keys weigh the same)."""
+    wl = workloads.Workload(f"prescale_{dtype}_{block}_{prescale}", 3, 700, 2, 64, dtype, block, 5, 77, "normal",
+                            q_prescale=prescale)
+    end_to_end(s3r, oracle, wl, with_gate=True)
+
+
 def test_config2_generic_kernels(s3r, oracle):
     s3r.speed3r_set_kernel_choice(1)
     try:
