@@ -346,6 +346,33 @@ def test_peaked_and_flat_softmax(s3r, oracle, dtype, block, prescale):
     end_to_end(s3r, oracle, wl, with_gate=True)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("block", [16, 64, 128])
+@pytest.mark.parametrize("case", ["q_zero", "k_zero", "v_zero", "all_ones", "one_hot_rows"])
+def test_degenerate_inputs(s3r, oracle, dtype, block, case):
+    """Inputs on which every score ties (zero queries or keys, constant tensors), on which the result is zero, and
+    on which each row has a single non-zero channel: the index sets are then any valid ones under the near-tie
+    rule, and the outputs are compared on the device's sets."""
+    n_tok, heads = 5 * block + 7, 2
+    q, k, v = (draw(n_tok, heads, dtype, 4400 + i) for i in range(3))
+    if case == "q_zero":
+        q = torch.zeros_like(q)
+    elif case == "k_zero":
+        k = torch.zeros_like(k)
+    elif case == "v_zero":
+        v = torch.zeros_like(v)
+    elif case == "all_ones":
+        q, k, v = torch.ones_like(q), torch.ones_like(k), torch.ones_like(v)
+    else:
+        hot = torch.arange(n_tok)[:, None] % 64
+        mask = (torch.arange(64)[None, None, :] == hot[:, :, None]).to(q.dtype)
+        q, k = q * mask, k * mask
+    res = run_device(s3r, q.cuda(), k.cuda(), v.cuda(), block, 3)
+    assert torch.isfinite(res["out"].float()).all()
+    compare_with_oracle(oracle, res, to_host_f32(q), to_host_f32(k), to_host_f32(v), None, block, 3, dtype,
+                        label=f"{case} {dtype} B={block}")
+
+
 def test_config2_generic_kernels(s3r, oracle):
     s3r.speed3r_set_kernel_choice(1)
     try:
