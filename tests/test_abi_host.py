@@ -52,6 +52,36 @@ def test_params_struct_matches_header(s3r):
     assert fields == [f[0] for f in s3r.s3r_params._fields_]
 
 
+def test_header_is_plain_c_and_its_layout_is_the_bindings(s3r, tmp_path):
+    """include/speed3r.h compiles as C99 with gcc, a C program linked against the library calls it with no
+    Python in between, and the size and field offsets of s3r_params it sees are those of the ctypes mirror."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    fields = [f[0] for f in s3r.s3r_params._fields_]
+    prog = ['#include <stddef.h>', '#include <stdio.h>', '#include "speed3r.h"', 'int main(void) {',
+            '  printf("sizeof %zu\\n", sizeof(s3r_params));']
+    prog += [f'  printf("{f} %zu\\n", offsetof(s3r_params, {f}));' for f in fields]
+    prog += ['  printf("ws %zu\\n", speed3r_workspace_bytes(1024, 2, 64, 64, 4, 0, S3R_BF16));',
+             '  printf("bad %zu\\n", speed3r_workspace_bytes(1024, 2, 48, 64, 4, 0, S3R_BF16));',
+             '  printf("err %s\\n", speed3r_last_error());', '  return 0; }']
+    src = tmp_path / "abi.c"
+    src.write_text("\n".join(prog).replace("\\\\n", "\\n"))
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(s3r.LIB_PATH)
+    cmd = ["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+           "-L", libdir, "-lspeed3r", f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines()
+    got = dict(line.split(" ", 1) for line in out)
+    assert int(got["sizeof"]) == ctypes.sizeof(s3r.s3r_params)
+    for f in fields:
+        assert int(got[f]) == getattr(s3r.s3r_params, f).offset, f
+    assert int(got["ws"]) == s3r.speed3r_workspace_bytes(1024, 2, 64, 64, 4, s3r.S3R_BF16) > 0
+    assert int(got["bad"]) == 0 and "head_dim" in got["err"]
+
+
 def test_workspace_bytes_and_shape_validation(s3r):
     lib = s3r.load()
     assert s3r.speed3r_workspace_bytes(1024, 2, 64, 64, 4, s3r.S3R_F32) > 0
